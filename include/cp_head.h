@@ -1,0 +1,148 @@
+/*
+ * cp_head.h - C ABI of the MI355X (gfx950) CP multi-token-prediction head.
+ *
+ * The head models the joint distribution of the next n tokens after a position
+ * as a rank-r canonical (CP) mixture (paper eq. 2):
+ *
+ *     P(x_1..x_n | h) = sum_a  w_a  prod_s  P^(s)(x_s | a)
+ *     w               = softmax(G h)                               (eq. 7)
+ *     P^(s)(. | a)    = softmax(U (W_sa h))                        (eq. 6, with the
+ *                        shared-unembedding head of section "Fine tuning")
+ *
+ * Tensors (all dense, row-major, DEVICE pointers owned by the caller):
+ *     H[T,d]       hidden states, one row per position
+ *     W[n,r,d,d]   W[s,a] is d x d, y = W[s,a] h  (row = output feature)
+ *     U[V,d]       shared unembedding
+ *     G[r,d]       gate
+ *     X[T,n]       int32 targets, X[t,s] = token s+1 steps after position t;
+ *                  a negative entry drops that factor (no loss term, no gradient);
+ *                  entries >= V are undefined behaviour
+ * H, W, U, G have the storage type named by cp_head_desc.dtype; all arithmetic
+ * accumulates in fp32.
+ *
+ * General rules for every entry point:
+ *   - the library allocates no memory and keeps no state between calls: the
+ *     caller supplies `ctx` (values saved by the forward pass for the backward
+ *     pass) and `workspace` (scratch, contents undefined afterwards), sized by
+ *     the two query functions; both must be 256-byte aligned;
+ *   - every call only enqueues work on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and never synchronises;
+ *   - the return value is CP_HEAD_OK or a negative error code; on error nothing
+ *     was enqueued, except CP_HEAD_ERR_LAUNCH which reports a failed launch;
+ *   - results are deterministic: no floating-point atomics are used.
+ *
+ * Limits: 1 <= r <= 64, 1 <= n <= 64, d >= 1, V >= 1, T >= 0, T*n*r*max(d,V) < 2^62.
+ * The matrix-core path is taken for dtype = bf16 with d a multiple of 64; other
+ * shapes and fp32 storage run on a plain fp32 path (correct for any shape, slow).
+ */
+#ifndef CP_HEAD_H
+#define CP_HEAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CP_HEAD_FP32 = 0,   /* H, W, U, G are float */
+    CP_HEAD_BF16 = 1    /* H, W, U, G are bfloat16 (raw 16-bit patterns) */
+};
+
+enum {
+    CP_HEAD_FORCE_GENERIC = 1   /* flags bit 0: use the plain fp32 path even where the
+                                   matrix-core path applies (a second opinion in tests) */
+};
+
+enum {
+    CP_HEAD_OK = 0,
+    CP_HEAD_ERR_INVALID_ARG = -1,     /* null pointer, bad dimension, misaligned buffer */
+    CP_HEAD_ERR_UNSUPPORTED = -2,     /* shape or dtype outside the stated limits */
+    CP_HEAD_ERR_WORKSPACE = -3,       /* workspace_bytes smaller than the query reports */
+    CP_HEAD_ERR_LAUNCH = -4           /* a kernel launch failed (hipGetLastError) */
+};
+
+enum { CP_HEAD_OP_LOSS_FWD = 0, CP_HEAD_OP_LOSS_BWD = 1, CP_HEAD_OP_DRAFT = 2 };
+
+typedef struct cp_head_desc {
+    int64_t T;        /* positions (loss calls) or batch size B (draft call) */
+    int32_t d;        /* hidden size */
+    int32_t V;        /* vocabulary size */
+    int32_t n;        /* future tokens per position */
+    int32_t r;        /* CP rank = number of experts */
+    int32_t dtype;    /* CP_HEAD_FP32 or CP_HEAD_BF16 */
+    int32_t flags;    /* CP_HEAD_FORCE_GENERIC or 0 */
+} cp_head_desc;
+
+/* Human-readable text for an error code (static storage). */
+const char *cp_head_strerror(int code);
+
+/*
+ * Bytes of `ctx` that cp_head_loss_fwd fills and cp_head_loss_bwd reads: the
+ * log-normaliser of every factor (eq. 5), the gate weights (eq. 7), the
+ * posterior over experts, and the projected states y = W_sa h.  Host-only.
+ */
+int cp_head_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
+
+/*
+ * Bytes of scratch `workspace` that operation `op` (CP_HEAD_OP_*) needs for
+ * this shape.  Host-only.  The size is bounded in the number of positions for
+ * the logit-sized buffers: logits and their gradients are only ever held for a
+ * bounded chunk of rows, never for all T*n*r rows.
+ */
+int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes);
+
+/*
+ * Training loss, forward (section "Training procedure", eq. 8 and eq. 9):
+ *     C_sa    = z_sa[X[t,s]] - logsumexp_v z_sa[v],   z_sa = U (W_sa h_t)
+ *     loss[t] = -logsumexp_a( log w_a + sum_s C_sa )          (nats, no reduction)
+ * loss[T] is fp32, overwritten.  ctx receives what the backward pass needs.
+ */
+int cp_head_loss_fwd(const cp_head_desc *desc,
+                     const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X,
+                     float *loss,
+                     void *ctx, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Training loss, backward: gradients of  sum_t dloss[t] * loss[t]  (the
+ * derivative of eq. 9 through eq. 8, 6 and 7).  `ctx` must come from
+ * cp_head_loss_fwd on the same desc and inputs.  dloss[T] is fp32; NULL means
+ * dloss[t] = scale for all t (otherwise `scale` multiplies dloss).
+ * Outputs are fp32 and OVERWRITTEN: dH[T,d], dW[n,r,d,d], dU[V,d], dG[r,d].
+ * dU may be NULL (frozen unembedding: that product is skipped); dW and dG may
+ * be NULL too; dH is required.
+ */
+int cp_head_loss_bwd(const cp_head_desc *desc,
+                     const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X,
+                     const float *dloss, float scale,
+                     const void *ctx,
+                     float *dH, float *dW, float *dU, float *dG,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Draft step for self-speculative decoding (section "Sampling method"): for
+ * each of the B = desc->T rows of H draw an expert a* ~ w and then, for every
+ * s, a token from P^(s)(. | a*).  The pair of draws has exactly the joint of
+ * eq. 2, i.e. the distribution the paper's sequential scheme (eq. 11-13)
+ * samples from.  The library holds no random-number generator:
+ *     uniforms[B,1+n]  fp32 in [0,1): column 0 draws the expert, column 1+s token s.
+ * Inverse-CDF convention: index order, the first index whose running sum
+ * exceeds u, clamped to the last index.  With bf16 storage y = W_sa h is
+ * rounded to bf16 (nearest-even) before z = U y: that rounding is part of the
+ * sampled distribution's definition.
+ * Outputs: alpha[B] int32, tokens[B,n] int32, logq[B] fp32 (may be NULL) =
+ * log of eq. 2 at the drawn tuple, summed over all experts.
+ */
+int cp_head_draft_sample(const cp_head_desc *desc,
+                         const void *H, const void *W, const void *U, const void *G,
+                         const float *uniforms,
+                         int32_t *alpha, int32_t *tokens, float *logq,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CP_HEAD_H */

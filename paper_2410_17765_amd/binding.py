@@ -1,0 +1,127 @@
+"""Thin ctypes binding of libcphead.so: argument marshalling only.
+
+Function names mirror the C ABI (``include/cp_head.h``).  Device buffers are
+torch tensors (PyTorch supplies device memory and streams, nothing else);
+every step of the computation runs in the library's own kernels.  There is no
+fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+FP32 = 0
+BF16 = 1
+FORCE_GENERIC = 1
+OP_LOSS_FWD, OP_LOSS_BWD, OP_DRAFT = 0, 1, 2
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcphead.so")
+_lib: Optional[ctypes.CDLL] = None
+
+EXPORTS = ("cp_head_strerror", "cp_head_ctx_bytes", "cp_head_workspace_bytes",
+           "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample")
+
+
+class CpHeadError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("d", ctypes.c_int32), ("V", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("r", ctypes.c_int32), ("dtype", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcphead.so (built by ``paper_2410_17765_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2410_17765_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.cp_head_strerror.restype = ctypes.c_char_p
+        L.cp_head_strerror.argtypes = [ctypes.c_int]
+        L.cp_head_ctx_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(sz)]
+        L.cp_head_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.c_int, ctypes.POINTER(sz)]
+        L.cp_head_loss_fwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_loss_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, ctypes.c_float, vp,
+                                       vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_draft_sample.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        for name in EXPORTS[1:]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().cp_head_strerror(int(code)).decode()
+
+
+def make_desc(T: int, d: int, V: int, n: int, r: int, dtype: int, flags: int = 0) -> Desc:
+    return Desc(T, d, V, n, r, dtype, flags)
+
+
+def cp_head_ctx_bytes(desc: Desc) -> int:
+    out = ctypes.c_size_t(0)
+    rc = lib().cp_head_ctx_bytes(ctypes.byref(desc), ctypes.byref(out))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_ctx_bytes")
+    return out.value
+
+
+def cp_head_workspace_bytes(desc: Desc, op: int) -> int:
+    out = ctypes.c_size_t(0)
+    rc = lib().cp_head_workspace_bytes(ctypes.byref(desc), int(op), ctypes.byref(out))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_workspace_bytes")
+    return out.value
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or raw integer) pointer of a tensor; None passes NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "tensors must be contiguous"
+    return t.data_ptr()
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return int(stream)
+
+
+def cp_head_loss_fwd(desc: Desc, H, W, U, G, X, loss, ctx, workspace, stream=None) -> None:
+    rc = lib().cp_head_loss_fwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(X), _ptr(loss),
+                                _ptr(ctx), _ptr(workspace), _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_loss_fwd")
+
+
+def cp_head_loss_bwd(desc: Desc, H, W, U, G, X, dloss, scale: float, ctx, dH, dW, dU, dG, workspace,
+                     stream=None) -> None:
+    rc = lib().cp_head_loss_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(X), _ptr(dloss),
+                                float(scale), _ptr(ctx), _ptr(dH), _ptr(dW), _ptr(dU), _ptr(dG),
+                                _ptr(workspace), _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_loss_bwd")
+
+
+def cp_head_draft_sample(desc: Desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, stream=None) -> None:
+    rc = lib().cp_head_draft_sample(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(uniforms),
+                                    _ptr(alpha), _ptr(tokens), _ptr(logq), _ptr(workspace), _nbytes(workspace),
+                                    _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_draft_sample")

@@ -1,0 +1,117 @@
+// C ABI of libcphead.so: argument checks, path selection, dispatch.
+#include "cp_internal.hpp"
+
+using namespace cph;
+
+namespace {
+
+constexpr int kMaxRank = 64;
+constexpr int kMaxHeads = 64;
+constexpr int kMaxGenericD = 16000;   // the plain path keeps one fp32 row of length d in LDS
+
+int check_desc(const cp_head_desc *ds)
+{
+    if (!ds) return CP_HEAD_ERR_INVALID_ARG;
+    if (ds->T < 0 || ds->d < 1 || ds->V < 1 || ds->n < 1 || ds->r < 1) return CP_HEAD_ERR_INVALID_ARG;
+    if (ds->dtype != CP_HEAD_FP32 && ds->dtype != CP_HEAD_BF16) return CP_HEAD_ERR_UNSUPPORTED;
+    if (ds->r > kMaxRank || ds->n > kMaxHeads) return CP_HEAD_ERR_UNSUPPORTED;
+    const double rows = (double)ds->T * ds->n * ds->r;
+    if (rows * (double)(ds->d > ds->V ? ds->d : ds->V) >= 4.6e18) return CP_HEAD_ERR_UNSUPPORTED;
+    if (rows >= 2147483647.0) return CP_HEAD_ERR_UNSUPPORTED;   // one thread block per head row
+    if (!use_fast_path(*ds) && ds->d > kMaxGenericD) return CP_HEAD_ERR_UNSUPPORTED;
+    return CP_HEAD_OK;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *cp_head_strerror(int code)
+{
+    switch (code) {
+    case CP_HEAD_OK: return "ok";
+    case CP_HEAD_ERR_INVALID_ARG: return "invalid argument (null pointer, bad dimension or misaligned buffer)";
+    case CP_HEAD_ERR_UNSUPPORTED: return "unsupported shape or storage type";
+    case CP_HEAD_ERR_WORKSPACE: return "workspace too small";
+    case CP_HEAD_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown error code";
+    }
+}
+
+int cp_head_ctx_bytes(const cp_head_desc *desc, size_t *bytes)
+{
+    if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
+    const int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    *bytes = ctx_layout(*desc, use_fast_path(*desc)).total;
+    return CP_HEAD_OK;
+}
+
+int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes)
+{
+    if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
+    const int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (op != CP_HEAD_OP_LOSS_FWD && op != CP_HEAD_OP_LOSS_BWD && op != CP_HEAD_OP_DRAFT)
+        return CP_HEAD_ERR_INVALID_ARG;
+    *bytes = use_fast_path(*desc) ? fast_workspace_bytes(*desc, op) : generic_workspace_bytes(*desc, op);
+    return CP_HEAD_OK;
+}
+
+int cp_head_loss_fwd(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, float *loss, void *ctx, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !X || !loss)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    const bool fast = use_fast_path(*desc);
+    const size_t need = fast ? fast_workspace_bytes(*desc, CP_HEAD_OP_LOSS_FWD)
+                             : generic_workspace_bytes(*desc, CP_HEAD_OP_LOSS_FWD);
+    if (workspace_bytes < need) return CP_HEAD_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (fast) return fast_loss_fwd(*desc, H, W, U, G, X, loss, ctx, workspace, workspace_bytes, st);
+    return generic_loss_fwd(*desc, H, W, U, G, X, loss, ctx, workspace, st);
+}
+
+int cp_head_loss_bwd(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, const float *dloss, float scale, const void *ctx, float *dH, float *dW,
+                     float *dU, float *dG, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !X || !dH)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    const bool fast = use_fast_path(*desc);
+    const size_t need = fast ? fast_workspace_bytes(*desc, CP_HEAD_OP_LOSS_BWD)
+                             : generic_workspace_bytes(*desc, CP_HEAD_OP_LOSS_BWD);
+    if (workspace_bytes < need) return CP_HEAD_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (fast)
+        return fast_loss_bwd(*desc, H, W, U, G, X, dloss, scale, ctx, dH, dW, dU, dG, workspace, workspace_bytes, st);
+    return generic_loss_bwd(*desc, H, W, U, G, X, dloss, scale, ctx, dH, dW, dU, dG, workspace, st);
+}
+
+int cp_head_draft_sample(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                         const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !uniforms || !alpha || !tokens)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    const bool fast = use_fast_path(*desc);
+    const size_t need = fast ? fast_workspace_bytes(*desc, CP_HEAD_OP_DRAFT)
+                             : generic_workspace_bytes(*desc, CP_HEAD_OP_DRAFT);
+    if (workspace_bytes < need) return CP_HEAD_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (fast) return fast_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, workspace_bytes, st);
+    return generic_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Internal declarations shared by the translation units of libcphead.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "cp_head.h"
+
+namespace cph {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bit pattern
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16, round to nearest even (finite inputs)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float ld_f32(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ld_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// ---------------------------------------------------------------- host-side layout
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Saved-for-backward buffer: [lse M f32][w T*r f32][gamma T*r f32][Y M*d].
+struct CtxLayout {
+    size_t lse, w, gamma, Y, total;
+};
+// Y is fp32 on the generic path and bf16 on the matrix-core path.
+inline CtxLayout ctx_layout(const cp_head_desc &ds, bool fast)
+{
+    CtxLayout c;
+    size_t M = (size_t)ds.T * ds.n * ds.r, Tr = (size_t)ds.T * ds.r;
+    size_t off = 0;
+    c.lse = off;   off = align_up(off + M * 4);
+    c.w = off;     off = align_up(off + Tr * 4);
+    c.gamma = off; off = align_up(off + Tr * 4);
+    c.Y = off;     off = align_up(off + M * ds.d * (fast ? 2 : 4));
+    c.total = off;
+    return c;
+}
+
+inline bool use_fast_path(const cp_head_desc &ds)
+{
+    return false && ds.dtype == CP_HEAD_BF16 && (ds.d % 64) == 0 && !(ds.flags & CP_HEAD_FORCE_GENERIC);
+}
+
+// ---------------------------------------------------------------- generic (plain fp32) path
+size_t generic_workspace_bytes(const cp_head_desc &ds, int op);
+int generic_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, float *loss, void *ctx, void *ws, hipStream_t st);
+int generic_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, const float *dloss, float scale, const void *ctx,
+                     float *dH, float *dW, float *dU, float *dG, void *ws, hipStream_t st);
+int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                  const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, hipStream_t st);
+
+// Kernels of the generic path that the matrix-core path reuses (fp32 bookkeeping per position).
+void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *logw, float *w, hipStream_t st);
+void launch_mixture(const cp_head_desc &ds, const float *logw, const float *C, float *loss, float *gamma,
+                    hipStream_t st);
+void launch_fill_zero(float *p, size_t count, hipStream_t st);
+void launch_pick_alpha(const cp_head_desc &ds, const float *w, const float *uniforms, int32_t *alpha,
+                       hipStream_t st);
+
+// ---------------------------------------------------------------- matrix-core path
+size_t fast_workspace_bytes(const cp_head_desc &ds, int op);
+int fast_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                  const int32_t *X, float *loss, void *ctx, void *ws, size_t ws_bytes, hipStream_t st);
+int fast_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                  const int32_t *X, const float *dloss, float scale, const void *ctx,
+                  float *dH, float *dW, float *dU, float *dG, void *ws, size_t ws_bytes, hipStream_t st);
+int fast_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+               const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, size_t ws_bytes,
+               hipStream_t st);
+
+}  // namespace cph

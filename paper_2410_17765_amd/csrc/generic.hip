@@ -1,0 +1,529 @@
+// Plain fp32 path of the CP head: correct for every shape and storage type, no
+// tiling.  It serves fp32 storage and shapes the matrix-core path does not take,
+// and its per-position bookkeeping kernels (gate, mixture, expert draw) are
+// shared with that path.  One thread block per head row (t, s, a) or one thread
+// per output element; every sum runs in a fixed order, so results are reproducible.
+//
+// Head rows are ordered m = (t*n + s)*r + a, so X[m / r] is the row's target and
+// m / (n*r) its position.
+#include "cp_internal.hpp"
+
+#include <math.h>
+
+namespace cph {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+// ------------------------------------------------------------------------------------------
+// gate: logw = log_softmax(G h), w = exp(logw)      (eq. 7)
+// one wavefront per position; lane a ends up holding g_a
+// ------------------------------------------------------------------------------------------
+template <typename TIn>
+__global__ void __launch_bounds__(kWave) k_gate(int d, int r, const TIn *__restrict__ H, const TIn *__restrict__ G,
+                                                float *__restrict__ logw, float *__restrict__ w)
+{
+    const size_t t = blockIdx.x;
+    const int lane = threadIdx.x;
+    const TIn *h = H + t * d;
+    float mine = -INFINITY;
+    for (int a = 0; a < r; ++a) {
+        float p = 0.f;
+        for (int k = lane; k < d; k += kWave) p += ld_f32(G, (size_t)a * d + k) * ld_f32(h, k);
+        p = wave_sum(p);
+        if (lane == a) mine = p;
+    }
+    const float mx = wave_max(mine);
+    const float s = wave_sum(lane < r ? expf(mine - mx) : 0.f);
+    const float lse = mx + logf(s);
+    if (lane < r) {
+        logw[t * r + lane] = mine - lse;
+        w[t * r + lane] = expf(mine - lse);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// y = W_sa h for one head row m = (t, s, a); optional rounding of y to bf16
+// ------------------------------------------------------------------------------------------
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_y_generic(int d, int nr, const TIn *__restrict__ H,
+                                                      const TIn *__restrict__ W, float *__restrict__ Y, int round_y)
+{
+    extern __shared__ float hs[];
+    const size_t m = blockIdx.x;
+    const size_t t = m / nr;
+    const int sa = (int)(m % nr);
+    for (int k = threadIdx.x; k < d; k += kBlock) hs[k] = ld_f32(H, t * d + k);
+    __syncthreads();
+    const TIn *Wsa = W + (size_t)sa * d * d;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    for (int k = wave; k < d; k += kWavesPerBlock) {
+        float p = 0.f;
+        for (int j = lane; j < d; j += kWave) p += ld_f32(Wsa, (size_t)k * d + j) * hs[j];
+        p = wave_sum(p);
+        if (lane == 0) Y[m * d + k] = round_y ? bf16_to_f32(f32_to_bf16(p)) : p;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// z = U y for one head row; running (max, sum exp) over the vocabulary gives the
+// log-normaliser (eq. 5); C = z[x] - lse (eq. 8).  z is written only if z_out != NULL.
+// ------------------------------------------------------------------------------------------
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_zstats_generic(int d, int V, int r, const TIn *__restrict__ U,
+                                                           const float *__restrict__ Y, const int32_t *__restrict__ X,
+                                                           float *__restrict__ lse_out, float *__restrict__ C_out,
+                                                           float *__restrict__ z_out)
+{
+    extern __shared__ float ys[];
+    __shared__ float red_m[kWavesPerBlock], red_l[kWavesPerBlock], red_zt;
+    const size_t m = blockIdx.x;
+    for (int k = threadIdx.x; k < d; k += kBlock) ys[k] = Y[m * d + k];
+    if (threadIdx.x == 0) red_zt = 0.f;
+    __syncthreads();
+    const int x = X ? X[m / r] : -1;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    float mx = -INFINITY, l = 0.f;
+    for (int v = wave; v < V; v += kWavesPerBlock) {
+        float p = 0.f;
+        for (int k = lane; k < d; k += kWave) p += ld_f32(U, (size_t)v * d + k) * ys[k];
+        const float z = wave_sum(p);
+        if (z_out && lane == 0) z_out[m * V + v] = z;
+        if (z > mx) { l = l * expf(mx - z) + 1.f; mx = z; }
+        else l += expf(z - mx);
+        if (v == x && lane == 0) red_zt = z;
+    }
+    if (lane == 0) { red_m[wave] = mx; red_l[wave] = l; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float Mx = red_m[0];
+        for (int i = 1; i < kWavesPerBlock; ++i) Mx = fmaxf(Mx, red_m[i]);
+        float L = 0.f;
+        for (int i = 0; i < kWavesPerBlock; ++i) L += red_l[i] * expf(red_m[i] - Mx);
+        const float lse = Mx + logf(L);
+        lse_out[m] = lse;
+        if (C_out) C_out[m] = (x >= 0) ? red_zt - lse : 0.f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// mixture over experts (eq. 9) and the posterior gamma_a = exp(a_a - L); one wavefront per position
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kWave) k_mixture(int n, int r, const float *__restrict__ logw,
+                                                   const float *__restrict__ C, float *__restrict__ loss,
+                                                   float *__restrict__ gamma)
+{
+    const size_t t = blockIdx.x;
+    const int lane = threadIdx.x;
+    float a = -INFINITY;
+    if (lane < r) {
+        a = logw[t * r + lane];
+        for (int s = 0; s < n; ++s) a += C[(t * n + s) * r + lane];
+    }
+    const float mx = wave_max(a);
+    const float sum = wave_sum(lane < r ? expf(a - mx) : 0.f);
+    const float L = mx + logf(sum);
+    if (lane == 0) loss[t] = -L;
+    if (gamma && lane < r) gamma[t * r + lane] = expf(a - L);
+}
+
+// ------------------------------------------------------------------------------------------
+// backward pieces
+// ------------------------------------------------------------------------------------------
+
+__global__ void k_fill_zero(size_t count, float *__restrict__ p)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+// dg[t,a] = up_t (w_a - gamma_a): derivative of eq. 9 with respect to the gate pre-activations
+__global__ void k_dgate(size_t Tr, int r, const float *__restrict__ w, const float *__restrict__ gamma,
+                        const float *__restrict__ dloss, float scale, float *__restrict__ dg)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= Tr) return;
+    const float up = dloss ? dloss[i / r] * scale : scale;
+    dg[i] = up * (w[i] - gamma[i]);
+}
+
+// dz[v] = up_t gamma_a (softmax(z)[v] - 1[v = x]) for the rows m0 .. m0+gridDim.x-1
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_dz_generic(int d, int V, int n, int r, size_t m0,
+                                                       const TIn *__restrict__ U, const float *__restrict__ Y,
+                                                       const int32_t *__restrict__ X, const float *__restrict__ lse,
+                                                       const float *__restrict__ gamma,
+                                                       const float *__restrict__ dloss, float scale,
+                                                       float *__restrict__ dZ)
+{
+    extern __shared__ float ys[];
+    const size_t mc = blockIdx.x, m = m0 + mc;
+    for (int k = threadIdx.x; k < d; k += kBlock) ys[k] = Y[m * d + k];
+    __syncthreads();
+    const size_t t = m / ((size_t)n * r);
+    const int a = (int)(m % r);
+    const int x = X[m / r];
+    const float up = dloss ? dloss[t] * scale : scale;
+    const float coef = up * gamma[t * r + a];
+    const float l = lse[m];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    for (int v = wave; v < V; v += kWavesPerBlock) {
+        float p = 0.f;
+        for (int k = lane; k < d; k += kWave) p += ld_f32(U, (size_t)v * d + k) * ys[k];
+        const float z = wave_sum(p);
+        if (lane == 0) dZ[mc * V + v] = (x < 0) ? 0.f : coef * (expf(z - l) - (v == x ? 1.f : 0.f));
+    }
+}
+
+// dY[m,k] = sum_v dZ[mc,v] U[v,k]
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_dy_generic(int d, int V, size_t m0, size_t Mc,
+                                                       const TIn *__restrict__ U, const float *__restrict__ dZ,
+                                                       float *__restrict__ dY)
+{
+    const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= Mc * d) return;
+    const size_t mc = idx / d;
+    const int k = (int)(idx % d);
+    float acc = 0.f;
+    for (int v = 0; v < V; ++v) acc += dZ[mc * V + v] * ld_f32(U, (size_t)v * d + k);
+    dY[(m0 + mc) * d + k] = acc;
+}
+
+// dU[v,k] (+)= sum_mc dZ[mc,v] Y[m0+mc,k]
+__global__ void __launch_bounds__(kBlock) k_du_generic(int d, int V, size_t m0, size_t Mc,
+                                                       const float *__restrict__ dZ, const float *__restrict__ Y,
+                                                       float *__restrict__ dU, int accumulate)
+{
+    const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= (size_t)V * d) return;
+    const size_t v = idx / d;
+    const int k = (int)(idx % d);
+    float acc = accumulate ? dU[idx] : 0.f;
+    for (size_t mc = 0; mc < Mc; ++mc) acc += dZ[mc * V + v] * Y[(m0 + mc) * d + k];
+    dU[idx] = acc;
+}
+
+// dW[sa,k,j] = sum_t dY[(t,sa),k] H[t,j]
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_dw_generic(size_t T, int d, int nr, const TIn *__restrict__ H,
+                                                       const float *__restrict__ dY, float *__restrict__ dW)
+{
+    const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= (size_t)nr * d * d) return;
+    const int j = (int)(idx % d);
+    const size_t sak = idx / d;
+    const size_t sa = sak / d;
+    const int k = (int)(sak % d);
+    float acc = 0.f;
+    for (size_t t = 0; t < T; ++t) acc += dY[(t * nr + sa) * d + k] * ld_f32(H, t * d + j);
+    dW[idx] = acc;
+}
+
+// dH[t,j] = sum_{sa,k} dY[(t,sa),k] W[sa,k,j] + sum_a dg[t,a] G[a,j]
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_dh_generic(size_t T, int d, int nr, int r, const TIn *__restrict__ W,
+                                                       const TIn *__restrict__ G, const float *__restrict__ dY,
+                                                       const float *__restrict__ dg, float *__restrict__ dH)
+{
+    const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= T * d) return;
+    const size_t t = idx / d;
+    const int j = (int)(idx % d);
+    float acc = 0.f;
+    for (int sa = 0; sa < nr; ++sa)
+        for (int k = 0; k < d; ++k) acc += dY[(t * nr + sa) * d + k] * ld_f32(W, ((size_t)sa * d + k) * d + j);
+    for (int a = 0; a < r; ++a) acc += dg[t * r + a] * ld_f32(G, (size_t)a * d + j);
+    dH[idx] = acc;
+}
+
+// dG[a,j] = sum_t dg[t,a] H[t,j]
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_dg_generic(size_t T, int d, int r, const TIn *__restrict__ H,
+                                                       const float *__restrict__ dg, float *__restrict__ dG)
+{
+    const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= (size_t)r * d) return;
+    const int a = (int)(idx / d);
+    const int j = (int)(idx % d);
+    float acc = 0.f;
+    for (size_t t = 0; t < T; ++t) acc += dg[t * r + a] * ld_f32(H, t * d + j);
+    dG[idx] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
+// draft pieces
+// ------------------------------------------------------------------------------------------
+
+// expert draw: first a with cdf_w[a] > u, running sum in fp64, clamp to r-1
+__global__ void k_pick_alpha(size_t B, int n, int r, const float *__restrict__ w, const float *__restrict__ uniforms,
+                             int32_t *__restrict__ alpha)
+{
+    const size_t b = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const double u = (double)uniforms[b * (1 + n)];
+    double c = 0.0;
+    int pick = r - 1;
+    bool found = false;
+    for (int a = 0; a < r; ++a) {
+        c += (double)w[b * r + a];
+        if (!found && c > u) { pick = a; found = true; }
+    }
+    alpha[b] = pick;
+}
+
+// token draw for (b, s) from the stored logits of row (b, s, a*): thread i owns a contiguous
+// segment of the vocabulary; segment sums in fp64, then one thread walks the segment sums and
+// the owner of the crossing segment walks its tokens.
+__global__ void __launch_bounds__(kBlock) k_sample_generic(int V, int n, int r, const float *__restrict__ z,
+                                                           const float *__restrict__ lse,
+                                                           const int32_t *__restrict__ alpha,
+                                                           const float *__restrict__ uniforms,
+                                                           int32_t *__restrict__ tokens)
+{
+    __shared__ double seg_sum[kBlock];
+    __shared__ double base;
+    __shared__ int chosen;
+    const size_t bs = blockIdx.x;            // b*n + s
+    const size_t b = bs / n;
+    const int s = (int)(bs % n);
+    const size_t row = bs * r + alpha[b];
+    const float *zr = z + row * V;
+    const float l = lse[row];
+    const double u = (double)uniforms[b * (1 + n) + 1 + s];
+    const int seg = (V + kBlock - 1) / kBlock;
+    const int lo = min(V, (int)threadIdx.x * seg), hi = min(V, lo + seg);
+    double sum = 0.0;
+    for (int v = lo; v < hi; ++v) sum += (double)expf(zr[v] - l);
+    seg_sum[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double c = 0.0;
+        int pick = -1;
+        for (int i = 0; i < kBlock; ++i) {
+            if (c + seg_sum[i] > u) { pick = i; break; }
+            c += seg_sum[i];
+        }
+        chosen = pick;
+        base = c;
+        if (pick < 0) tokens[bs] = V - 1;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x == chosen) {
+        double c = base;
+        int tok = hi - 1;
+        for (int v = lo; v < hi; ++v) {
+            c += (double)expf(zr[v] - l);
+            if (c > u) { tok = v; break; }
+        }
+        tokens[bs] = tok;
+    }
+}
+
+// logq[b] = logsumexp_a( logw_a + sum_s (z_sa[tok_s] - lse_sa) )    (eq. 9 at the drawn tuple)
+__global__ void __launch_bounds__(kWave) k_logq_generic(int V, int n, int r, const float *__restrict__ logw,
+                                                        const float *__restrict__ z, const float *__restrict__ lse,
+                                                        const int32_t *__restrict__ tokens, float *__restrict__ logq)
+{
+    const size_t b = blockIdx.x;
+    const int lane = threadIdx.x;
+    float a = -INFINITY;
+    if (lane < r) {
+        a = logw[b * r + lane];
+        for (int s = 0; s < n; ++s) {
+            const size_t row = (b * n + s) * r + lane;
+            a += z[row * V + tokens[b * n + s]] - lse[row];
+        }
+    }
+    const float mx = wave_max(a);
+    const float sum = wave_sum(lane < r ? expf(a - mx) : 0.f);
+    if (lane == 0) logq[b] = mx + logf(sum);
+}
+
+// rows of the dZ chunk on this path: at most 512 MiB of fp32 logit gradients at a time
+inline size_t generic_chunk_rows(const cp_head_desc &ds)
+{
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    size_t rows = ((size_t)1 << 27) / (size_t)ds.V;
+    if (rows < 1) rows = 1;
+    return rows < M ? rows : (M ? M : 1);
+}
+
+struct GenericWs {
+    size_t logw, C, dY, dZ, dg, w, Y, z, lse, total;
+};
+
+inline GenericWs generic_ws(const cp_head_desc &ds, int op)
+{
+    GenericWs g = {};
+    const size_t M = (size_t)ds.T * ds.n * ds.r, Tr = (size_t)ds.T * ds.r;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    if (op == CP_HEAD_OP_LOSS_FWD) {
+        g.logw = take(Tr * 4);
+        g.C = take(M * 4);
+    } else if (op == CP_HEAD_OP_LOSS_BWD) {
+        g.dY = take(M * ds.d * 4);
+        g.dZ = take(generic_chunk_rows(ds) * ds.V * 4);
+        g.dg = take(Tr * 4);
+    } else {
+        g.logw = take(Tr * 4);
+        g.w = take(Tr * 4);
+        g.Y = take(M * ds.d * 4);
+        g.z = take(M * ds.V * 4);
+        g.lse = take(M * 4);
+    }
+    g.total = off;
+    return g;
+}
+
+template <typename T>
+inline T *at(void *base, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(base) + off); }
+template <typename T>
+inline const T *at(const void *base, size_t off) { return reinterpret_cast<const T *>(static_cast<const char *>(base) + off); }
+
+template <typename TIn>
+int loss_fwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const int32_t *X,
+               float *loss, void *ctx, void *ws, hipStream_t st)
+{
+    const CtxLayout cl = ctx_layout(ds, false);
+    const GenericWs g = generic_ws(ds, CP_HEAD_OP_LOSS_FWD);
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    float *Y = at<float>(ctx, cl.Y);
+    float *logw = at<float>(ws, g.logw), *C = at<float>(ws, g.C);
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    k_gate<TIn><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
+    k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, Y, 0);
+    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, X, lse, C, nullptr);
+    k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, loss, gamma);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+template <typename TIn>
+int loss_bwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const int32_t *X,
+               const float *dloss, float scale, const void *ctx, float *dH, float *dW, float *dU, float *dG,
+               void *ws, hipStream_t st)
+{
+    const CtxLayout cl = ctx_layout(ds, false);
+    const GenericWs g = generic_ws(ds, CP_HEAD_OP_LOSS_BWD);
+    const size_t T = (size_t)ds.T, M = T * ds.n * ds.r, Tr = T * ds.r;
+    const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    const float *Y = at<float>(ctx, cl.Y);
+    float *dY = at<float>(ws, g.dY), *dZ = at<float>(ws, g.dZ), *dg = at<float>(ws, g.dg);
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    const size_t chunk = generic_chunk_rows(ds);
+    k_dgate<<<blocks_for(Tr, kBlock), kBlock, 0, st>>>(Tr, ds.r, w, gamma, dloss, scale, dg);
+    int first = 1;
+    for (size_t m0 = 0; m0 < M; m0 += chunk) {
+        const size_t Mc = (M - m0 < chunk) ? M - m0 : chunk;
+        k_dz_generic<TIn><<<(unsigned)Mc, kBlock, lds, st>>>(ds.d, ds.V, ds.n, ds.r, m0, U, Y, X, lse, gamma, dloss,
+                                                             scale, dZ);
+        k_dy_generic<TIn><<<blocks_for(Mc * ds.d, kBlock), kBlock, 0, st>>>(ds.d, ds.V, m0, Mc, U, dZ, dY);
+        if (dU)
+            k_du_generic<<<blocks_for((size_t)ds.V * ds.d, kBlock), kBlock, 0, st>>>(ds.d, ds.V, m0, Mc, dZ, Y, dU,
+                                                                                    first ? 0 : 1);
+        first = 0;
+    }
+    if (dW)
+        k_dw_generic<TIn><<<blocks_for((size_t)ds.n * ds.r * ds.d * ds.d, kBlock), kBlock, 0, st>>>(T, ds.d,
+                                                                                                  ds.n * ds.r, H, dY, dW);
+    k_dh_generic<TIn><<<blocks_for(T * ds.d, kBlock), kBlock, 0, st>>>(T, ds.d, ds.n * ds.r, ds.r, W, G, dY, dg, dH);
+    if (dG) k_dg_generic<TIn><<<blocks_for((size_t)ds.r * ds.d, kBlock), kBlock, 0, st>>>(T, ds.d, ds.r, H, dg, dG);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+template <typename TIn>
+int draft_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const float *uniforms,
+            int32_t *alpha, int32_t *tokens, float *logq, void *ws, hipStream_t st)
+{
+    const GenericWs g = generic_ws(ds, CP_HEAD_OP_DRAFT);
+    const size_t B = (size_t)ds.T, M = B * ds.n * ds.r;
+    float *logw = at<float>(ws, g.logw), *w = at<float>(ws, g.w), *Y = at<float>(ws, g.Y);
+    float *z = at<float>(ws, g.z), *lse = at<float>(ws, g.lse);
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    const int round_y = ds.dtype == CP_HEAD_BF16 ? 1 : 0;
+    k_gate<TIn><<<(unsigned)B, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
+    k_pick_alpha<<<blocks_for(B, kWave), kWave, 0, st>>>(B, ds.n, ds.r, w, uniforms, alpha);
+    k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, Y, round_y);
+    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, nullptr, lse, nullptr, z);
+    k_sample_generic<<<(unsigned)(B * ds.n), kBlock, 0, st>>>(ds.V, ds.n, ds.r, z, lse, alpha, uniforms, tokens);
+    if (logq) k_logq_generic<<<(unsigned)B, kWave, 0, st>>>(ds.V, ds.n, ds.r, logw, z, lse, tokens, logq);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+}  // namespace
+
+size_t generic_workspace_bytes(const cp_head_desc &ds, int op) { return generic_ws(ds, op).total; }
+
+int generic_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, float *loss, void *ctx, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (ds.dtype == CP_HEAD_FP32)
+        return loss_fwd_t<float>(ds, (const float *)H, (const float *)W, (const float *)U, (const float *)G, X, loss,
+                                 ctx, ws, st);
+    return loss_fwd_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G, X, loss,
+                              ctx, ws, st);
+}
+
+void launch_fill_zero(float *p, size_t count, hipStream_t st)
+{
+    if (p && count) k_fill_zero<<<blocks_for(count, kBlock), kBlock, 0, st>>>(count, p);
+}
+
+int generic_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, const float *dloss, float scale, const void *ctx, float *dH, float *dW,
+                     float *dU, float *dG, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) {   // empty batch: the weight gradients are empty sums
+        launch_fill_zero(dW, (size_t)ds.n * ds.r * ds.d * ds.d, st);
+        launch_fill_zero(dU, (size_t)ds.V * ds.d, st);
+        launch_fill_zero(dG, (size_t)ds.r * ds.d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (ds.dtype == CP_HEAD_FP32)
+        return loss_bwd_t<float>(ds, (const float *)H, (const float *)W, (const float *)U, (const float *)G, X, dloss,
+                                 scale, ctx, dH, dW, dU, dG, ws, st);
+    return loss_bwd_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G, X,
+                              dloss, scale, ctx, dH, dW, dU, dG, ws, st);
+}
+
+int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                  const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (ds.dtype == CP_HEAD_FP32)
+        return draft_t<float>(ds, (const float *)H, (const float *)W, (const float *)U, (const float *)G, uniforms,
+                              alpha, tokens, logq, ws, st);
+    return draft_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G, uniforms,
+                           alpha, tokens, logq, ws, st);
+}
+
+void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *logw, float *w, hipStream_t st)
+{
+    if (ds.T == 0) return;
+    if (ds.dtype == CP_HEAD_FP32)
+        k_gate<float><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, (const float *)H, (const float *)G, logw, w);
+    else
+        k_gate<bf16_t><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, (const bf16_t *)H, (const bf16_t *)G, logw, w);
+}
+
+void launch_mixture(const cp_head_desc &ds, const float *logw, const float *C, float *loss, float *gamma,
+                    hipStream_t st)
+{
+    if (ds.T == 0) return;
+    k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, loss, gamma);
+}
+
+void launch_pick_alpha(const cp_head_desc &ds, const float *w, const float *uniforms, int32_t *alpha, hipStream_t st)
+{
+    if (ds.T == 0) return;
+    k_pick_alpha<<<blocks_for((size_t)ds.T, kWave), kWave, 0, st>>>((size_t)ds.T, ds.n, ds.r, w, uniforms, alpha);
+}
+
+}  // namespace cph

@@ -1,0 +1,87 @@
+"""Convenience holder of device buffers for the three C-ABI calls.
+
+Only memory management lives here (torch tensors on ``cuda:0`` for inputs,
+outputs, ctx and workspace); every computation is a call through ``binding``.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding, synth
+
+
+def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """Upload a float32 array whose values are exact in `dtype` ("fp32" or "bf16")."""
+    if dtype == "bf16":
+        bits = synth.bf16_bits(x).view(np.int16)
+        return torch.from_numpy(bits).to(device).view(torch.bfloat16).reshape(x.shape)
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device)
+
+
+def _scratch(nbytes: int, device) -> torch.Tensor:
+    # torch's caching allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+class CpHead:
+    """Weights of one head on the device plus the scratch the calls need."""
+
+    def __init__(self, W: np.ndarray, U: np.ndarray, G: np.ndarray, dtype: str = "bf16", flags: int = 0,
+                 device="cuda:0"):
+        self.device = torch.device(device)
+        self.dtype = dtype
+        self.flags = flags
+        self.n, self.r, self.d, _ = W.shape
+        self.V = U.shape[0]
+        self.W = to_device(W, dtype, self.device)
+        self.U = to_device(U, dtype, self.device)
+        self.G = to_device(G, dtype, self.device)
+        self._ctx: Optional[torch.Tensor] = None
+        self._desc = None
+
+    def desc(self, T: int) -> binding.Desc:
+        return binding.make_desc(T, self.d, self.V, self.n, self.r,
+                                 binding.BF16 if self.dtype == "bf16" else binding.FP32, self.flags)
+
+    # ------------------------------------------------------------------ loss
+    def loss_fwd(self, H: torch.Tensor, X: torch.Tensor, stream=None) -> torch.Tensor:
+        """H[T,d] (storage dtype), X[T,n] int32 on the device -> loss[T] fp32 (device).  Keeps ctx for loss_bwd."""
+        T = H.shape[0]
+        ds = self.desc(T)
+        self._ctx = _scratch(binding.cp_head_ctx_bytes(ds), self.device)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD), self.device)
+        loss = torch.empty(T, dtype=torch.float32, device=self.device)
+        binding.cp_head_loss_fwd(ds, H, self.W, self.U, self.G, X, loss, self._ctx, ws, stream)
+        self._desc = ds
+        return loss
+
+    def loss_bwd(self, H: torch.Tensor, X: torch.Tensor, dloss: Optional[torch.Tensor] = None, scale: float = 1.0,
+                 want_dU: bool = True, stream=None) -> Dict[str, torch.Tensor]:
+        assert self._ctx is not None, "call loss_fwd first"
+        T = H.shape[0]
+        ds = self.desc(T)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_BWD), self.device)
+        f32 = dict(dtype=torch.float32, device=self.device)
+        out = {
+            "dH": torch.empty((T, self.d), **f32),
+            "dW": torch.empty((self.n, self.r, self.d, self.d), **f32),
+            "dU": torch.empty((self.V, self.d), **f32) if want_dU else None,
+            "dG": torch.empty((self.r, self.d), **f32),
+        }
+        binding.cp_head_loss_bwd(ds, H, self.W, self.U, self.G, X, dloss, scale, self._ctx,
+                                 out["dH"], out["dW"], out["dU"], out["dG"], ws, stream)
+        return {k: v for k, v in out.items() if v is not None}
+
+    # ------------------------------------------------------------------ draft
+    def draft_sample(self, H: torch.Tensor, uniforms: torch.Tensor, stream=None):
+        B = H.shape[0]
+        ds = self.desc(B)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT), self.device)
+        alpha = torch.empty(B, dtype=torch.int32, device=self.device)
+        tokens = torch.empty((B, self.n), dtype=torch.int32, device=self.device)
+        logq = torch.empty(B, dtype=torch.float32, device=self.device)
+        binding.cp_head_draft_sample(ds, H, self.W, self.U, self.G, uniforms, alpha, tokens, logq, ws, stream)
+        return alpha, tokens, logq

@@ -1,0 +1,104 @@
+"""Host-side checks of libcphead.so that need no GPU: the library loads, exports every symbol the
+header declares, answers the size queries and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_17765_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2410_17765_amd import build
+        build.build(verbose=False)
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cp_head.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cp_head_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror(lib):
+    assert binding.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert binding.strerror(code)
+
+
+def test_size_queries(lib):
+    ds = binding.make_desc(64, 64, 512, 2, 2, binding.FP32)
+    ctx = binding.cp_head_ctx_bytes(ds)
+    M = 64 * 2 * 2
+    assert ctx >= M * 4 + 2 * 64 * 2 * 4 + M * 64 * 4
+    for op in (binding.OP_LOSS_FWD, binding.OP_LOSS_BWD, binding.OP_DRAFT):
+        assert binding.cp_head_workspace_bytes(ds, op) > 0
+    # the backward workspace does not keep logit-sized buffers for all rows: it stops growing with T
+    big = binding.make_desc(1 << 20, 64, 512, 2, 2, binding.FP32)
+    huge = binding.make_desc(1 << 21, 64, 512, 2, 2, binding.FP32)
+    per_row_big = binding.cp_head_workspace_bytes(big, binding.OP_LOSS_BWD) / (1 << 20)
+    per_row_huge = binding.cp_head_workspace_bytes(huge, binding.OP_LOSS_BWD) / (1 << 21)
+    assert per_row_huge < 2 * 2 * 512 * 2      # far below one row of logits per head row
+    assert per_row_huge <= per_row_big + 1
+
+
+def test_headline_shape_sizes(lib):
+    ds = binding.make_desc(16384, 4096, 32000, 4, 8, binding.BF16)
+    logits_bytes = 16384 * 32 * 32000 * 2
+    assert binding.cp_head_ctx_bytes(ds) < logits_bytes // 4
+    assert binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD) < logits_bytes // 4
+
+
+@pytest.mark.parametrize("kw", [dict(T=-1), dict(d=0), dict(V=0), dict(n=0), dict(r=0)])
+def test_bad_dimensions(lib, kw):
+    base = dict(T=4, d=8, V=16, n=2, r=2)
+    base.update(kw)
+    ds = binding.make_desc(base["T"], base["d"], base["V"], base["n"], base["r"], binding.FP32)
+    out = ctypes.c_size_t()
+    assert lib.cp_head_ctx_bytes(ctypes.byref(ds), ctypes.byref(out)) == -1
+
+
+def test_unsupported(lib):
+    out = ctypes.c_size_t()
+    assert lib.cp_head_ctx_bytes(ctypes.byref(binding.make_desc(4, 8, 16, 2, 65, binding.FP32)),
+                                 ctypes.byref(out)) == -2
+    assert lib.cp_head_ctx_bytes(ctypes.byref(binding.make_desc(4, 8, 16, 2, 2, 7)), ctypes.byref(out)) == -2
+    assert lib.cp_head_ctx_bytes(None, ctypes.byref(out)) == -1
+    assert lib.cp_head_workspace_bytes(ctypes.byref(binding.make_desc(4, 8, 16, 2, 2, 0)), 9,
+                                       ctypes.byref(out)) == -1
+
+
+def test_null_and_small_workspace_rejected_before_launch(lib):
+    # fake, aligned, never dereferenced "device pointers": every call must fail in validation
+    ds = binding.make_desc(4, 8, 16, 2, 2, binding.FP32)
+    p = 0x10000
+    need = binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD)
+    args = [ctypes.byref(ds), p, p, p, p, p, p, p, p, need, None]
+    bad = list(args); bad[2] = None
+    assert lib.cp_head_loss_fwd(*bad) == -1
+    bad = list(args); bad[8] = p + 8            # misaligned workspace
+    assert lib.cp_head_loss_fwd(*bad) == -1
+    bad = list(args); bad[9] = need - 1
+    assert lib.cp_head_loss_fwd(*bad) == -3
+    needb = binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_BWD)
+    argsb = [ctypes.byref(ds), p, p, p, p, p, None, 1.0, p, p, p, p, p, p, needb - 1, None]
+    assert lib.cp_head_loss_bwd(*argsb) == -3
+    argsb[14] = needb; argsb[9] = None          # dH is required
+    assert lib.cp_head_loss_bwd(*argsb) == -1
+    needd = binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT)
+    argsd = [ctypes.byref(ds), p, p, p, p, p, None, p, p, p, needd, None]
+    assert lib.cp_head_draft_sample(*argsd) == -1
+    argsd[6] = p; argsd[10] = 0
+    assert lib.cp_head_draft_sample(*argsd) == -3
