@@ -1,0 +1,185 @@
+"""Benchmark of the CP-head hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input:
+cp_head_loss_fwd followed by cp_head_loss_bwd (all gradients, unembedding not
+frozen).  Inputs are resident in HBM before the timed region.  One JSON line
+is printed: whole-job positions/s ("token" = one position, each predicting n
+future tokens), the roofline of the dominant kernel timed with events on the
+launch stream, and the fp64 CPU oracle timed on a bounded sample of the same
+workload as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads) or 'draft'")
+    ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per thread)")
+    ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
+    return ap.parse_args()
+
+
+def cpu_baseline_loss(cfg, inp, positions):
+    """The oracle, as it stands, on a few positions of the same workload (forward + backward)."""
+    import numpy as np
+    from oracle import cp_oracle
+    from paper_2410_17765_amd import synth
+    cp_oracle.build()
+    cores = cp_oracle.num_threads()
+    S = positions or cores
+    sel = synth.position_subset(cfg.T, S)
+    H, X = inp["H"][sel], inp["X"][sel]
+    t0 = time.time()
+    cp_oracle.loss_fwd(H, inp["W"], inp["U"], inp["G"], X)
+    cp_oracle.loss_bwd(H, inp["W"], inp["U"], inp["G"], X, np.ones(len(sel)))
+    dt = time.time() - t0
+    return {"value": len(sel) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(sel)} seeded positions of the workload at full d, V, n, r; fp64 forward + backward "
+                      f"with all gradients; {dt:.1f} s wall"}
+
+
+def bench_loss(args):
+    import numpy as np
+    import torch
+    from paper_2410_17765_amd import binding, head, synth
+
+    cfg = synth.CONFIGS[args.workload]
+    binding.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t0 = time.time()
+    inp = synth.make_inputs(cfg)
+    print(f"[bench] inputs for {cfg.name} generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    H = head.to_device(inp["H"], cfg.dtype)
+    X = torch.from_numpy(inp["X"]).to(dev)
+    ds = h.desc(cfg.T)
+    ctx = torch.empty(binding.cp_head_ctx_bytes(ds), dtype=torch.uint8, device=dev)
+    ws_bytes = max(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD),
+                   binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_BWD))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    loss = torch.empty(cfg.T, **f32)
+    dH = torch.empty((cfg.T, cfg.d), **f32)
+    dW = torch.empty((cfg.n, cfg.r, cfg.d, cfg.d), **f32)
+    dU = None if args.frozen_u else torch.empty((cfg.V, cfg.d), **f32)
+    dG = torch.empty((cfg.r, cfg.d), **f32)
+    scale = 1.0 / cfg.T
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
+        binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, dU, dG, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.cp_head_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    binding.cp_head_profile_enable(False)
+    kernels = binding.cp_head_profile_read()
+    ms_per_step = dt * 1e3 / args.steps
+    value = cfg.T * args.steps / dt
+    mean_loss = float(loss.mean())
+
+    # roofline of the dominant matrix-product kernel: algorithmic FLOPs of its launches / their summed duration
+    gemms = [k for k in kernels if k[0].startswith("gemm_")]
+    dom = max(gemms, key=lambda k: k[2])
+    achieved = dom[3] / (dom[2] * 1e-3) / 1e12
+    roof = {"bound": "mfma", "kernel": dom[0], "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+            "launches": dom[1], "avg_ms": dom[2] / dom[1]}
+    model_flops = 6.0 * cfg.n * cfg.r * cfg.d * (cfg.d + cfg.V) * cfg.T
+    if args.frozen_u:
+        model_flops = 2.0 * cfg.n * cfg.r * cfg.d * (3 * cfg.d + 2 * cfg.V) * cfg.T
+    out = {
+        "metric": "CP-head fwd+bwd tokens/s", "value": value, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
+                   "frozen_u": bool(args.frozen_u), "token": "one position (n future tokens each)"},
+        "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
+        "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "mean_loss": mean_loss,
+        "roofline": roof,
+        "kernels": [{"name": k[0], "launches": k[1], "ms_per_step": k[2] / args.steps,
+                     "rate": (k[3] / (k[2] * 1e-3) / 1e12) if k[2] > 0 else None,
+                     "rate_unit": "TFLOP/s" if k[0].startswith("gemm_") else "TB/s"} for k in kernels],
+    }
+    if not args.no_cpu_baseline:
+        del ws, ctx, dW
+        out["cpu_baseline"] = cpu_baseline_loss(cfg, inp, args.cpu_positions)
+    return out
+
+
+def bench_draft(args):
+    import torch
+    from paper_2410_17765_amd import binding, head, synth
+
+    cfg = synth.CONFIGS["draft"].with_(T=args.batch)
+    binding.lib()
+    dev = torch.device("cuda:0")
+    inp = synth.make_inputs(cfg)
+    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    H = head.to_device(inp["H"], cfg.dtype)
+    u = torch.from_numpy(synth.uniforms(cfg.T, cfg.n)).to(dev)
+    ds = h.desc(cfg.T)
+    ws = torch.empty(binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT), dtype=torch.uint8, device=dev)
+    alpha = torch.empty(cfg.T, dtype=torch.int32, device=dev)
+    tokens = torch.empty((cfg.T, cfg.n), dtype=torch.int32, device=dev)
+    logq = torch.empty(cfg.T, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    step = lambda: binding.cp_head_draft_sample(ds, H, h.W, h.U, h.G, u, alpha, tokens, logq, ws, stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt * 1e3 / args.steps
+    weight_bytes = 2.0 * cfg.n * cfg.r * cfg.d * cfg.d + 2.0 * cfg.V * cfg.d
+    gbs = weight_bytes / (ms * 1e-3) / 1e9
+    return {
+        "metric": "CP-head draft step latency", "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "draft", "B": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": None},
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    out = bench_draft(args) if args.workload == "draft" else bench_loss(args)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

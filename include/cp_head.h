@@ -51,8 +51,11 @@ enum {
 };
 
 enum {
-    CP_HEAD_FORCE_GENERIC = 1   /* flags bit 0: use the plain fp32 path even where the
+    CP_HEAD_FORCE_GENERIC = 1,  /* flags bit 0: use the plain fp32 path even where the
                                    matrix-core path applies (a second opinion in tests) */
+    CP_HEAD_MIN_WORKSPACE = 2   /* flags bit 1: the backward pass holds logit gradients for one
+                                   tile of 256 head rows at a time (least workspace, slower)
+                                   instead of its default of about 2 GiB worth of rows */
 };
 
 enum {
@@ -72,7 +75,7 @@ typedef struct cp_head_desc {
     int32_t n;        /* future tokens per position */
     int32_t r;        /* CP rank = number of experts */
     int32_t dtype;    /* CP_HEAD_FP32 or CP_HEAD_BF16 */
-    int32_t flags;    /* CP_HEAD_FORCE_GENERIC or 0 */
+    int32_t flags;    /* OR of CP_HEAD_FORCE_GENERIC, CP_HEAD_MIN_WORKSPACE, or 0 */
 } cp_head_desc;
 
 /* Human-readable text for an error code (static storage). */
@@ -141,6 +144,26 @@ int cp_head_draft_sample(const cp_head_desc *desc,
                          const float *uniforms,
                          int32_t *alpha, int32_t *tokens, float *logq,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Optional per-kernel timing for benchmarks (not part of the method).  While
+ * enabled, every large launch inside the three calls above is bracketed by a
+ * pair of events on the stream it is launched on.  cp_head_profile_read waits
+ * for those events, folds them by kernel name (launch count, total
+ * milliseconds, total work: FLOPs for the matrix products, bytes for the
+ * transposes), clears the list and writes up to max_entries rows; *count
+ * receives the number of distinct names.  Not thread-safe; the event objects
+ * are the only thing the library ever creates.
+ */
+typedef struct cp_head_kernel_time {
+    char name[32];
+    int32_t launches;
+    double total_ms;
+    double total_work;
+} cp_head_kernel_time;
+
+int cp_head_profile_enable(int on);
+int cp_head_profile_read(cp_head_kernel_time *out, int max_entries, int *count);
 
 #ifdef __cplusplus
 }

@@ -14,6 +14,7 @@ from typing import Optional
 FP32 = 0
 BF16 = 1
 FORCE_GENERIC = 1
+MIN_WORKSPACE = 2
 OP_LOSS_FWD, OP_LOSS_BWD, OP_DRAFT = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -21,7 +22,8 @@ LIB_PATH = os.path.join(_PKG, "libcphead.so")
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("cp_head_strerror", "cp_head_ctx_bytes", "cp_head_workspace_bytes",
-           "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample")
+           "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample",
+           "cp_head_profile_enable", "cp_head_profile_read")
 
 
 class CpHeadError(RuntimeError):
@@ -33,6 +35,11 @@ class CpHeadError(RuntimeError):
 class Desc(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int64), ("d", ctypes.c_int32), ("V", ctypes.c_int32), ("n", ctypes.c_int32),
                 ("r", ctypes.c_int32), ("dtype", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+class KernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 32), ("launches", ctypes.c_int32), ("total_ms", ctypes.c_double),
+                ("total_work", ctypes.c_double)]
 
 
 def lib() -> ctypes.CDLL:
@@ -52,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.cp_head_loss_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, ctypes.c_float, vp,
                                        vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_draft_sample.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_profile_enable.argtypes = [ctypes.c_int]
+        L.cp_head_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         for name in EXPORTS[1:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -125,3 +134,18 @@ def cp_head_draft_sample(desc: Desc, H, W, U, G, uniforms, alpha, tokens, logq, 
                                     _stream(stream))
     if rc != 0:
         raise CpHeadError(rc, "cp_head_draft_sample")
+
+
+def cp_head_profile_enable(on: bool) -> None:
+    lib().cp_head_profile_enable(1 if on else 0)
+
+
+def cp_head_profile_read(max_entries: int = 64):
+    """[(name, launches, total_ms, total_work)] since profiling was enabled (clears the list)."""
+    rows = (KernelTime * max_entries)()
+    count = ctypes.c_int(0)
+    rc = lib().cp_head_profile_read(rows, max_entries, ctypes.byref(count))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_profile_read")
+    return [(rows[i].name.decode(), rows[i].launches, rows[i].total_ms, rows[i].total_work)
+            for i in range(min(count.value, max_entries))]

@@ -1,7 +1,40 @@
 // C ABI of libcphead.so: argument checks, path selection, dispatch.
 #include "cp_internal.hpp"
 
+#include <stdio.h>
+
+#include <mutex>
+#include <string>
+#include <vector>
+
 using namespace cph;
+
+// ---------------------------------------------------------------- optional per-kernel timing
+namespace {
+struct ProfileRecord {
+    const char *name;
+    double work;
+    hipEvent_t start, stop;
+};
+bool g_profile_on = false;
+std::vector<ProfileRecord> g_profile;
+}  // namespace
+
+namespace cph {
+void profile_begin(const char *name, double work, hipStream_t st)
+{
+    if (!g_profile_on) return;
+    ProfileRecord rec{name, work, nullptr, nullptr};
+    if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) return;
+    (void)hipEventRecord(rec.start, st);
+    g_profile.push_back(rec);
+}
+void profile_end(hipStream_t st)
+{
+    if (!g_profile_on || g_profile.empty()) return;
+    (void)hipEventRecord(g_profile.back().stop, st);
+}
+}  // namespace cph
 
 namespace {
 
@@ -38,6 +71,41 @@ const char *cp_head_strerror(int code)
     case CP_HEAD_ERR_LAUNCH: return "kernel launch failed";
     default: return "unknown error code";
     }
+}
+
+int cp_head_profile_enable(int on)
+{
+    g_profile_on = on != 0;
+    return CP_HEAD_OK;
+}
+
+int cp_head_profile_read(cp_head_kernel_time *out, int max_entries, int *count)
+{
+    if (!count || (max_entries > 0 && !out)) return CP_HEAD_ERR_INVALID_ARG;
+    // fold the records by kernel name, in order of first appearance
+    std::vector<cp_head_kernel_time> rows;
+    for (ProfileRecord &rec : g_profile) {
+        float ms = 0.f;
+        (void)hipEventSynchronize(rec.stop);
+        (void)hipEventElapsedTime(&ms, rec.start, rec.stop);
+        (void)hipEventDestroy(rec.start);
+        (void)hipEventDestroy(rec.stop);
+        size_t i = 0;
+        for (; i < rows.size(); ++i)
+            if (std::string(rows[i].name) == rec.name) break;
+        if (i == rows.size()) {
+            cp_head_kernel_time row = {};
+            snprintf(row.name, sizeof(row.name), "%s", rec.name);
+            rows.push_back(row);
+        }
+        rows[i].launches += 1;
+        rows[i].total_ms += ms;
+        rows[i].total_work += rec.work;
+    }
+    g_profile.clear();
+    *count = (int)rows.size();
+    for (int i = 0; i < max_entries && i < (int)rows.size(); ++i) out[i] = rows[i];
+    return CP_HEAD_OK;
 }
 
 int cp_head_ctx_bytes(const cp_head_desc *desc, size_t *bytes)

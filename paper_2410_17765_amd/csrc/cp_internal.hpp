@@ -63,7 +63,7 @@ inline CtxLayout ctx_layout(const cp_head_desc &ds, bool fast)
 
 inline bool use_fast_path(const cp_head_desc &ds)
 {
-    return false && ds.dtype == CP_HEAD_BF16 && (ds.d % 64) == 0 && !(ds.flags & CP_HEAD_FORCE_GENERIC);
+    return ds.dtype == CP_HEAD_BF16 && (ds.d % 64) == 0 && !(ds.flags & CP_HEAD_FORCE_GENERIC);
 }
 
 // ---------------------------------------------------------------- generic (plain fp32) path
@@ -83,6 +83,17 @@ void launch_mixture(const cp_head_desc &ds, const float *logw, const float *C, f
 void launch_fill_zero(float *p, size_t count, hipStream_t st);
 void launch_pick_alpha(const cp_head_desc &ds, const float *w, const float *uniforms, int32_t *alpha,
                        hipStream_t st);
+
+// ---------------------------------------------------------------- optional per-kernel timing
+// While profiling is switched on (cp_head_profile_enable), a ProfileScope brackets a launch with a
+// pair of events on the launch stream and remembers the work it stands for.
+void profile_begin(const char *name, double work, hipStream_t st);
+void profile_end(hipStream_t st);
+struct ProfileScope {
+    hipStream_t st;
+    ProfileScope(const char *name, double work, hipStream_t s) : st(s) { profile_begin(name, work, s); }
+    ~ProfileScope() { profile_end(st); }
+};
 
 // ---------------------------------------------------------------- matrix-core path
 size_t fast_workspace_bytes(const cp_head_desc &ds, int op);

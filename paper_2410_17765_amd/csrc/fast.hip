@@ -1,8 +1,407 @@
-// Matrix-core path (placeholder until the MFMA kernels land).
-#include "cp_internal.hpp"
+// Matrix-core path of the CP head loss (bf16 storage, d a multiple of 64).
+//
+// Forward:   gate -> Y = H W^T (hi/lo bf16) -> z = Y U^T with a running-statistics epilogue
+//            (logits never stored) -> per-row log-normaliser and fp32 target logit -> mixture.
+// Backward:  per bounded chunk of head rows: recompute z, epilogue writes dz in bf16 ->
+//            dY = dz U and dU += dz^T Y; then dW = dY^T H, dH = dY W + G^T dg, dG = dg^T H.
+// All products run through the one NT main loop of gemm_nt.hpp; operands that are not
+// K-contiguous are transposed first (HBM-bound passes that cost a few percent of the GEMM time).
+#include "gemm_nt.hpp"
+
+#include <math.h>
+
 namespace cph {
-size_t fast_workspace_bytes(const cp_head_desc &, int) { return 256; }
-int fast_loss_fwd(const cp_head_desc &, const void *, const void *, const void *, const void *, const int32_t *, float *, void *, void *, size_t, hipStream_t) { return CP_HEAD_ERR_UNSUPPORTED; }
-int fast_loss_bwd(const cp_head_desc &, const void *, const void *, const void *, const void *, const int32_t *, const float *, float, const void *, float *, float *, float *, float *, void *, size_t, hipStream_t) { return CP_HEAD_ERR_UNSUPPORTED; }
-int fast_draft(const cp_head_desc &, const void *, const void *, const void *, const void *, const float *, int32_t *, int32_t *, float *, void *, size_t, hipStream_t) { return CP_HEAD_ERR_UNSUPPORTED; }
+
+namespace {
+
+typedef TileCfg<256, 256, 2, 2> Cfg;
+constexpr int kBlock = 256;
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+template <typename T>
+inline T *at(void *base, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(base) + off); }
+template <typename T>
+inline const T *at(const void *base, size_t off) { return reinterpret_cast<const T *>(static_cast<const char *>(base) + off); }
+
+// ------------------------------------------------------------------------------------------
+// epilogues
+// ------------------------------------------------------------------------------------------
+
+// bf16 store of the accumulators; optionally also the bf16 residual acc - bf16(acc), so that
+// hi + lo carries the fp32 value to about 2^-17 relative.  N and ldc are multiples of 8.
+struct EpiStoreBf16 {
+    bf16_t *hi;
+    bf16_t *lo;     // may be null
+    long ldc;
+    int M, N;
+    template <class C>
+    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    {
+        store_tile_bf16<C>(smem, wave, lane, row0, col0, M, N, hi, ldc,
+                           [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); });
+        if (lo)
+            store_tile_bf16<C>(smem, wave, lane, row0, col0, M, N, lo, ldc, [&](int i, int j, int v, int, int) {
+                const float a = acc[i][j][v];
+                return f32_to_bf16(a - bf16_to_f32(f32_to_bf16(a)));
+            });
+    }
+};
+
+// fp32 store, optionally accumulating onto what is already there (chunked sums).  N, ldc multiples of 4.
+struct EpiStoreF32 {
+    float *C;
+    long ldc;
+    int M, N;
+    int accumulate;
+    template <class Cf>
+    __device__ void run(f32x16_t (&acc)[Cf::TM][Cf::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    {
+        store_tile_f32<Cf>(smem, wave, lane, row0, col0, M, N, C, ldc, accumulate != 0,
+                           [&](int i, int j, int v, int, int) { return acc[i][j][v]; });
+    }
+};
+
+// Running statistics of the logits (eq. 5 in log space): for every row of the wavefront's
+// sub-tile the maximum and the sum of exp(z - max) over its columns.  One (max, sum) pair per
+// row and per (tile column, wavefront column) goes to `part`; the logits themselves are dropped.
+struct EpiRowStats {
+    float2 *part;   // [M, parts]
+    int parts;      // tiles_n * WN
+    int M, V;
+    template <class C>
+    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int tn, char *) const
+    {
+        const int slot = tn * C::WN + (wave % C::WN);
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j)
+                    if (col0 + acc_col(j, lane) < V) mx = fmaxf(mx, acc[i][j][v]);
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+                const float ref = (mx == -INFINITY) ? 0.f : mx;
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j)
+                    if (col0 + acc_col(j, lane) < V) s += __expf(acc[i][j][v] - ref);
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
+                const int r = row0 + acc_row(i, v, lane);
+                if ((lane & 31) == 0 && r < M) part[(size_t)r * parts + slot] = make_float2(mx, s);
+            }
+    }
+};
+
+// Softmax gradient (derivative of eq. 8/9 with respect to the logits), written in bf16:
+//   dz[m, v] = coef[m] * (exp(z - lse[m]) - 1[v = x_m]),  zero in the padding columns V..Vp-1
+struct EpiDz {
+    bf16_t *dZ;          // [Mc, Vp] for the chunk
+    long ldz;
+    const float *lse;    // chunk-relative
+    const float *coef;   // chunk-relative; already zero for dropped factors
+    const int32_t *X;    // whole array
+    size_t m0;           // first row of the chunk
+    int r;
+    int Mc, V, Vp;
+    template <class C>
+    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    {
+        const float *__restrict__ lse_ = lse;
+        const float *__restrict__ coef_ = coef;
+        const int32_t *__restrict__ X_ = X;
+        store_tile_bf16<C>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, [&](int i, int j, int v, int row, int col) {
+            const int rr = row < Mc ? row : Mc - 1;
+            const float l = lse_[rr], cf = coef_[rr];
+            const int x = X_[(m0 + rr) / r];
+            const float g = cf * (__expf(acc[i][j][v] - l) - (col == x ? 1.f : 0.f));
+            return f32_to_bf16(col < V ? g : 0.f);
+        });
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// small kernels around the GEMMs
+// ------------------------------------------------------------------------------------------
+
+// dst[c, r] = src[r, c] (bf16); dst rows are ldd long and columns R..Rp-1 are zero-filled.
+__global__ void __launch_bounds__(kBlock) k_transpose_bf16(const bf16_t *__restrict__ src, long lds_, int R, int C,
+                                                           bf16_t *__restrict__ dst, long ldd, int Rp, int tiles_c)
+{
+    __shared__ bf16_t tile[64][66];
+    const int tc = blockIdx.x % tiles_c, tr = blockIdx.x / tiles_c;
+    const int r0 = tr * 64, c0 = tc * 64;
+    const int lx = threadIdx.x & 63, ly = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = r0 + i * 4 + ly, c = c0 + lx;
+        tile[i * 4 + ly][lx] = (r < R && c < C) ? src[(size_t)r * lds_ + c] : (bf16_t)0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = c0 + i * 4 + ly, r = r0 + lx;
+        if (c < C && r < Rp) dst[(size_t)c * ldd + r] = tile[lx][i * 4 + ly];
+    }
 }
+
+void transpose_bf16(const bf16_t *src, long lds_, int R, int C, bf16_t *dst, long ldd, int Rp, hipStream_t st)
+{
+    ProfileScope prof("transpose", 2.0 * ((double)R * C + (double)Rp * C), st);   // work = bytes moved
+    const int tiles_c = (C + 63) / 64, tiles_r = (Rp + 63) / 64;
+    k_transpose_bf16<<<(unsigned)((size_t)tiles_c * tiles_r), kBlock, 0, st>>>(src, lds_, R, C, dst, ldd, Rp, tiles_c);
+}
+
+// Per head row: combine the per-tile statistics into the log-normaliser (eq. 5), take the
+// target logit as an fp32 dot product of U[x] with y = hi + lo, and form C = z[x] - lse (eq. 8).
+// One wavefront per row.
+__global__ void __launch_bounds__(kBlock) k_row_finish(size_t M, int d, int r, int parts,
+                                                       const float2 *__restrict__ part,
+                                                       const bf16_t *__restrict__ Yhi, const bf16_t *__restrict__ Ylo,
+                                                       const bf16_t *__restrict__ U, const int32_t *__restrict__ X,
+                                                       float *__restrict__ lse_out, float *__restrict__ C_out)
+{
+    const size_t m = (size_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const int lane = threadIdx.x & 63;
+    float mx = -INFINITY, l = 0.f;
+    for (int p = lane; p < parts; p += kWave) {
+        const float2 q = part[m * parts + p];
+        if (q.x > mx) { l = l * __expf(mx - q.x) + q.y; mx = q.x; }
+        else if (q.x != -INFINITY) l += q.y * __expf(q.x - mx);
+    }
+    const float Mx = wave_max(mx);
+    const float L = wave_sum(mx == -INFINITY ? 0.f : l * __expf(mx - Mx));
+    const float lse = Mx + logf(L);
+    const int x = X[m / r];
+    float zt = 0.f;
+    if (x >= 0) {
+        const bf16_t *u = U + (size_t)x * d, *yh = Yhi + m * d, *yl = Ylo + m * d;
+        for (int k = lane; k < d; k += kWave) zt += bf16_to_f32(u[k]) * (bf16_to_f32(yh[k]) + bf16_to_f32(yl[k]));
+        zt = wave_sum(zt);
+    }
+    if (lane == 0) {
+        lse_out[m] = lse;
+        C_out[m] = (x >= 0) ? zt - lse : 0.f;
+    }
+}
+
+// coef[m] = up_t * gamma[t, a] (zero for dropped factors); dg[t, a] = up_t (w - gamma)
+__global__ void k_bwd_coefficients(size_t M, int n, int r, const float *__restrict__ w, const float *__restrict__ gamma,
+                                   const float *__restrict__ dloss, float scale, const int32_t *__restrict__ X,
+                                   float *__restrict__ coef, float *__restrict__ dg)
+{
+    const size_t m = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= M) return;
+    const size_t t = m / ((size_t)n * r);
+    const int a = (int)(m % r);
+    const float up = dloss ? dloss[t] * scale : scale;
+    const float gm = gamma[t * r + a];
+    coef[m] = (X[m / r] >= 0) ? up * gm : 0.f;
+    if ((m / r) % n == 0) dg[t * r + a] = up * (w[t * r + a] - gm);
+}
+
+// dH[t, j] += sum_a dg[t, a] G[a, j]
+__global__ void k_add_gate_to_dh(size_t T, int d, int r, const bf16_t *__restrict__ G, const float *__restrict__ dg,
+                                 float *__restrict__ dH)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= T * d) return;
+    const size_t t = idx / d;
+    const int j = (int)(idx % d);
+    float acc = dH[idx];
+    for (int a = 0; a < r; ++a) acc += dg[t * r + a] * bf16_to_f32(G[(size_t)a * d + j]);
+    dH[idx] = acc;
+}
+
+// dG[a, j] = sum_t dg[t, a] H[t, j], summed in increasing t
+__global__ void k_dgate_weights(size_t T, int d, int r, const bf16_t *__restrict__ H, const float *__restrict__ dg,
+                                float *__restrict__ dG)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)r * d) return;
+    const int a = (int)(idx / d);
+    const int j = (int)(idx % d);
+    float acc = 0.f;
+    for (size_t t = 0; t < T; ++t) acc += dg[t * r + a] * bf16_to_f32(H[t * d + j]);
+    dG[idx] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
+// workspace layouts
+// ------------------------------------------------------------------------------------------
+
+struct FwdWs {
+    size_t logw, C, Ylo, part, total;
+    int parts;
+};
+inline FwdWs fwd_ws(const cp_head_desc &ds)
+{
+    FwdWs f;
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    f.parts = ((ds.V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    f.logw = take((size_t)ds.T * ds.r * 4);
+    f.C = take(M * 4);
+    f.Ylo = take(M * ds.d * 2);
+    f.part = take(M * f.parts * sizeof(float2));
+    f.total = off;
+    return f;
+}
+
+// Rows of logit gradients held at a time: about 2 GiB of bf16, a multiple of the tile height.
+inline size_t bwd_chunk_rows(const cp_head_desc &ds)
+{
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    const size_t Vp = round_up((size_t)ds.V, 64);
+    size_t rows = (((size_t)1 << 31) / (Vp * 2)) / Cfg::BM * Cfg::BM;
+    if (rows < (size_t)Cfg::BM || (ds.flags & CP_HEAD_MIN_WORKSPACE)) rows = Cfg::BM;
+    return rows < M ? rows : (M ? M : 1);
+}
+
+struct BwdWs {
+    size_t coef, dg, Ut, Wt, Ht, dY, dYt, dZ, dZt, Yt, total;
+    size_t Vp, Tp, chunk, chunk_p;
+};
+inline BwdWs bwd_ws(const cp_head_desc &ds)
+{
+    BwdWs b;
+    const size_t T = (size_t)ds.T, nrd = (size_t)ds.n * ds.r * ds.d, M = T * ds.n * ds.r;
+    b.Vp = round_up((size_t)ds.V, 64);
+    b.Tp = round_up(T, 64);
+    b.chunk = bwd_chunk_rows(ds);
+    b.chunk_p = round_up(b.chunk, 64);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    b.coef = take(M * 4);
+    b.dg = take(T * ds.r * 4);
+    b.Ut = take((size_t)ds.d * b.Vp * 2);
+    b.Wt = take((size_t)ds.d * nrd * 2);
+    b.Ht = take((size_t)ds.d * b.Tp * 2);
+    b.dY = take(M * ds.d * 2);
+    b.dYt = take(nrd * b.Tp * 2);
+    b.dZ = take(b.chunk * b.Vp * 2);
+    b.dZt = take((size_t)ds.V * b.chunk_p * 2);
+    b.Yt = take((size_t)ds.d * b.chunk_p * 2);
+    b.total = off;
+    return b;
+}
+
+inline bool dims_fit(const cp_head_desc &ds)
+{
+    // the GEMM addresses rows of a tile with 32-bit byte offsets and counts rows in int
+    const size_t nrd = (size_t)ds.n * ds.r * ds.d, M = (size_t)ds.T * ds.n * ds.r;
+    const size_t max_ld = nrd > (size_t)ds.V + 64 ? nrd : (size_t)ds.V + 64;
+    return M < ((size_t)1 << 31) && nrd < ((size_t)1 << 31) && max_ld * 2 * 256 < ((size_t)1 << 32) &&
+           ((size_t)ds.T + 64) * 2 * 256 < ((size_t)1 << 32);
+}
+
+}  // namespace
+
+size_t fast_workspace_bytes(const cp_head_desc &ds, int op)
+{
+    if (op == CP_HEAD_OP_LOSS_FWD) return fwd_ws(ds).total;
+    if (op == CP_HEAD_OP_LOSS_BWD) return bwd_ws(ds).total;
+    return generic_workspace_bytes(ds, op);
+}
+
+int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                  const int32_t *X, float *loss, void *ctx, void *ws, size_t, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv;
+    const CtxLayout cl = ctx_layout(ds, true);
+    const FwdWs f = fwd_ws(ds);
+    const int T = (int)ds.T, d = ds.d, V = ds.V;
+    const size_t M = (size_t)T * ds.n * ds.r;
+    const int nrd = ds.n * ds.r * d;
+    float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    bf16_t *Y = at<bf16_t>(ctx, cl.Y);
+    float *logw = at<float>(ws, f.logw), *C = at<float>(ws, f.C);
+    bf16_t *Ylo = at<bf16_t>(ws, f.Ylo);
+    float2 *part = at<float2>(ws, f.part);
+
+    launch_gate(ds, Hv, Gv, logw, w, st);                                                      // eq. 7
+    launch_gemm_nt<Cfg>("gemm_y", H, d, T, W, d, nrd, d, EpiStoreBf16{Y, Ylo, (long)nrd, T, nrd}, st);   // y = W_sa h
+    launch_gemm_nt<Cfg>("gemm_z_stats", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);  // z = U y, statistics
+    k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, ds.r, f.parts, part, Y, Ylo, U, X, lse, C);
+    launch_mixture(ds, logw, C, loss, gamma, st);                                              // eq. 9
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                  const int32_t *X, const float *dloss, float scale, const void *ctx, float *dH, float *dW,
+                  float *dU, float *dG, void *ws, size_t, hipStream_t st)
+{
+    const int d = ds.d, V = ds.V, r = ds.r, n = ds.n;
+    const size_t nrd = (size_t)n * r * d;
+    if (ds.T == 0) {
+        launch_fill_zero(dW, nrd * d, st);
+        launch_fill_zero(dU, (size_t)V * d, st);
+        launch_fill_zero(dG, (size_t)r * d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
+    const CtxLayout cl = ctx_layout(ds, true);
+    const BwdWs b = bwd_ws(ds);
+    const size_t T = (size_t)ds.T, M = T * n * r;
+    const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    const bf16_t *Y = at<bf16_t>(ctx, cl.Y);
+    float *coef = at<float>(ws, b.coef), *dg = at<float>(ws, b.dg);
+    bf16_t *Ut = at<bf16_t>(ws, b.Ut), *Wt = at<bf16_t>(ws, b.Wt), *Ht = at<bf16_t>(ws, b.Ht);
+    bf16_t *dY = at<bf16_t>(ws, b.dY), *dYt = at<bf16_t>(ws, b.dYt);
+    bf16_t *dZ = at<bf16_t>(ws, b.dZ), *dZt = at<bf16_t>(ws, b.dZt), *Yt = at<bf16_t>(ws, b.Yt);
+    const int Vp = (int)b.Vp, Tp = (int)b.Tp;
+
+    k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, dloss, scale, X, coef, dg);
+    transpose_bf16(U, d, V, d, Ut, Vp, Vp, st);                       // Ut[d, Vp]
+
+    int first = 1;
+    for (size_t m0 = 0; m0 < M; m0 += b.chunk) {
+        const int Mc = (int)((M - m0 < b.chunk) ? M - m0 : b.chunk);
+        const int Mcp = (int)round_up((size_t)Mc, 64);
+        const bf16_t *Yc = Y + m0 * d;
+        // recompute z for the chunk; the epilogue turns it into dz (bf16); the tiles over V also
+        // cover the padding columns V..Vp-1, which the epilogue zero-fills
+        launch_gemm_nt<Cfg>("gemm_z_dz", Yc, d, Mc, U, d, V, d,
+                            EpiDz{dZ, (long)Vp, lse + m0, coef + m0, X, m0, r, Mc, V, Vp}, st);
+        // dY = dz U   (contraction over the vocabulary)
+        launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, Vp, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st);
+        if (dU) {
+            // dU += dz^T Y   (contraction over the rows of the chunk)
+            transpose_bf16(dZ, Vp, Mc, V, dZt, Mcp, Mcp, st);         // dZt[V, Mcp]
+            transpose_bf16(Yc, d, Mc, d, Yt, Mcp, Mcp, st);           // Yt[d, Mcp]
+            launch_gemm_nt<Cfg>("gemm_du", dZt, Mcp, V, Yt, Mcp, d, Mcp, EpiStoreF32{dU, (long)d, V, d, first ? 0 : 1}, st);
+        }
+        first = 0;
+    }
+    // dH = dY W + G^T dg   (contraction over (s, a, k))
+    transpose_bf16(W, d, (int)nrd, d, Wt, (long)nrd, (int)nrd, st);   // Wt[d, nrd]
+    launch_gemm_nt<Cfg>("gemm_dh", dY, (long)nrd, (int)T, Wt, (long)nrd, d, (int)nrd, EpiStoreF32{dH, (long)d, (int)T, d, 0}, st);
+    k_add_gate_to_dh<<<blocks_for(T * d, kBlock), kBlock, 0, st>>>(T, d, r, G, dg, dH);
+    if (dW) {
+        // dW_sa = dY_sa^T H   (contraction over positions)
+        transpose_bf16(dY, (long)nrd, (int)T, (int)nrd, dYt, Tp, Tp, st);   // dYt[nrd, Tp]
+        transpose_bf16(H, d, (int)T, d, Ht, Tp, Tp, st);                    // Ht[d, Tp]
+        launch_gemm_nt<Cfg>("gemm_dw", dYt, Tp, (int)nrd, Ht, Tp, d, Tp, EpiStoreF32{dW, (long)d, (int)nrd, d, 0}, st);
+    }
+    if (dG) k_dgate_weights<<<blocks_for((size_t)r * d, kBlock), kBlock, 0, st>>>(T, d, r, H, dg, dG);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int fast_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+               const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, size_t,
+               hipStream_t st)
+{
+    if (ds.d > 16000) return CP_HEAD_ERR_UNSUPPORTED;   // the plain draft kernels keep one row of y in LDS
+    return generic_draft(ds, H, W, U, G, uniforms, alpha, tokens, logq, ws, st);
+}
+
+}  // namespace cph

@@ -14,11 +14,25 @@ from . import binding, synth
 
 
 def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
-    """Upload a float32 array whose values are exact in `dtype` ("fp32" or "bf16")."""
-    if dtype == "bf16":
-        bits = synth.bf16_bits(x).view(np.int16)
-        return torch.from_numpy(bits).to(device).view(torch.bfloat16).reshape(x.shape)
-    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device)
+    """Upload a float32 array whose values are exact in `dtype` ("fp32" or "bf16").
+
+    For bf16 the upper 16 bits of each float32 are the bfloat16 pattern; they are copied out in
+    bounded chunks (values that are not bf16-exact are rounded to nearest-even first)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype != "bf16":
+        return torch.from_numpy(x).to(device)
+    flat = x.reshape(-1)
+    out = torch.empty(flat.shape[0], dtype=torch.int16, device=device)
+    chunk = 1 << 24
+    for lo in range(0, flat.shape[0], chunk):
+        part = flat[lo:lo + chunk]
+        halves = part.view(np.uint16).reshape(-1, 2)        # little-endian: [:, 1] is the upper half
+        if halves[:, 0].any():
+            bits = synth.bf16_bits(part)
+        else:
+            bits = np.ascontiguousarray(halves[:, 1])
+        out[lo:lo + part.shape[0]] = torch.from_numpy(bits.view(np.int16)).to(device)
+    return out.view(torch.bfloat16).reshape(x.shape)
 
 
 def _scratch(nbytes: int, device) -> torch.Tensor:

@@ -96,53 +96,59 @@ def bf16_round(x: np.ndarray) -> np.ndarray:
     return bf16_bits_to_f32(bf16_bits(x))
 
 
-def _store(x: np.ndarray, dtype: str) -> np.ndarray:
-    if dtype == "bf16":
-        return bf16_round(x)
-    if dtype == "fp32":
-        return np.ascontiguousarray(x, dtype=np.float32)
-    raise ValueError(f"unknown storage dtype {dtype!r}")
-
-
 # ----------------------------------------------------------------------------
 # tensors
 # ----------------------------------------------------------------------------
 
-def _normal(seed: int, shape: Sequence[int], scale: float) -> np.ndarray:
-    """N(0, scale^2) float32 from a Philox stream, drawn in bounded chunks."""
+def _normal(seed: int, shape: Sequence[int], scale: float, dtype: str = "fp32") -> np.ndarray:
+    """N(0, scale^2) float32 from a Philox stream, scaled in float32 and (for bf16 storage) rounded
+    to bfloat16, nearest-even.  Drawn and rounded in bounded chunks with reused buffers."""
+    if dtype not in ("fp32", "bf16"):
+        raise ValueError(f"unknown storage dtype {dtype!r}")
     rng = np.random.Generator(np.random.Philox(seed))
     total = int(np.prod(shape))
     out = np.empty(total, dtype=np.float32)
-    chunk = 1 << 24
+    chunk = 1 << 22
+    buf = np.empty(min(chunk, max(total, 1)), dtype=np.float32)
+    tmp = np.empty(buf.shape, dtype=np.uint32)
     for lo in range(0, total, chunk):
-        hi = min(total, lo + chunk)
-        out[lo:hi] = rng.standard_normal(hi - lo, dtype=np.float32)
-    if scale != 1.0:
-        out *= np.float32(scale)
+        m = min(total, lo + chunk) - lo
+        b = buf[:m]
+        rng.standard_normal(m, dtype=np.float32, out=b)
+        if scale != 1.0:
+            b *= np.float32(scale)
+        if dtype == "bf16":
+            u, t = b.view(np.uint32), tmp[:m]
+            np.right_shift(u, np.uint32(16), out=t)
+            t &= np.uint32(1)
+            t += np.uint32(0x7FFF)
+            u += t
+            u &= np.uint32(0xFFFF0000)
+        out[lo:lo + m] = b
     return out.reshape(shape)
 
 
 def hidden(cfg: HeadConfig, positions: Optional[np.ndarray] = None) -> np.ndarray:
     """H[T,d] (or the rows listed in `positions`, taken from the full tensor)."""
-    H = _normal(SEED_H, (cfg.T, cfg.d), 1.0)
+    H = _normal(SEED_H, (cfg.T, cfg.d), 1.0, cfg.dtype)
     if positions is not None:
-        H = H[np.asarray(positions)]
-    return _store(H, cfg.dtype)
+        H = np.ascontiguousarray(H[np.asarray(positions)])
+    return H
 
 
 def head_weights(cfg: HeadConfig) -> np.ndarray:
     """W[n,r,d,d]; y = W[s,a] @ h."""
-    return _store(_normal(SEED_W, (cfg.n, cfg.r, cfg.d, cfg.d), cfg.d ** -0.5), cfg.dtype)
+    return _normal(SEED_W, (cfg.n, cfg.r, cfg.d, cfg.d), cfg.d ** -0.5, cfg.dtype)
 
 
 def unembedding(cfg: HeadConfig) -> np.ndarray:
     """U[V,d]."""
-    return _store(_normal(SEED_U, (cfg.V, cfg.d), cfg.u_scale * cfg.d ** -0.5), cfg.dtype)
+    return _normal(SEED_U, (cfg.V, cfg.d), cfg.u_scale * cfg.d ** -0.5, cfg.dtype)
 
 
 def gate(cfg: HeadConfig) -> np.ndarray:
     """G[r,d]."""
-    return _store(_normal(SEED_G, (cfg.r, cfg.d), cfg.d ** -0.5), cfg.dtype)
+    return _normal(SEED_G, (cfg.r, cfg.d), cfg.d ** -0.5, cfg.dtype)
 
 
 def vocabulary_permutation(V: int) -> np.ndarray:
