@@ -98,11 +98,12 @@ __device__ __forceinline__ void gemm_nt_mainloop(const GemmOperands &g, int tm, 
     const unsigned voff_b = (unsigned)lrow * (unsigned)g.ldb * 2u + lchunk * 16u;
     const unsigned pass_a = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.lda * 2u;
     const unsigned pass_b = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.ldb * 2u;
-    // LDS position of that chunk: rows are 128 bytes, the 16-byte chunk index is XORed with row%8
-    const int lds_w = lrow * 128 + ((lchunk ^ (lrow & 7)) << 4);
+    // LDS position of that chunk: rows are 128 bytes, the 16-byte chunk index is XORed with (row/2)%8,
+    // which spreads the 16 rows that one quarter-wavefront reads over all 64 banks
+    const int lds_w = lrow * 128 + ((lchunk ^ ((lrow >> 1) & 7)) << 4);
 
     // fragment reads: lane l reads row l%32 of a 32-row block, k-chunk 2*kk + l/32
-    const int frag_row = lane & 31, frag_half = lane >> 5, frag_sw = lane & 7;
+    const int frag_row = lane & 31, frag_half = lane >> 5, frag_sw = (lane >> 1) & 7;
     const int lds_ra = (wm0 + frag_row) * 128;
     const int lds_rb = Cfg::A_BYTES + (wn0 + frag_row) * 128;
 
@@ -164,20 +165,320 @@ __device__ __forceinline__ void gemm_nt_mainloop(const GemmOperands &g, int tm, 
     }
 }
 
+// Software-pipelined variant of the main loop.  One K-step of 64 is four MFMA phases of 16 MFMAs
+// per wavefront; fragments are double-buffered in registers so that the LDS reads of phase p+1,
+// the LDS writes of the next operand tile and the buffer loads of the tile after that are all
+// issued in the shadow of the MFMAs of phase p.  The single workgroup barrier of a K-step sits
+// between phases 2 and 3, so MFMAs are queued on both sides of it.  The loop body is branch-free:
+// loads past the end of K stay inside the buffer descriptor (or read as zero) and are never used.
+template <class Cfg>
+__device__ __forceinline__ void gemm_nt_mainloop_pipelined(const GemmOperands &g, int tm, int tn, char *smem,
+                                                           f32x16_t (&acc)[Cfg::TM][Cfg::TN])
+{
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
+    static_assert(BK == 64, "four phases of k = 16");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / Cfg::WN) * Cfg::WTM;
+    const int wn0 = (wave % Cfg::WN) * Cfg::WTN;
+
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int rows_a = min(BM, g.M - m0), rows_b = min(BN, g.N - n0);
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A + (size_t)m0 * g.lda, (unsigned)((size_t)rows_a * g.lda * 2));
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.B + (size_t)n0 * g.ldb, (unsigned)((size_t)rows_b * g.ldb * 2));
+
+    const int lrow = tid >> 3, lchunk = tid & 7;
+    const unsigned voff_a = (unsigned)lrow * (unsigned)g.lda * 2u + lchunk * 16u;
+    const unsigned voff_b = (unsigned)lrow * (unsigned)g.ldb * 2u + lchunk * 16u;
+    const unsigned pass_a = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.lda * 2u;
+    const unsigned pass_b = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.ldb * 2u;
+    const int lds_w = lrow * 128 + ((lchunk ^ ((lrow >> 1) & 7)) << 4);
+
+    const int frag_row = lane & 31, frag_half = lane >> 5, frag_sw = (lane >> 1) & 7;
+    const int lds_ra = (wm0 + frag_row) * 128;
+    const int lds_rb = Cfg::A_BYTES + (wn0 + frag_row) * 128;
+    int coff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) coff[kk] = ((kk * 2 + frag_half) ^ frag_sw) << 4;
+
+    // two sets of staging registers: while one operand tile moves from registers to LDS the loads
+    // of the next two tiles are in flight (about 128 KB per compute unit)
+    u32x4_t sa[2][Cfg::A_PASSES], sb[2][Cfg::B_PASSES];
+    bf16x8_t fa[2][TM], fb[2][TN];
+
+    auto load_global = [&](int kt, int set) {
+        const int soff = kt * BK * 2;
+#pragma unroll
+        for (int p = 0; p < Cfg::A_PASSES; ++p)
+            sa[set][p] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(voff_a + p * pass_a), soff, 0);
+#pragma unroll
+        for (int p = 0; p < Cfg::B_PASSES; ++p)
+            sb[set][p] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(voff_b + p * pass_b), soff, 0);
+    };
+    auto store_lds = [&](int stage, int set) {
+        char *base = smem + stage * Cfg::STAGE_BYTES + lds_w;
+#pragma unroll
+        for (int p = 0; p < Cfg::A_PASSES; ++p)
+            *reinterpret_cast<u32x4_t *>(base + p * Cfg::ROWS_PER_PASS * 128) = sa[set][p];
+#pragma unroll
+        for (int p = 0; p < Cfg::B_PASSES; ++p)
+            *reinterpret_cast<u32x4_t *>(base + Cfg::A_BYTES + p * Cfg::ROWS_PER_PASS * 128) = sb[set][p];
+    };
+    auto keep_alive = [&](int set) {
+#pragma unroll
+        for (int p = 0; p < Cfg::A_PASSES; ++p) asm volatile("" ::"v"(sa[set][p]));
+#pragma unroll
+        for (int p = 0; p < Cfg::B_PASSES; ++p) asm volatile("" ::"v"(sb[set][p]));
+    };
+    auto load_frags = [&](const char *st, int kk, int buf) {
+        fa[buf][0] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + coff[kk]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[buf][j] = *reinterpret_cast<const bf16x8_t *>(st + lds_rb + j * 32 * 128 + coff[kk]);
+#pragma unroll
+        for (int i = 1; i < TM; ++i)
+            fa[buf][i] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + i * 32 * 128 + coff[kk]);
+    };
+    auto mfmas = [&](int buf) {
+#ifndef CPH_DBG_NO_MFMA
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+#endif
+    };
+    // issue order inside one phase: after every few MFMAs one LDS read and a share of the other memory operations
+    constexpr int kMfma = 0x008, kVmemRead = 0x020, kDsRead = 0x100, kDsWrite = 0x200;
+    constexpr int kReads = TM + TN, kMfmaN = TM * TN;
+#ifdef CPH_NO_SCHED
+#define CPH_PHASE_ORDER(OTHER_MASK, OTHER_TOTAL)
+#else
+#define CPH_PHASE_ORDER(OTHER_MASK, OTHER_TOTAL)                                                   \
+    _Pragma("unroll") for (int q = 0; q < kReads; ++q) {                                           \
+        __builtin_amdgcn_sched_group_barrier(kMfma, kMfmaN / kReads, 0);                           \
+        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);                                       \
+        if ((OTHER_TOTAL) > 0) __builtin_amdgcn_sched_group_barrier(OTHER_MASK, (OTHER_TOTAL) / kReads, 0); \
+    }
+#endif
+    // one K-step: compute on stage `cur`, move tile kt+1 (register set `set`) into the other stage,
+    // then refill that register set with tile kt+3
+#if !defined(CPH_DBG_NO_GLOBAL) && !defined(CPH_DBG_NO_DSWRITE)
+#define CPH_DBG_DSWRITE(x) x
+#elif defined(CPH_DBG_NO_DSWRITE)
+#define CPH_DBG_DSWRITE(x) keep_alive(SET_);
+#else
+#define CPH_DBG_DSWRITE(x)
+#endif
+#if !defined(CPH_DBG_NO_GLOBAL) && !defined(CPH_DBG_NO_VMEM)
+#define CPH_DBG_VMEM(x) x
+#else
+#define CPH_DBG_VMEM(x)
+#endif
+#ifndef CPH_DBG_NO_FRAGS
+#define CPH_DBG_FRAGS(x) x
+#else
+#define CPH_DBG_FRAGS(x)
+#endif
+#define CPH_K_STEP(KT_, CUR, SET)                                                                  \
+    {                                                                                              \
+        constexpr int SET_ = SET;                                                                  \
+        const char *st = smem + (CUR) * Cfg::STAGE_BYTES;                                          \
+        const char *nx = smem + ((CUR) ^ 1) * Cfg::STAGE_BYTES;                                    \
+        CPH_DBG_FRAGS(load_frags(st, 1, 1);)                                                       \
+        CPH_DBG_DSWRITE(store_lds((CUR) ^ 1, SET);)                                                \
+        mfmas(0);                                                                                  \
+        CPH_PHASE_ORDER(kDsWrite, Cfg::A_PASSES + Cfg::B_PASSES)                                   \
+        CPH_DBG_FRAGS(load_frags(st, 2, 0);)                                                       \
+        CPH_DBG_VMEM(load_global((KT_) + 3, SET);)                                                 \
+        mfmas(1);                                                                                  \
+        CPH_PHASE_ORDER(kVmemRead, Cfg::A_PASSES + Cfg::B_PASSES)                                  \
+        CPH_DBG_FRAGS(load_frags(st, 3, 1);)                                                       \
+        mfmas(0);                                                                                  \
+        CPH_PHASE_ORDER(0, 0)                                                                      \
+        __syncthreads(); /* the other stage is complete and nobody reads this one any more */     \
+        CPH_DBG_FRAGS(load_frags(nx, 0, 0);)                                                       \
+        mfmas(1);                                                                                  \
+        CPH_PHASE_ORDER(0, 0)                                                                      \
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int KT = g.K / BK;
+    load_global(0, 0);
+    store_lds(0, 0);
+    __syncthreads();
+    load_global(1, 0);
+    load_global(2, 1);
+    load_frags(smem, 0, 0);
+
+    int kt = 0;
+    for (; kt + 1 < KT; kt += 2) {
+        CPH_K_STEP(kt, 0, 0)
+        CPH_K_STEP(kt + 1, 1, 1)
+    }
+    if (kt < KT) CPH_K_STEP(kt, 0, 0)
+#undef CPH_K_STEP
+#undef CPH_PHASE_ORDER
+}
+
+// Main loop with direct global->LDS loads (no staging registers, no LDS write instructions).
+// Each wavefront load instruction moves 64 x 16 bytes = 8 operand rows of 128 bytes into 1 KB of
+// consecutive LDS; the XOR swizzle is realised by permuting which 16-byte chunk of its row each
+// lane fetches.
+//
+// Schedule of one K-step of 64 (stage s = kt & 1), four phases of 16 MFMAs per wavefront:
+//   phase 0   MFMAs k 0..15    + LDS reads of the k 16..31 fragments + 2nd half of the loads of tile kt+1
+//   phase 1   MFMAs k 16..31   + LDS reads of the k 32..47 fragments
+//   phase 2   MFMAs k 32..47   + LDS reads of the k 48..63 fragments
+//   wait for tile kt+1, workgroup barrier (stage s is dead from here on)
+//   phase 3   MFMAs k 48..63   + LDS reads of the first fragments of tile kt+1 + 1st half of the loads of tile kt+2
+// Memory instructions are issued one at a time between MFMAs (the order is pinned with scheduling
+// barriers): a wavefront issues in order, so a cluster of loads would hold back its MFMAs.
+template <class Cfg>
+__device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, int tm, int tn, char *smem,
+                                                        f32x16_t (&acc)[Cfg::TM][Cfg::TN])
+{
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int NLOAD = Cfg::A_PASSES + Cfg::B_PASSES;     // direct loads per wavefront and K-step
+    constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
+    static_assert(BK == 64, "four phases of k = 16");
+    static_assert(NMFMA % NFRAG == 0 && NLOAD % 2 == 0 && NLOAD / 2 <= NFRAG, "schedule slots");
+    typedef __attribute__((address_space(3))) void lds_void;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave / Cfg::WN) * Cfg::WTM;
+    const int wn0 = (wave % Cfg::WN) * Cfg::WTN;
+
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int rows_a = min(BM, g.M - m0), rows_b = min(BN, g.N - n0);
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A + (size_t)m0 * g.lda, (unsigned)((size_t)rows_a * g.lda * 2));
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.B + (size_t)n0 * g.ldb, (unsigned)((size_t)rows_b * g.ldb * 2));
+
+    // lane -> (row, physical chunk) inside a pass; the lane fetches the global chunk that belongs there
+    const int lrow = tid >> 3, pchunk = tid & 7;
+    const int gchunk = pchunk ^ ((lrow >> 1) & 7);
+    const unsigned voff_a = (unsigned)lrow * (unsigned)g.lda * 2u + gchunk * 16u;
+    const unsigned voff_b = (unsigned)lrow * (unsigned)g.ldb * 2u + gchunk * 16u;
+    const unsigned pass_a = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.lda * 2u;
+    const unsigned pass_b = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.ldb * 2u;
+    const int lds_wave = wave * 8 * 128;     // this wavefront's 1 KB slot inside a pass of 32 rows
+
+    const int frag_row = lane & 31, frag_half = lane >> 5, frag_sw = (lane >> 1) & 7;
+    const int lds_ra = (wm0 + frag_row) * 128;
+    const int lds_rb = Cfg::A_BYTES + (wn0 + frag_row) * 128;
+    int coff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) coff[kk] = ((kk * 2 + frag_half) ^ frag_sw) << 4;
+
+    bf16x8_t fa[2][TM], fb[2][TN];
+
+    // load number q of a K-step: q < A_PASSES moves 32 rows of A, the rest 32 rows of B
+    auto load_one = [&](int kt, int stage, int q) {
+        const int soff = kt * BK * 2;
+        char *base = smem + stage * Cfg::STAGE_BYTES + lds_wave;
+        if (q < Cfg::A_PASSES)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void *)(base + q * Cfg::ROWS_PER_PASS * 128), 16,
+                                                     (int)(voff_a + q * pass_a), soff, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rb, (lds_void *)(base + Cfg::A_BYTES + (q - Cfg::A_PASSES) * Cfg::ROWS_PER_PASS * 128), 16,
+                (int)(voff_b + (q - Cfg::A_PASSES) * pass_b), soff, 0, 0);
+    };
+    // fragment number q of a phase, in the order the MFMAs need them: A0, B0..B(TN-1), A1..A(TM-1)
+    auto frag_one = [&](const char *st, int kk, int buf, int q) {
+        if (q == 0) fa[buf][0] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + coff[kk]);
+        else if (q <= TN) fb[buf][q - 1] = *reinterpret_cast<const bf16x8_t *>(st + lds_rb + (q - 1) * 32 * 128 + coff[kk]);
+        else fa[buf][q - TN] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + (q - TN) * 32 * 128 + coff[kk]);
+    };
+    auto mfma_one = [&](int buf, int idx) {
+        const int i = idx / TN, j = idx % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    };
+#define CPH_PIN() __builtin_amdgcn_sched_barrier(0)
+    // one phase: MFMAs on fragment buffer BUF, fragments of (ST, KK) into the other buffer and,
+    // if LOAD_KT >= 0, the loads LOAD_Q0 .. LOAD_Q0 + NLOAD/2 - 1 of tile LOAD_KT into LOAD_STAGE
+#define CPH_PHASE(BUF, ST, KK, DO_LOAD, LOAD_KT, LOAD_STAGE, LOAD_Q0)                              \
+    _Pragma("unroll") for (int q = 0; q < NFRAG; ++q) {                                            \
+        _Pragma("unroll") for (int e = 0; e < NMFMA / NFRAG; ++e) {                                \
+            mfma_one(BUF, q * (NMFMA / NFRAG) + e);                                                \
+            if (e == 0 && (DO_LOAD) && q < NLOAD / 2) { CPH_PIN(); load_one(LOAD_KT, LOAD_STAGE, (LOAD_Q0) + q); } \
+            CPH_PIN();                                                                             \
+        }                                                                                          \
+        frag_one(ST, KK, (BUF) ^ 1, q);                                                            \
+        CPH_PIN();                                                                                 \
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int KT = g.K / BK;
+#pragma unroll
+    for (int q = 0; q < NLOAD; ++q) load_one(0, 0, q);
+#pragma unroll
+    for (int q = 0; q < NLOAD / 2; ++q) load_one(1, 1, q);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (NLOAD / 2));   // vmcnt(NLOAD/2): tile 0 has landed
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < NFRAG; ++q) frag_one(smem, 0, 0, q);
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        const char *st = smem + cur * Cfg::STAGE_BYTES;
+        const char *nx = smem + (cur ^ 1) * Cfg::STAGE_BYTES;
+        CPH_PHASE(0, st, 1, true, kt + 1, cur ^ 1, NLOAD / 2)
+        CPH_PHASE(1, st, 2, false, 0, 0, 0)
+        CPH_PHASE(0, st, 3, false, 0, 0, 0)
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): tile kt+1 is complete in the other stage
+        __syncthreads();
+        CPH_PHASE(1, nx, 0, true, kt + 2, cur, 0)
+    }
+#undef CPH_PHASE
+#undef CPH_PIN
+}
+
 // Generic kernel: main loop + epilogue functor.  Epi::operator() receives the accumulators of one
 // wavefront together with the global row/column of its sub-tile's origin.
+#ifdef CPH_DBG_CLOCK
+__device__ long long g_dbg_clk[2];
+#endif
 template <class Cfg, class Epi>
 __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi epi)
 {
     __shared__ __attribute__((aligned(16))) char smem[Cfg::LDS_BYTES];
     int tm, tn;
     if (!tile_of_block(blockIdx.x, gridDim.x, g.tiles_m, g.tiles_n, tm, tn)) return;
+#ifdef CPH_DBG_CLOCK
+    const long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
+#endif
     f32x16_t acc[Cfg::TM][Cfg::TN];
+#if defined(CPH_MAINLOOP_SIMPLE)
     gemm_nt_mainloop<Cfg>(g, tm, tn, smem, acc);
+#elif defined(CPH_MAINLOOP_STAGED)
+    gemm_nt_mainloop_pipelined<Cfg>(g, tm, tn, smem, acc);
+#else
+    gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
+#endif
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int row0 = tm * Cfg::BM + (wave / Cfg::WN) * Cfg::WTM;
     const int col0 = tn * Cfg::BN + (wave % Cfg::WN) * Cfg::WTN;
     epi.template run<Cfg>(acc, row0, col0, lane, wave, tn, smem);
+#ifdef CPH_DBG_CLOCK
+    if (blockIdx.x == 8 * 100 && threadIdx.x == 0) {
+        g_dbg_clk[0] = clock64() - dbg_c0;
+        g_dbg_clk[1] = wall_clock64() - dbg_w0;
+    }
+#endif
 }
 
 template <class Cfg, class Epi>

@@ -1,0 +1,124 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times (fast path,
+default workspace, dloss = NULL with scale = 1/T).
+
+The fp64 oracle cannot run a full configuration, so:
+* per-position outputs (loss, rows of dH) are compared on a seeded subset S of positions;
+* weight gradients are compared on a second GPU call with exactly the positions of S (T = |S|),
+  whose sums the oracle can form, and the full-T weight gradients are tied to that by
+  self-consistency on the GPU: the gradient of the full batch equals the sum of the gradients of
+  its two halves, and the zero-sum invariants of the softmax and gate gradients hold.
+"""
+import numpy as np
+import pytest
+
+from paper_2410_17765_amd import synth
+from tests.helpers import GRAD_REL_FRO, LOSS_ATOL, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+SUBSET = 8
+
+
+class FullRun:
+    """One full-size forward+backward on the GPU, kept for the tests of a module run."""
+
+    def __init__(self, name):
+        import torch
+        from paper_2410_17765_amd import head
+        self.torch = torch
+        self.cfg = synth.CONFIGS[name]
+        cfg = self.cfg
+        print(f"[full-size] generating {name}", flush=True)
+        self.inp = synth.make_inputs(cfg)
+        self.head = head.CpHead(self.inp["W"], self.inp["U"], self.inp["G"], dtype=cfg.dtype)
+        self.H = head.to_device(self.inp["H"], cfg.dtype)
+        self.X = torch.from_numpy(self.inp["X"]).cuda()
+        self.scale = 1.0 / cfg.T
+        print(f"[full-size] running {name} on the GPU", flush=True)
+        self.loss = self.head.loss_fwd(self.H, self.X)
+        self.grads = self.head.loss_bwd(self.H, self.X, None, scale=self.scale)
+        torch.cuda.synchronize()
+        self.sel = synth.position_subset(cfg.T, SUBSET)
+
+    def run_rows(self, lo, hi):
+        H, X = self.H[lo:hi].contiguous(), self.X[lo:hi].contiguous()
+        self.head.loss_fwd(H, X)
+        g = self.head.loss_bwd(H, X, None, scale=self.scale)
+        self.torch.cuda.synchronize()
+        return g
+
+
+NAMES = ["small_lm", "head_7b", "large_vocab"]
+
+
+@pytest.fixture(scope="module", params=NAMES)
+def run(request):
+    """One configuration resident at a time; pytest groups the tests by this parameter."""
+    import gc
+    import torch
+    gc.collect()
+    torch.cuda.empty_cache()
+    r = FullRun(request.param)
+    yield r
+    del r
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def test_generate_and_run(run):
+    assert bool(run.torch.isfinite(run.loss).all())
+
+
+def test_loss_on_sampled_positions(oracle, run):
+    inp, sel, name = run.inp, run.sel, run.cfg.name
+    print(f"[full-size] oracle forward on {len(sel)} positions of {name}", flush=True)
+    ref = oracle.loss_fwd(inp["H"][sel], inp["W"], inp["U"], inp["G"], inp["X"][sel])
+    got = run.loss.cpu().numpy()[sel]
+    err = np.abs(got - ref).max()
+    print(f"  loss max abs err {err:.3e} (mean loss {ref.mean():.3f})", flush=True)
+    assert err <= LOSS_ATOL
+
+
+def test_gradients_on_sampled_positions(oracle, run):
+    inp, sel, cfg, name = run.inp, run.sel, run.cfg, run.cfg.name
+    print(f"[full-size] oracle backward on {len(sel)} positions of {name}", flush=True)
+    dloss = np.full(len(sel), run.scale)
+    ref = oracle.loss_bwd(inp["H"][sel], inp["W"], inp["U"], inp["G"], inp["X"][sel], dloss)
+    # rows of dH are per-position: compare the full run's rows directly
+    got_dH = run.grads["dH"][run.torch.from_numpy(sel).cuda()].cpu().numpy()
+    e = rel_fro(got_dH, ref["dH"])
+    print(f"  dH rows rel fro {e:.3e}", flush=True)
+    assert e <= GRAD_REL_FRO
+    # weight gradients: a GPU call on exactly these positions
+    import torch
+    from paper_2410_17765_amd import head
+    Hs = head.to_device(inp["H"][sel], cfg.dtype)
+    Xs = torch.from_numpy(inp["X"][sel]).cuda()
+    run.head.loss_fwd(Hs, Xs)
+    g = run.head.loss_bwd(Hs, Xs, None, scale=run.scale)
+    torch.cuda.synchronize()
+    for k in ("dW", "dU", "dG", "dH"):
+        e = rel_fro(g[k].cpu().numpy(), ref[k])
+        print(f"  subset {k} rel fro {e:.3e}", flush=True)
+        assert e <= GRAD_REL_FRO, k
+
+
+def test_full_batch_gradients_are_consistent(run):
+    cfg, torch = run.cfg, run.torch
+    g = run.grads
+    # zero-sum invariants: sum_v dz_v = 0 for every row, sum_a dg_a = 0 for every position
+    for k in ("dU", "dG"):
+        col_sum = g[k].double().sum(dim=0)
+        scale = g[k].double().abs().sum(dim=0) + 1e-30
+        assert float((col_sum.abs() / scale).max()) < 2e-2, k
+    # the batch gradient is the sum of the gradients of its halves
+    half = cfg.T // 2
+    ga = {k: v.clone() for k, v in run.run_rows(0, half).items() if k != "dH"}
+    gb = run.run_rows(half, cfg.T)
+    for k in ("dW", "dU", "dG"):
+        tot = ga[k] + gb[k]
+        num = float((tot - g[k]).double().norm())
+        den = float(g[k].double().norm())
+        print(f"  {k}: |full - (first half + second half)| / |full| = {num / den:.3e}", flush=True)
+        assert num / den <= 2e-3, k
+    assert float((gb["dH"] - g["dH"][half:]).double().norm() / g["dH"][half:].double().norm()) <= 2e-3
