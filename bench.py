@@ -21,6 +21,15 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy) from the rocprofv3 --pmc
+# runs summarised in profiles/loss_head_7b_kernel_stats.md; kernels whose counters were not separated
+# there report null.
+GIB = float(1 << 30)
+TRAFFIC_BYTES = {
+    ("head_7b", "gemm_z_stats"): (253.510 + 1.292) * GIB,
+    ("head_7b", "gemm_z_dz"): (14.981 + 1.953) * GIB,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -30,7 +39,7 @@ def parse():
     ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads) or 'draft'")
     ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per thread)")
+    ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per two threads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
     return ap.parse_args()
 
@@ -42,7 +51,7 @@ def cpu_baseline_loss(cfg, inp, positions):
     from paper_2410_17765_amd import synth
     cp_oracle.build()
     cores = cp_oracle.num_threads()
-    S = positions or cores
+    S = positions or max(1, cores // 2)
     sel = synth.position_subset(cfg.T, S)
     H, X = inp["H"][sel], inp["X"][sel]
     t0 = time.time()
@@ -107,8 +116,8 @@ def bench_loss(args):
     dom = max(gemms, key=lambda k: k[2])
     achieved = dom[3] / (dom[2] * 1e-3) / 1e12
     roof = {"bound": "mfma", "kernel": dom[0], "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-            "launches": dom[1], "avg_ms": dom[2] / dom[1]}
+            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get((cfg.name, dom[0])),
+            "traffic_unit": "bytes per launch", "launches": dom[1], "avg_ms": dom[2] / dom[1]}
     model_flops = 6.0 * cfg.n * cfg.r * cfg.d * (cfg.d + cfg.V) * cfg.T
     if args.frozen_u:
         model_flops = 2.0 * cfg.n * cfg.r * cfg.d * (3 * cfg.d + 2 * cfg.V) * cfg.T
