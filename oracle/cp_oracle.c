@@ -90,15 +90,29 @@ static void gate_logw(const cpo_shape *sh, const in_t *h, const in_t *G, double 
     for (int a = 0; a < sh->r; ++a) logw[a] -= lse;
 }
 
-/* y = W_sa h  (W_sa is d x d, row = output feature) */
-static void head_y(const cpo_shape *sh, const in_t *h, const in_t *W, int s, int a, double *y)
+/*
+ * y = W_sa h  (W_sa is d x d, row = output feature).
+ * With round_y the result is rounded to bfloat16.  Rounding is discontinuous: an element that lies
+ * within accumulation error of a rounding midpoint may legitimately land on either neighbour in an
+ * implementation that accumulates in fp32.  For tests of such cases the exact y can be returned
+ * (y_exact, may be NULL) and a caller-chosen nudge (may be NULL) is added before rounding.
+ */
+static void head_y_ex(const cpo_shape *sh, const in_t *h, const in_t *W, int s, int a,
+                      const double *nudge, double *y_exact, double *y)
 {
     const in_t *Wsa = W + ((size_t)s * sh->r + a) * sh->d * sh->d;
     for (int k = 0; k < sh->d; ++k) {
         double acc = 0.0;
         for (int j = 0; j < sh->d; ++j) acc += (double)Wsa[(size_t)k * sh->d + j] * (double)h[j];
+        if (y_exact) y_exact[k] = acc;
+        if (nudge) acc += nudge[k];
         y[k] = sh->round_y ? round_to_bf16(acc) : acc;
     }
+}
+
+static void head_y(const cpo_shape *sh, const in_t *h, const in_t *W, int s, int a, double *y)
+{
+    head_y_ex(sh, h, W, s, a, NULL, NULL, y);
 }
 
 /* z = U y  (U is V x d) */
@@ -379,12 +393,15 @@ static int inverse_cdf(const double *p, int len, double u, double *cdf_out)
  *   alpha[B], tokens[B,n]: the draw.  logq[B] (may be NULL): eq. 9 evaluated at
  *   the drawn tuple, over all experts.
  *   cdf_w[B,r], cdf_tok[B,n,V] (may be NULL): the running sums the draw used.
+ *   y_exact[B,n,r,d] (may be NULL): y before rounding; y_nudge[B,n,r,d] (may be NULL): added to y
+ *   before rounding (see head_y_ex).
  *
  * Inverse-CDF convention: index order, first index with cdf > u, clamp to last.
  */
 int CPO(draft_sample)(const cpo_shape *sh, const in_t *H, const in_t *W, const in_t *U, const in_t *G,
                       const double *uniforms, const int32_t *alpha_in,
-                      int32_t *alpha, int32_t *tokens, double *logq, double *cdf_w, double *cdf_tok)
+                      int32_t *alpha, int32_t *tokens, double *logq, double *cdf_w, double *cdf_tok,
+                      double *y_exact, const double *y_nudge)
 {
     const int d = sh->d, V = sh->V, n = sh->n, r = sh->r;
     const size_t nr = (size_t)n * r;
@@ -412,7 +429,9 @@ int CPO(draft_sample)(const cpo_shape *sh, const in_t *H, const in_t *W, const i
                 for (int s = 0; s < n; ++s)
                     for (int al = 0; al < r; ++al) {
                         double *z = zs + ((size_t)s * r + al) * V;
-                        head_y(sh, h, W, s, al, y);
+                        size_t row = ((size_t)b * n + s) * r + al;
+                        head_y_ex(sh, h, W, s, al, y_nudge ? y_nudge + row * d : NULL,
+                                  y_exact ? y_exact + row * d : NULL, y);
                         head_z(sh, U, y, z);
                         double l = logsumexp(z, V);
                         for (int v = 0; v < V; ++v) z[v] -= l;

@@ -137,8 +137,10 @@ def loss_bwd(H, W, U, G, X, dloss=None, want=("dH", "dW", "dU", "dG")):
     return {k: v for k, v in out.items() if v is not None}
 
 
-def draft_sample(H, W, U, G, uniforms, round_y: bool = True, alpha_in=None, want_cdf: bool = False):
-    """Draw (alpha[B], tokens[B,n], logq[B]); with want_cdf also cdf_w[B,r], cdf_tok[B,n,V]."""
+def draft_sample(H, W, U, G, uniforms, round_y: bool = True, alpha_in=None, want_cdf: bool = False,
+                 want_y: bool = False, y_nudge=None):
+    """Draw (alpha[B], tokens[B,n], logq[B]); with want_cdf also cdf_w[B,r], cdf_tok[B,n,V]; with want_y
+    also the exact y[B,n,r,d] before rounding.  y_nudge[B,n,r,d] is added to y before rounding."""
     kind, (H, W, U, G) = _prep(H, W, U, G)
     sh = _shape(H, W, U, round_y)
     u = np.ascontiguousarray(uniforms, dtype=np.float64)
@@ -149,15 +151,21 @@ def draft_sample(H, W, U, G, uniforms, round_y: bool = True, alpha_in=None, want
     logq = np.empty(sh.T, dtype=np.float64)
     cdf_w = np.empty((sh.T, sh.r)) if want_cdf else None
     cdf_tok = np.empty((sh.T, sh.n, sh.V)) if want_cdf else None
+    y_exact = np.empty((sh.T, sh.n, sh.r, sh.d)) if want_y else None
+    nudge = None if y_nudge is None else np.ascontiguousarray(y_nudge, dtype=np.float64)
+    assert nudge is None or nudge.shape == (sh.T, sh.n, sh.r, sh.d)
     fn = getattr(_lib(kind), f"cpo_{kind}_draft_sample")
     fn.restype = ctypes.c_int
     rc = fn(ctypes.byref(sh), _p(H), _p(W), _p(U), _p(G), _p(u), _p(a_in),
-            _p(alpha), _p(tokens), _p(logq), _p(cdf_w), _p(cdf_tok))
+            _p(alpha), _p(tokens), _p(logq), _p(cdf_w), _p(cdf_tok), _p(y_exact), _p(nudge))
     if rc != 0:
         raise RuntimeError("oracle draft_sample failed")
+    out = [alpha, tokens, logq]
     if want_cdf:
-        return alpha, tokens, logq, cdf_w, cdf_tok
-    return alpha, tokens, logq
+        out += [cdf_w, cdf_tok]
+    if want_y:
+        out.append(y_exact)
+    return tuple(out)
 
 
 def sequential_conditional(H, W, U, G, t: int, prefix):

@@ -157,37 +157,137 @@ void transpose_bf16(const bf16_t *src, long lds_, int R, int C, bf16_t *dst, lon
 }
 
 // Per head row: combine the per-tile statistics into the log-normaliser (eq. 5), take the
-// target logit as an fp32 dot product of U[x] with y = hi + lo, and form C = z[x] - lse (eq. 8).
-// One wavefront per row.
+// target logit as an fp32 dot product of U[x] with y = hi (+ lo), and form C = z[x] - lse (eq. 8).
+// One wavefront per row.  part == NULL: the log-normaliser is read from lse_io instead of being
+// computed.  X == NULL: only the log-normaliser is produced.  Ylo == NULL: y = hi.
 __global__ void __launch_bounds__(kBlock) k_row_finish(size_t M, int d, int r, int parts,
                                                        const float2 *__restrict__ part,
                                                        const bf16_t *__restrict__ Yhi, const bf16_t *__restrict__ Ylo,
                                                        const bf16_t *__restrict__ U, const int32_t *__restrict__ X,
-                                                       float *__restrict__ lse_out, float *__restrict__ C_out)
+                                                       float *__restrict__ lse_io, float *__restrict__ C_out)
 {
     const size_t m = (size_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
     if (m >= M) return;
     const int lane = threadIdx.x & 63;
-    float mx = -INFINITY, l = 0.f;
-    for (int p = lane; p < parts; p += kWave) {
-        const float2 q = part[m * parts + p];
-        if (q.x > mx) { l = l * __expf(mx - q.x) + q.y; mx = q.x; }
-        else if (q.x != -INFINITY) l += q.y * __expf(q.x - mx);
+    float lse;
+    if (part) {
+        float mx = -INFINITY, l = 0.f;
+        for (int p = lane; p < parts; p += kWave) {
+            const float2 q = part[m * parts + p];
+            if (q.x > mx) { l = l * __expf(mx - q.x) + q.y; mx = q.x; }
+            else if (q.x != -INFINITY) l += q.y * __expf(q.x - mx);
+        }
+        const float Mx = wave_max(mx);
+        const float L = wave_sum(mx == -INFINITY ? 0.f : l * __expf(mx - Mx));
+        lse = Mx + logf(L);
+        if (lane == 0) lse_io[m] = lse;
+    } else {
+        lse = lse_io[m];
     }
-    const float Mx = wave_max(mx);
-    const float L = wave_sum(mx == -INFINITY ? 0.f : l * __expf(mx - Mx));
-    const float lse = Mx + logf(L);
+    if (!X) return;
     const int x = X[m / r];
     float zt = 0.f;
     if (x >= 0) {
-        const bf16_t *u = U + (size_t)x * d, *yh = Yhi + m * d, *yl = Ylo + m * d;
-        for (int k = lane; k < d; k += kWave) zt += bf16_to_f32(u[k]) * (bf16_to_f32(yh[k]) + bf16_to_f32(yl[k]));
+        const bf16_t *u = U + (size_t)x * d, *yh = Yhi + m * d;
+        if (Ylo) {
+            const bf16_t *yl = Ylo + m * d;
+            for (int k = lane; k < d; k += kWave)
+                zt += bf16_to_f32(u[k]) * (bf16_to_f32(yh[k]) + bf16_to_f32(yl[k]));
+        } else {
+            for (int k = lane; k < d; k += kWave) zt += bf16_to_f32(u[k]) * bf16_to_f32(yh[k]);
+        }
         zt = wave_sum(zt);
     }
-    if (lane == 0) {
-        lse_out[m] = lse;
-        C_out[m] = (x >= 0) ? zt - lse : 0.f;
+    if (lane == 0) C_out[m] = (x >= 0) ? zt - lse : 0.f;
+}
+
+// Token draw for one (b, s) from the statistics of head row (b, s, a*) ("Sampling method").
+// The GEMM left one (max, sum exp) pair per 128-column segment of the vocabulary; their masses
+// sum_j exp(max_j - lse) are accumulated in vocabulary order in fp64 until the running sum passes
+// u, the 128 logits of that segment are recomputed (fp32 dot products with the bf16 y) and the
+// scan continues token by token.  First index whose running sum exceeds u; V-1 if none does.
+__global__ void __launch_bounds__(kBlock) k_draft_token(int d, int V, int n, int r, int parts, int seg_cols,
+                                                        const float2 *__restrict__ part, const float *__restrict__ lse,
+                                                        const bf16_t *__restrict__ Y, const bf16_t *__restrict__ U,
+                                                        const int32_t *__restrict__ alpha,
+                                                        const float *__restrict__ uniforms, int32_t *__restrict__ tokens)
+{
+    __shared__ double grp_sum[kBlock];
+    __shared__ double base_s;
+    __shared__ int seg_s;
+    __shared__ float p_s[256];
+    const size_t bs = blockIdx.x;                 // b*n + s
+    const size_t b = bs / n;
+    const int s = (int)(bs % n);
+    const size_t m = bs * r + alpha[b];
+    const float l = lse[m];
+    const double u = (double)uniforms[b * (1 + n) + 1 + s];
+    const float2 *pm = part + m * parts;
+    // masses of the segments this thread owns (a contiguous range, so that order is vocabulary order)
+    const int per = (parts + kBlock - 1) / kBlock;
+    const int lo = min(parts, (int)threadIdx.x * per), hi = min(parts, lo + per);
+    double sum = 0.0;
+    for (int j = lo; j < hi; ++j) {
+        const float2 q = pm[j];
+        sum += (q.x == -INFINITY) ? 0.0 : (double)(q.y * expf(q.x - l));
     }
+    grp_sum[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double c = 0.0;
+        int g = -1;
+        for (int i = 0; i < kBlock; ++i) {
+            if (c + grp_sum[i] > u) { g = i; break; }
+            c += grp_sum[i];
+        }
+        int seg = -1;
+        if (g >= 0) {
+            const int glo = min(parts, g * per), ghi = min(parts, glo + per);
+            seg = ghi - 1;
+            for (int j = glo; j < ghi; ++j) {
+                const float2 q = pm[j];
+                const double mj = (q.x == -INFINITY) ? 0.0 : (double)(q.y * expf(q.x - l));
+                if (c + mj > u) { seg = j; break; }
+                c += mj;
+            }
+        }
+        seg_s = seg;
+        base_s = c;
+    }
+    __syncthreads();
+    const int seg = seg_s;
+    if (seg < 0) {                                 // the running sum never passes u
+        if (threadIdx.x == 0) tokens[bs] = V - 1;
+        return;
+    }
+    // recompute the logits of the segment: one wavefront per column, lanes over k
+    const int v0 = seg * seg_cols, cols = min(seg_cols, V - v0);
+    const bf16_t *y = Y + m * d;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int c = wave; c < cols; c += kBlock / kWave) {
+        const bf16_t *urow = U + (size_t)(v0 + c) * d;
+        float acc = 0.f;
+        for (int k = lane; k < d; k += kWave) acc += bf16_to_f32(urow[k]) * bf16_to_f32(y[k]);
+        acc = wave_sum(acc);
+        if (lane == 0) p_s[c] = expf(acc - l);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double c = base_s;
+        int tok = v0 + cols - 1;
+        for (int i = 0; i < cols; ++i) {
+            c += (double)p_s[i];
+            if (c > u) { tok = v0 + i; break; }
+        }
+        tokens[bs] = tok;
+    }
+}
+
+// logq = -loss (the mixture kernel writes the negative joint log-likelihood)
+__global__ void k_negate(size_t count, const float *__restrict__ in, float *__restrict__ out)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) out[i] = -in[i];
 }
 
 // coef[m] = up_t * gamma[t, a] (zero for dropped factors); dg[t, a] = up_t (w - gamma)
@@ -254,12 +354,16 @@ inline FwdWs fwd_ws(const cp_head_desc &ds)
     return f;
 }
 
-// Rows of logit gradients held at a time: about 2 GiB of bf16, a multiple of the tile height.
+// Rows of logit gradients held at a time: about 2 GiB of bf16.  The count is a multiple of 16
+// tiles of 256 rows where possible, so that the d-wide products of a chunk (16 tile columns at
+// d = 4096) fill all 256 compute units in whole rounds.
 inline size_t bwd_chunk_rows(const cp_head_desc &ds)
 {
     const size_t M = (size_t)ds.T * ds.n * ds.r;
     const size_t Vp = round_up((size_t)ds.V, 64);
-    size_t rows = (((size_t)1 << 31) / (Vp * 2)) / Cfg::BM * Cfg::BM;
+    size_t rows = ((size_t)1 << 31) / (Vp * 2);
+    if (rows >= 16 * (size_t)Cfg::BM) rows = rows / (16 * Cfg::BM) * (16 * Cfg::BM);
+    else rows = rows / Cfg::BM * Cfg::BM;
     if (rows < (size_t)Cfg::BM || (ds.flags & CP_HEAD_MIN_WORKSPACE)) rows = Cfg::BM;
     return rows < M ? rows : (M ? M : 1);
 }
@@ -303,11 +407,33 @@ inline bool dims_fit(const cp_head_desc &ds)
 
 }  // namespace
 
+struct DraftWs {
+    size_t logw, w, Y, part, lse, C, nll, total;
+    int parts;
+};
+inline DraftWs draft_ws(const cp_head_desc &ds)
+{
+    DraftWs f;
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    f.parts = ((ds.V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    f.logw = take((size_t)ds.T * ds.r * 4);
+    f.w = take((size_t)ds.T * ds.r * 4);
+    f.Y = take(M * ds.d * 2);
+    f.part = take(M * f.parts * sizeof(float2));
+    f.lse = take(M * 4);
+    f.C = take(M * 4);
+    f.nll = take((size_t)ds.T * 4);
+    f.total = off;
+    return f;
+}
+
 size_t fast_workspace_bytes(const cp_head_desc &ds, int op)
 {
     if (op == CP_HEAD_OP_LOSS_FWD) return fwd_ws(ds).total;
     if (op == CP_HEAD_OP_LOSS_BWD) return bwd_ws(ds).total;
-    return generic_workspace_bytes(ds, op);
+    return draft_ws(ds).total;
 }
 
 int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
@@ -396,12 +522,40 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
-int fast_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
                const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, size_t,
                hipStream_t st)
 {
-    if (ds.d > 16000) return CP_HEAD_ERR_UNSUPPORTED;   // the plain draft kernels keep one row of y in LDS
-    return generic_draft(ds, H, W, U, G, uniforms, alpha, tokens, logq, ws, st);
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv;
+    const DraftWs f = draft_ws(ds);
+    const int B = (int)ds.T, d = ds.d, V = ds.V, n = ds.n, r = ds.r;
+    const size_t M = (size_t)B * n * r;
+    const int nrd = n * r * d;
+    float *logw = at<float>(ws, f.logw), *w = at<float>(ws, f.w), *lse = at<float>(ws, f.lse);
+    float *C = at<float>(ws, f.C), *nll = at<float>(ws, f.nll);
+    bf16_t *Y = at<bf16_t>(ws, f.Y);
+    float2 *part = at<float2>(ws, f.part);
+
+    launch_gate(ds, Hv, Gv, logw, w, st);                                                  // eq. 7
+    launch_pick_alpha(ds, w, uniforms, alpha, st);                                         // a* ~ w
+    // y = W_sa h, rounded to bf16 (part of the draft distribution's definition); streams W once
+    launch_gemm_nt<Cfg>("draft_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
+    // z = U y for all B*n*r rows with running statistics; streams U once, logits are not stored
+    launch_gemm_nt<Cfg>("draft_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);
+    k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, r, f.parts, part, Y, nullptr, U, nullptr, lse,
+                                                                   nullptr);
+    k_draft_token<<<(unsigned)(B * n), kBlock, 0, st>>>(d, V, n, r, f.parts, Cfg::WTN, part, lse, Y, U, alpha, uniforms,
+                                                       tokens);
+    if (logq) {
+        // eq. 9 at the drawn tuple, over all experts: the loss kernels with the tokens as targets
+        k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, r, f.parts, nullptr, Y, nullptr, U, tokens,
+                                                                       lse, C);
+        launch_mixture(ds, logw, C, nll, nullptr, st);
+        k_negate<<<blocks_for((size_t)B, kBlock), kBlock, 0, st>>>((size_t)B, nll, logq);
+    }
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
 }  // namespace cph

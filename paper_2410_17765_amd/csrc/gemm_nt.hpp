@@ -283,6 +283,7 @@ __device__ __forceinline__ void gemm_nt_mainloop_pipelined(const GemmOperands &g
 #define CPH_K_STEP(KT_, CUR, SET)                                                                  \
     {                                                                                              \
         constexpr int SET_ = SET;                                                                  \
+        (void)SET_;                                                                                \
         const char *st = smem + (CUR) * Cfg::STAGE_BYTES;                                          \
         const char *nx = smem + ((CUR) ^ 1) * Cfg::STAGE_BYTES;                                    \
         CPH_DBG_FRAGS(load_frags(st, 1, 1);)                                                       \

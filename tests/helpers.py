@@ -22,29 +22,75 @@ def band_valid(cdf: np.ndarray, idx: int, u: float, band: float = CDF_BAND) -> b
     return (lo - band <= u) and (u < hi + band)
 
 
+TIE_ULPS = 1e-3   # |distance to a bf16 rounding midpoint| (in bf16 ulps) below which fp32 accumulation
+                  # of y may legitimately round to the other neighbour than the exact value does
+
+
+def _near_ties(y):
+    """Indices of y (exact, fp64) that lie within TIE_ULPS of a bf16 rounding midpoint, and the nudge
+    that pushes each across it."""
+    y = np.asarray(y, dtype=np.float64)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(y), 1e-300))) - 7)
+    q = y / ulp
+    dist = (q - np.floor(q)) - 0.5
+    idx = np.nonzero(np.abs(dist) < TIE_ULPS)[0]
+    nudge = -np.where(dist[idx] >= 0, 1.0, -1.0) * (np.abs(dist[idx]) + 1e-4) * ulp[idx]
+    return idx, nudge
+
+
+def _valid_under_rounding_ties(oracle, H, W, U, G, u, b, s, a, v, y_exact):
+    """The draw v for (b, s) under expert a is admissible if it is band-valid for some way of rounding
+    the (at most 3) elements of y that sit on a rounding tie.  Returns the number of flipped elements
+    that explains it, or 0 if nothing does."""
+    import itertools
+    idx, nudge = _near_ties(y_exact[b, s, a])
+    if len(idx) == 0 or len(idx) > 3:
+        return 0
+    n, r, d = y_exact.shape[1:]
+    for k in range(1, len(idx) + 1):
+        for subset in itertools.combinations(range(len(idx)), k):
+            nd = np.zeros((1, n, r, d))
+            for j in subset:
+                nd[0, s, a, idx[j]] = nudge[j]
+            out = oracle.draft_sample(H[b:b + 1], W, U, G, u[b:b + 1], round_y=True, alpha_in=np.array([a], np.int32),
+                                      want_cdf=True, y_nudge=nd)
+            if band_valid(out[4][0, s], v, float(u[b, 1 + s])):
+                return k
+    return 0
+
+
 def check_draft(oracle, H, W, U, G, u, alpha_gpu, tokens_gpu, logq_gpu, round_y, logq_atol=2e-3):
     """Compare one draft call with the oracle.  Returns a dict of match statistics; raises on a
-    draw outside the CDF band or a wrong logq."""
+    draw outside the CDF band (unless a rounding tie of y explains it) or a wrong logq."""
     B, n = tokens_gpu.shape
-    a_o, tok_o, logq_o, cdf_w, cdf_tok = oracle.draft_sample(H, W, U, G, u, round_y=round_y, want_cdf=True)
+    a_o, tok_o, logq_o, cdf_w, cdf_tok, y_exact = oracle.draft_sample(H, W, U, G, u, round_y=round_y, want_cdf=True,
+                                                                      want_y=True)
     stats = {"alpha_exact": int((a_o == alpha_gpu).sum()), "alpha_total": B,
-             "tokens_exact": 0, "tokens_total": B * n}
+             "tokens_exact": 0, "tokens_total": B * n, "tie_draws": 0}
     for b in range(B):
         assert band_valid(cdf_w[b], int(alpha_gpu[b]), float(u[b, 0])), ("alpha out of band", b)
     if (a_o != alpha_gpu).any():
         # token distributions are conditional on the expert: take the oracle's under the GPU's (valid) expert
         a_o, tok_o, logq_o, _, cdf_tok = oracle.draft_sample(H, W, U, G, u, round_y=round_y,
                                                             alpha_in=alpha_gpu, want_cdf=True)
+    tie_rows = set()
     for b in range(B):
         for s in range(n):
             v = int(tokens_gpu[b, s])
             assert 0 <= v < cdf_tok.shape[2]
-            assert band_valid(cdf_tok[b, s], v, float(u[b, 1 + s])), ("token out of band", b, s, v, int(tok_o[b, s]))
+            if not band_valid(cdf_tok[b, s], v, float(u[b, 1 + s])):
+                flips = _valid_under_rounding_ties(oracle, H, W, U, G, u, b, s, int(alpha_gpu[b]), v, y_exact) \
+                    if round_y else 0
+                assert flips > 0, ("token out of band", b, s, v, int(tok_o[b, s]))
+                stats["tie_draws"] += 1
+                tie_rows.add(b)
             stats["tokens_exact"] += int(v == tok_o[b, s])
     if logq_gpu is not None:
         # log-probability of the tuple the GPU drew, by the oracle's loss at those tokens
         lq = -oracle.loss_fwd(H, W, U, G, tokens_gpu.astype(np.int32), round_y=round_y)
-        err = np.abs(lq - logq_gpu.astype(np.float64)).max()
-        assert err <= logq_atol, ("logq", err)
-        stats["logq_err"] = float(err)
+        keep = np.array([b not in tie_rows for b in range(B)])
+        if keep.any():
+            err = np.abs(lq - logq_gpu.astype(np.float64))[keep].max()
+            assert err <= logq_atol, ("logq", err)
+            stats["logq_err"] = float(err)
     return stats

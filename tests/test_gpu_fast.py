@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2410_17765_amd import synth
-from tests.helpers import GRAD_REL_FRO, LOSS_ATOL, rel_fro
+from tests.helpers import GRAD_REL_FRO, LOSS_ATOL, check_draft, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -77,3 +77,43 @@ def test_deterministic(gpu):
     np.testing.assert_array_equal(l1, l2)
     for k in g1:
         np.testing.assert_array_equal(g1[k], g2[k])
+
+
+DRAFT_CASES = [
+    synth.HeadConfig("draft_mfma_peaked", T=9, d=128, V=1000, n=3, r=4, targets="uniform", u_scale=4.0),
+    synth.HeadConfig("draft_mfma_flat", T=5, d=64, V=2000, n=2, r=8, targets="uniform"),
+    synth.HeadConfig("draft_mfma_ragged", T=70, d=192, V=777, n=4, r=3, targets="uniform", u_scale=6.0),
+    synth.HeadConfig("draft_mfma_r1", T=3, d=64, V=130, n=2, r=1, targets="uniform", u_scale=3.0),
+]
+
+
+@pytest.mark.parametrize("cfg", DRAFT_CASES, ids=lambda c: c.name)
+def test_draft_sampling(gpu, oracle, cfg):
+    import torch
+    print(f"case {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    u = synth.uniforms(cfg.T, cfg.n)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    alpha, tokens, logq = h.draft_sample(gpu.to_device(inp["H"], cfg.dtype), torch.from_numpy(u).cuda())
+    torch.cuda.synchronize()
+    stats = check_draft(oracle, inp["H"], inp["W"], inp["U"], inp["G"], u, alpha.cpu().numpy(),
+                        tokens.cpu().numpy(), logq.cpu().numpy(), round_y=True, logq_atol=1e-3)
+    print(f"  {stats}", flush=True)
+    # the CDF steps at these sizes are far wider than the band: every draw matches exactly, except
+    # where an element of y sits on a bf16 rounding tie (counted in tie_draws)
+    assert stats["alpha_exact"] == stats["alpha_total"]
+    assert stats["tokens_exact"] >= stats["tokens_total"] - stats["tie_draws"]
+    assert stats["tie_draws"] <= 2
+
+
+def test_draft_boundaries(gpu):
+    import torch
+    cfg = synth.HeadConfig("draft_mfma_edge", T=4, d=64, V=300, n=2, r=3, targets="uniform")
+    inp = synth.make_inputs(cfg)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16")
+    H = gpu.to_device(inp["H"], "bf16")
+    a, tok, _ = h.draft_sample(H, torch.zeros((4, 3), device="cuda"))
+    assert (a.cpu().numpy() == 0).all() and (tok.cpu().numpy() == 0).all()
+    top = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
+    a, tok, _ = h.draft_sample(H, torch.full((4, 3), top, device="cuda"))
+    assert (a.cpu().numpy() == cfg.r - 1).all() and (tok.cpu().numpy() == cfg.V - 1).all()
