@@ -169,6 +169,32 @@ def bench_draft(args):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = dt * 1e3 / args.steps
+    # the same step replayed from a HIP graph, as a serving loop would issue it (the call only launches
+    # kernels on the stream it is given, so it can be captured); every replay is checked against the eager result
+    ref = (alpha.clone(), tokens.clone(), logq.clone())
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            binding.cp_head_draft_sample(ds, H, h.W, h.U, h.G, u, alpha, tokens, logq, ws, side.cuda_stream)
+    graph_ok = True
+    for _ in range(3):
+        alpha.zero_(); tokens.zero_(); logq.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        graph_ok = graph_ok and bool((alpha == ref[0]).all() and (tokens == ref[1]).all() and (logq == ref[2]).all())
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_graph = (time.perf_counter() - t0) * 1e3 / args.steps
+    # per-kernel times from a second, event-instrumented pass (kept out of the latency above)
+    binding.cp_head_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    binding.cp_head_profile_enable(False)
+    kernels = binding.cp_head_profile_read()
     weight_bytes = 2.0 * cfg.n * cfg.r * cfg.d * cfg.d + 2.0 * cfg.V * cfg.d
     gbs = weight_bytes / (ms * 1e-3) / 1e9
     return {
@@ -176,8 +202,11 @@ def bench_draft(args):
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "draft", "B": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r},
+        "ms_per_step_graph": ms_graph, "graph_replays_match_eager": graph_ok,
+        "graph_gbs": weight_bytes / (ms_graph * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": gbs / PEAK_HBM_GBS, "traffic": None},
+        "kernels": [{"name": k[0], "launches": k[1], "ms_per_step": k[2] / args.steps} for k in kernels],
     }
 
 

@@ -78,8 +78,9 @@ int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const vo
 
 // Kernels of the generic path that the matrix-core path reuses (fp32 bookkeeping per position).
 void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *logw, float *w, hipStream_t st);
-void launch_mixture(const cp_head_desc &ds, const float *logw, const float *C, float *loss, float *gamma,
-                    hipStream_t st);
+// out[t] = sign * logsumexp_a(logw + sum_s C): sign = -1 gives the loss, +1 the joint log-probability
+void launch_mixture(const cp_head_desc &ds, const float *logw, const float *C, float *out, float *gamma,
+                    float sign, hipStream_t st);
 void launch_fill_zero(float *p, size_t count, hipStream_t st);
 void launch_pick_alpha(const cp_head_desc &ds, const float *w, const float *uniforms, int32_t *alpha,
                        hipStream_t st);

@@ -201,21 +201,30 @@ __global__ void __launch_bounds__(kBlock) k_row_finish(size_t M, int d, int r, i
     if (lane == 0) C_out[m] = (x >= 0) ? zt - lse : 0.f;
 }
 
-// Token draw for one (b, s) from the statistics of head row (b, s, a*) ("Sampling method").
-// The GEMM left one (max, sum exp) pair per 128-column segment of the vocabulary; their masses
-// sum_j exp(max_j - lse) are accumulated in vocabulary order in fp64 until the running sum passes
-// u, the 128 logits of that segment are recomputed (fp32 dot products with the bf16 y) and the
-// scan continues token by token.  First index whose running sum exceeds u; V-1 if none does.
-__global__ void __launch_bounds__(kBlock) k_draft_token(int d, int V, int n, int r, int parts, int seg_cols,
-                                                        const float2 *__restrict__ part, const float *__restrict__ lse,
-                                                        const bf16_t *__restrict__ Y, const bf16_t *__restrict__ U,
-                                                        const int32_t *__restrict__ alpha,
-                                                        const float *__restrict__ uniforms, int32_t *__restrict__ tokens)
+// Token draw for (b, s) from the statistics of head row (b, s, a*) ("Sampling method"), in three
+// small kernels.  The GEMM left one (max, sum exp) pair per 128-column segment of the vocabulary.
+//  1. k_draft_segment: the segment masses sum_j exp(max_j - lse) are accumulated in vocabulary order
+//     in fp64 (lane-local runs, then a wavefront scan) until the running sum passes u;
+//  2. k_draft_logits: the 128 logits of that segment are recomputed, one wavefront per column
+//     (fp32 dot products of U rows with the bf16 y);
+//  3. k_draft_pick: the scan continues token by token inside the segment.
+// Convention: first index whose running sum exceeds u; V-1 if none does.
+__device__ __forceinline__ double wave_scan_inclusive(double v, int lane)
 {
-    __shared__ double grp_sum[kBlock];
-    __shared__ double base_s;
-    __shared__ int seg_s;
-    __shared__ float p_s[256];
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const double o = __shfl_up(v, off, kWave);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+__global__ void __launch_bounds__(kWave) k_draft_segment(int n, int r, int parts, const float2 *__restrict__ part,
+                                                         const float *__restrict__ lse,
+                                                         const int32_t *__restrict__ alpha,
+                                                         const float *__restrict__ uniforms, int32_t *__restrict__ seg_out,
+                                                         double *__restrict__ base_out)
+{
     const size_t bs = blockIdx.x;                 // b*n + s
     const size_t b = bs / n;
     const int s = (int)(bs % n);
@@ -223,71 +232,101 @@ __global__ void __launch_bounds__(kBlock) k_draft_token(int d, int V, int n, int
     const float l = lse[m];
     const double u = (double)uniforms[b * (1 + n) + 1 + s];
     const float2 *pm = part + m * parts;
-    // masses of the segments this thread owns (a contiguous range, so that order is vocabulary order)
-    const int per = (parts + kBlock - 1) / kBlock;
-    const int lo = min(parts, (int)threadIdx.x * per), hi = min(parts, lo + per);
+    const int lane = threadIdx.x;
+    const int per = (parts + kWave - 1) / kWave;  // consecutive segments per lane: lane order = vocabulary order
+    const int lo = min(parts, lane * per), hi = min(parts, lo + per);
     double sum = 0.0;
     for (int j = lo; j < hi; ++j) {
         const float2 q = pm[j];
         sum += (q.x == -INFINITY) ? 0.0 : (double)(q.y * expf(q.x - l));
     }
-    grp_sum[threadIdx.x] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double c = 0.0;
-        int g = -1;
-        for (int i = 0; i < kBlock; ++i) {
-            if (c + grp_sum[i] > u) { g = i; break; }
-            c += grp_sum[i];
-        }
-        int seg = -1;
-        if (g >= 0) {
-            const int glo = min(parts, g * per), ghi = min(parts, glo + per);
-            seg = ghi - 1;
-            for (int j = glo; j < ghi; ++j) {
-                const float2 q = pm[j];
-                const double mj = (q.x == -INFINITY) ? 0.0 : (double)(q.y * expf(q.x - l));
-                if (c + mj > u) { seg = j; break; }
-                c += mj;
-            }
-        }
-        seg_s = seg;
-        base_s = c;
-    }
-    __syncthreads();
-    const int seg = seg_s;
-    if (seg < 0) {                                 // the running sum never passes u
-        if (threadIdx.x == 0) tokens[bs] = V - 1;
+    const double incl = wave_scan_inclusive(sum, lane);
+    const unsigned long long crossed = __ballot(incl > u);
+    if (crossed == 0ull) {                         // the running sum never passes u
+        if (lane == 0) { seg_out[bs] = -1; base_out[bs] = 0.0; }
         return;
     }
-    // recompute the logits of the segment: one wavefront per column, lanes over k
-    const int v0 = seg * seg_cols, cols = min(seg_cols, V - v0);
-    const bf16_t *y = Y + m * d;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int c = wave; c < cols; c += kBlock / kWave) {
-        const bf16_t *urow = U + (size_t)(v0 + c) * d;
-        float acc = 0.f;
-        for (int k = lane; k < d; k += kWave) acc += bf16_to_f32(urow[k]) * bf16_to_f32(y[k]);
-        acc = wave_sum(acc);
-        if (lane == 0) p_s[c] = expf(acc - l);
+    const int first = __ffsll((long long)crossed) - 1;
+    if (lane == first) {
+        double c = incl - sum;
+        int seg = hi - 1;
+        for (int j = lo; j < hi; ++j) {
+            const float2 q = pm[j];
+            const double mj = (q.x == -INFINITY) ? 0.0 : (double)(q.y * expf(q.x - l));
+            if (c + mj > u) { seg = j; break; }
+            c += mj;
+        }
+        seg_out[bs] = seg;
+        base_out[bs] = c;
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double c = base_s;
-        int tok = v0 + cols - 1;
-        for (int i = 0; i < cols; ++i) {
-            c += (double)p_s[i];
+}
+
+__global__ void __launch_bounds__(kBlock) k_draft_logits(int d, int V, int n, int r, int seg_cols,
+                                                         const float *__restrict__ lse, const bf16_t *__restrict__ Y,
+                                                         const bf16_t *__restrict__ U, const int32_t *__restrict__ alpha,
+                                                         const int32_t *__restrict__ seg_in, float *__restrict__ p_out)
+{
+    const int blocks_per_row = seg_cols / (kBlock / kWave);
+    const size_t bs = blockIdx.x / blocks_per_row;
+    const int c = (blockIdx.x % blocks_per_row) * (kBlock / kWave) + (threadIdx.x >> 6);
+    const int seg = seg_in[bs];
+    if (seg < 0) return;
+    const int v = seg * seg_cols + c;
+    const int lane = threadIdx.x & 63;
+    float p = 0.f;
+    if (v < V) {
+        const size_t m = bs * r + alpha[bs / n];
+        const u32x4_t *urow = reinterpret_cast<const u32x4_t *>(U + (size_t)v * d);
+        const u32x4_t *yrow = reinterpret_cast<const u32x4_t *>(Y + m * d);
+        float acc = 0.f;
+        for (int k = lane; k < d / 8; k += kWave) {      // 8 bf16 per 16-byte load
+            const u32x4_t a = urow[k], bq = yrow[k];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc += __uint_as_float(a[e] << 16) * __uint_as_float(bq[e] << 16);
+                acc += __uint_as_float(a[e] & 0xFFFF0000u) * __uint_as_float(bq[e] & 0xFFFF0000u);
+            }
+        }
+        acc = wave_sum(acc);
+        p = expf(acc - lse[m]);
+    }
+    if (lane == 0) p_out[bs * seg_cols + c] = p;
+}
+
+__global__ void __launch_bounds__(kWave) k_draft_pick(int V, int seg_cols, const int32_t *__restrict__ seg_in,
+                                                      const double *__restrict__ base_in,
+                                                      const float *__restrict__ p_in, const float *__restrict__ uniforms,
+                                                      int n, int32_t *__restrict__ tokens)
+{
+    const size_t bs = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int seg = seg_in[bs];
+    if (seg < 0) {
+        if (lane == 0) tokens[bs] = V - 1;
+        return;
+    }
+    const double u = (double)uniforms[(bs / n) * (1 + n) + 1 + (bs % n)];
+    const int v0 = seg * seg_cols, cols = min(seg_cols, V - v0);
+    const int per = (seg_cols + kWave - 1) / kWave;
+    const int lo = lane * per;
+    double sum = 0.0;
+    for (int i = lo; i < lo + per && i < cols; ++i) sum += (double)p_in[bs * seg_cols + i];
+    const double incl = base_in[bs] + wave_scan_inclusive(sum, lane);
+    const unsigned long long crossed = __ballot(incl > u);
+    if (crossed == 0ull) {                         // rounding between the two passes: stay in the segment
+        if (lane == 0) tokens[bs] = v0 + cols - 1;
+        return;
+    }
+    const int first = __ffsll((long long)crossed) - 1;
+    if (lane == first) {
+        double c = incl - sum;
+        int tok = v0 + min(cols, lo + per) - 1;
+        for (int i = lo; i < lo + per && i < cols; ++i) {
+            c += (double)p_in[bs * seg_cols + i];
             if (c > u) { tok = v0 + i; break; }
         }
         tokens[bs] = tok;
     }
-}
-
-// logq = -loss (the mixture kernel writes the negative joint log-likelihood)
-__global__ void k_negate(size_t count, const float *__restrict__ in, float *__restrict__ out)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) out[i] = -in[i];
 }
 
 // coef[m] = up_t * gamma[t, a] (zero for dropped factors); dg[t, a] = up_t (w - gamma)
@@ -408,7 +447,7 @@ inline bool dims_fit(const cp_head_desc &ds)
 }  // namespace
 
 struct DraftWs {
-    size_t logw, w, Y, part, lse, C, nll, total;
+    size_t logw, w, Y, part, lse, C, nll, seg, base, p, total;
     int parts;
 };
 inline DraftWs draft_ws(const cp_head_desc &ds)
@@ -425,6 +464,9 @@ inline DraftWs draft_ws(const cp_head_desc &ds)
     f.lse = take(M * 4);
     f.C = take(M * 4);
     f.nll = take((size_t)ds.T * 4);
+    f.seg = take((size_t)ds.T * ds.n * 4);
+    f.base = take((size_t)ds.T * ds.n * 8);
+    f.p = take((size_t)ds.T * ds.n * Cfg::WTN * 4);
     f.total = off;
     return f;
 }
@@ -457,7 +499,7 @@ int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     launch_gemm_nt<Cfg>("gemm_y", H, d, T, W, d, nrd, d, EpiStoreBf16{Y, Ylo, (long)nrd, T, nrd}, st);   // y = W_sa h
     launch_gemm_nt<Cfg>("gemm_z_stats", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);  // z = U y, statistics
     k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, ds.r, f.parts, part, Y, Ylo, U, X, lse, C);
-    launch_mixture(ds, logw, C, loss, gamma, st);                                              // eq. 9
+    launch_mixture(ds, logw, C, loss, gamma, -1.f, st);                                              // eq. 9
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
@@ -534,7 +576,7 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
     const size_t M = (size_t)B * n * r;
     const int nrd = n * r * d;
     float *logw = at<float>(ws, f.logw), *w = at<float>(ws, f.w), *lse = at<float>(ws, f.lse);
-    float *C = at<float>(ws, f.C), *nll = at<float>(ws, f.nll);
+    float *C = at<float>(ws, f.C);
     bf16_t *Y = at<bf16_t>(ws, f.Y);
     float2 *part = at<float2>(ws, f.part);
 
@@ -544,16 +586,28 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
     launch_gemm_nt<Cfg>("draft_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
     // z = U y for all B*n*r rows with running statistics; streams U once, logits are not stored
     launch_gemm_nt<Cfg>("draft_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);
-    k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, r, f.parts, part, Y, nullptr, U, nullptr, lse,
-                                                                   nullptr);
-    k_draft_token<<<(unsigned)(B * n), kBlock, 0, st>>>(d, V, n, r, f.parts, Cfg::WTN, part, lse, Y, U, alpha, uniforms,
-                                                       tokens);
+    {
+        ProfileScope prof("draft_row_lse", (double)M * f.parts * 8, st);
+        k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, r, f.parts, part, Y, nullptr, U, nullptr,
+                                                                       lse, nullptr);
+    }
+    {
+        ProfileScope prof("draft_token", (double)B * n * Cfg::WTN * d * 2, st);
+        int32_t *seg = at<int32_t>(ws, f.seg);
+        double *base = at<double>(ws, f.base);
+        float *pseg = at<float>(ws, f.p);
+        const unsigned rows = (unsigned)(B * n);
+        k_draft_segment<<<rows, kWave, 0, st>>>(n, r, f.parts, part, lse, alpha, uniforms, seg, base);
+        k_draft_logits<<<rows * (Cfg::WTN / (kBlock / kWave)), kBlock, 0, st>>>(d, V, n, r, Cfg::WTN, lse, Y, U, alpha,
+                                                                                seg, pseg);
+        k_draft_pick<<<rows, kWave, 0, st>>>(V, Cfg::WTN, seg, base, pseg, uniforms, n, tokens);
+    }
     if (logq) {
+        ProfileScope prof("draft_logq", (double)M * d * 4, st);
         // eq. 9 at the drawn tuple, over all experts: the loss kernels with the tokens as targets
         k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, r, f.parts, nullptr, Y, nullptr, U, tokens,
                                                                        lse, C);
-        launch_mixture(ds, logw, C, nll, nullptr, st);
-        k_negate<<<blocks_for((size_t)B, kBlock), kBlock, 0, st>>>((size_t)B, nll, logq);
+        launch_mixture(ds, logw, C, logq, nullptr, 1.f, st);
     }
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }

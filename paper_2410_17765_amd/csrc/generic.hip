@@ -115,7 +115,7 @@ __global__ void __launch_bounds__(kBlock) k_zstats_generic(int d, int V, int r, 
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kWave) k_mixture(int n, int r, const float *__restrict__ logw,
                                                    const float *__restrict__ C, float *__restrict__ loss,
-                                                   float *__restrict__ gamma)
+                                                   float *__restrict__ gamma, float sign)
 {
     const size_t t = blockIdx.x;
     const int lane = threadIdx.x;
@@ -127,7 +127,7 @@ __global__ void __launch_bounds__(kWave) k_mixture(int n, int r, const float *__
     const float mx = wave_max(a);
     const float sum = wave_sum(lane < r ? expf(a - mx) : 0.f);
     const float L = mx + logf(sum);
-    if (lane == 0) loss[t] = -L;
+    if (lane == 0) loss[t] = sign * L;   // -L: the loss; +L: the joint log-probability
     if (gamma && lane < r) gamma[t * r + lane] = expf(a - L);
 }
 
@@ -400,7 +400,7 @@ int loss_fwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U,
     k_gate<TIn><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
     k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, Y, 0);
     k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, X, lse, C, nullptr);
-    k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, loss, gamma);
+    k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, loss, gamma, -1.f);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
@@ -513,11 +513,11 @@ void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *lo
         k_gate<bf16_t><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, (const bf16_t *)H, (const bf16_t *)G, logw, w);
 }
 
-void launch_mixture(const cp_head_desc &ds, const float *logw, const float *C, float *loss, float *gamma,
-                    hipStream_t st)
+void launch_mixture(const cp_head_desc &ds, const float *logw, const float *C, float *out, float *gamma,
+                    float sign, hipStream_t st)
 {
     if (ds.T == 0) return;
-    k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, loss, gamma);
+    k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, out, gamma, sign);
 }
 
 void launch_pick_alpha(const cp_head_desc &ds, const float *w, const float *uniforms, int32_t *alpha, hipStream_t st)
