@@ -98,29 +98,46 @@ struct EpiRowStats {
 };
 
 // Softmax gradient (derivative of eq. 8/9 with respect to the logits), written in bf16:
-//   dz[m, v] = coef[m] * (exp(z - lse[m]) - 1[v = x_m]),  zero in the padding columns V..Vp-1
+//   dz[m, v] = coef[m] * (exp(z - lse[m]) - 1[v = x_m]),  zero in the padding columns V..Vp-1;
+// optionally also transposed (dzT[v, m], rows of the chunk padded with zeros up to Mcp), which is the
+// operand layout of the dU product.
 struct EpiDz {
     bf16_t *dZ;          // [Mc, Vp] for the chunk
     long ldz;
+    bf16_t *dZt;         // [V, Mcp] or null
+    long ldzt;
     const float *lse;    // chunk-relative
     const float *coef;   // chunk-relative; already zero for dropped factors
     const int32_t *X;    // whole array
     size_t m0;           // first row of the chunk
     int r;
-    int Mc, V, Vp;
+    int Mc, Mcp, V, Vp;
     template <class C>
     __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
     {
         const float *__restrict__ lse_ = lse;
         const float *__restrict__ coef_ = coef;
         const int32_t *__restrict__ X_ = X;
-        store_tile_bf16<C>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, [&](int i, int j, int v, int row, int col) {
-            const int rr = row < Mc ? row : Mc - 1;
-            const float l = lse_[rr], cf = coef_[rr];
-            const int x = X_[(m0 + rr) / r];
-            const float g = cf * (__expf(acc[i][j][v] - l) - (col == x ? 1.f : 0.f));
-            return f32_to_bf16(col < V ? g : 0.f);
-        });
+        // turn the logits into their gradients in place (per-row quantities are loaded once per row)
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + acc_row(i, v, lane);
+                const int rr = row < Mc ? row : Mc - 1;
+                const float l = lse_[rr];
+                const float cf = row < Mc ? coef_[rr] : 0.f;
+                const int x = X_[(m0 + rr) / r];
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j) {
+                    const int col = col0 + acc_col(j, lane);
+                    const float g = cf * (__expf(acc[i][j][v] - l) - (col == x ? 1.f : 0.f));
+                    acc[i][j][v] = col < V ? g : 0.f;
+                }
+            }
+        auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
+        store_tile_bf16<C>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+        if (dZt) store_tile_bf16_transposed<C>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
     }
 };
 
@@ -357,16 +374,35 @@ __global__ void k_add_gate_to_dh(size_t T, int d, int r, const bf16_t *__restric
     dH[idx] = acc;
 }
 
-// dG[a, j] = sum_t dg[t, a] H[t, j], summed in increasing t
-__global__ void k_dgate_weights(size_t T, int d, int r, const bf16_t *__restrict__ H, const float *__restrict__ dg,
-                                float *__restrict__ dG)
+// dG[a, j] = sum_t dg[t, a] H[t, j] in two deterministic stages: partial sums over chunks of 512
+// positions (one thread per column j, eight experts at a time), then the chunks in increasing order.
+constexpr int kGateChunk = 512;
+__global__ void __launch_bounds__(kBlock) k_dgate_partial(size_t T, int d, int r, const bf16_t *__restrict__ H,
+                                                          const float *__restrict__ dg, float *__restrict__ partial)
+{
+    const int j = blockIdx.x * kBlock + threadIdx.x;
+    const size_t tc = blockIdx.y;
+    if (j >= d) return;
+    const size_t t0 = tc * kGateChunk, t1 = min(T, t0 + kGateChunk);
+    for (int a0 = 0; a0 < r; a0 += 8) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (size_t t = t0; t < t1; ++t) {
+            const float h = bf16_to_f32(H[t * d + j]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (a0 + e < r) acc[e] += dg[t * r + a0 + e] * h;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (a0 + e < r) partial[(tc * r + a0 + e) * d + j] = acc[e];
+    }
+}
+__global__ void k_dgate_reduce(int chunks, int d, int r, const float *__restrict__ partial, float *__restrict__ dG)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)r * d) return;
-    const int a = (int)(idx / d);
-    const int j = (int)(idx % d);
     float acc = 0.f;
-    for (size_t t = 0; t < T; ++t) acc += dg[t * r + a] * bf16_to_f32(H[t * d + j]);
+    for (int c = 0; c < chunks; ++c) acc += partial[(size_t)c * r * d + idx];
     dG[idx] = acc;
 }
 
@@ -408,8 +444,9 @@ inline size_t bwd_chunk_rows(const cp_head_desc &ds)
 }
 
 struct BwdWs {
-    size_t coef, dg, Ut, Wt, Ht, dY, dYt, dZ, dZt, Yt, total;
+    size_t coef, dg, dGpart, Ut, Wt, Ht, dY, dYt, dZ, dZt, Yt, total;
     size_t Vp, Tp, chunk, chunk_p;
+    size_t ldV, ldT, ldM, ldN;   // leading dimensions of the transposed operands (K padded to 64, plus 64)
 };
 inline BwdWs bwd_ws(const cp_head_desc &ds)
 {
@@ -419,18 +456,20 @@ inline BwdWs bwd_ws(const cp_head_desc &ds)
     b.Tp = round_up(T, 64);
     b.chunk = bwd_chunk_rows(ds);
     b.chunk_p = round_up(b.chunk, 64);
+    b.ldV = b.Vp + 64; b.ldT = b.Tp + 64; b.ldM = b.chunk_p + 64; b.ldN = nrd + 64;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     b.coef = take(M * 4);
     b.dg = take(T * ds.r * 4);
-    b.Ut = take((size_t)ds.d * b.Vp * 2);
-    b.Wt = take((size_t)ds.d * nrd * 2);
-    b.Ht = take((size_t)ds.d * b.Tp * 2);
+    b.dGpart = take(((T + kGateChunk - 1) / kGateChunk) * ds.r * ds.d * 4);
+    b.Ut = take((size_t)ds.d * b.ldV * 2);
+    b.Wt = take((size_t)ds.d * b.ldN * 2);
+    b.Ht = take((size_t)ds.d * b.ldT * 2);
     b.dY = take(M * ds.d * 2);
-    b.dYt = take(nrd * b.Tp * 2);
+    b.dYt = take(nrd * b.ldT * 2);
     b.dZ = take(b.chunk * b.Vp * 2);
-    b.dZt = take((size_t)ds.V * b.chunk_p * 2);
-    b.Yt = take((size_t)ds.d * b.chunk_p * 2);
+    b.dZt = take((size_t)ds.V * b.ldM * 2);
+    b.Yt = take((size_t)ds.d * b.ldM * 2);
     b.total = off;
     return b;
 }
@@ -439,9 +478,9 @@ inline bool dims_fit(const cp_head_desc &ds)
 {
     // the GEMM addresses rows of a tile with 32-bit byte offsets and counts rows in int
     const size_t nrd = (size_t)ds.n * ds.r * ds.d, M = (size_t)ds.T * ds.n * ds.r;
-    const size_t max_ld = nrd > (size_t)ds.V + 64 ? nrd : (size_t)ds.V + 64;
+    const size_t max_ld = (nrd > (size_t)ds.V + 64 ? nrd : (size_t)ds.V + 64) + 64;
     return M < ((size_t)1 << 31) && nrd < ((size_t)1 << 31) && max_ld * 2 * 256 < ((size_t)1 << 32) &&
-           ((size_t)ds.T + 64) * 2 * 256 < ((size_t)1 << 32);
+           ((size_t)ds.T + 128) * 2 * 256 < ((size_t)1 << 32);
 }
 
 }  // namespace
@@ -527,9 +566,10 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     bf16_t *dY = at<bf16_t>(ws, b.dY), *dYt = at<bf16_t>(ws, b.dYt);
     bf16_t *dZ = at<bf16_t>(ws, b.dZ), *dZt = at<bf16_t>(ws, b.dZt), *Yt = at<bf16_t>(ws, b.Yt);
     const int Vp = (int)b.Vp, Tp = (int)b.Tp;
+    const long ldV = (long)b.ldV, ldT = (long)b.ldT, ldM = (long)b.ldM, ldN = (long)b.ldN;
 
     k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, dloss, scale, X, coef, dg);
-    transpose_bf16(U, d, V, d, Ut, Vp, Vp, st);                       // Ut[d, Vp]
+    transpose_bf16(U, d, V, d, Ut, ldV, Vp, st);                      // Ut[d, Vp]
 
     int first = 1;
     for (size_t m0 = 0; m0 < M; m0 += b.chunk) {
@@ -539,28 +579,34 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
         // recompute z for the chunk; the epilogue turns it into dz (bf16); the tiles over V also
         // cover the padding columns V..Vp-1, which the epilogue zero-fills
         launch_gemm_nt<Cfg>("gemm_z_dz", Yc, d, Mc, U, d, V, d,
-                            EpiDz{dZ, (long)Vp, lse + m0, coef + m0, X, m0, r, Mc, V, Vp}, st);
+                            EpiDz{dZ, (long)Vp, dU ? dZt : nullptr, ldM, lse + m0, coef + m0, X, m0, r, Mc, Mcp, V,
+                                  Vp},
+                            st);
         // dY = dz U   (contraction over the vocabulary)
-        launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, Vp, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st);
+        launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st);
         if (dU) {
             // dU += dz^T Y   (contraction over the rows of the chunk)
-            transpose_bf16(dZ, Vp, Mc, V, dZt, Mcp, Mcp, st);         // dZt[V, Mcp]
-            transpose_bf16(Yc, d, Mc, d, Yt, Mcp, Mcp, st);           // Yt[d, Mcp]
-            launch_gemm_nt<Cfg>("gemm_du", dZt, Mcp, V, Yt, Mcp, d, Mcp, EpiStoreF32{dU, (long)d, V, d, first ? 0 : 1}, st);
+            transpose_bf16(Yc, d, Mc, d, Yt, ldM, Mcp, st);           // Yt[d, Mcp]
+            launch_gemm_nt<Cfg>("gemm_du", dZt, ldM, V, Yt, ldM, d, Mcp, EpiStoreF32{dU, (long)d, V, d, first ? 0 : 1}, st);
         }
         first = 0;
     }
     // dH = dY W + G^T dg   (contraction over (s, a, k))
-    transpose_bf16(W, d, (int)nrd, d, Wt, (long)nrd, (int)nrd, st);   // Wt[d, nrd]
-    launch_gemm_nt<Cfg>("gemm_dh", dY, (long)nrd, (int)T, Wt, (long)nrd, d, (int)nrd, EpiStoreF32{dH, (long)d, (int)T, d, 0}, st);
+    transpose_bf16(W, d, (int)nrd, d, Wt, ldN, (int)nrd, st);         // Wt[d, nrd]
+    launch_gemm_nt<Cfg>("gemm_dh", dY, (long)nrd, (int)T, Wt, ldN, d, (int)nrd, EpiStoreF32{dH, (long)d, (int)T, d, 0}, st);
     k_add_gate_to_dh<<<blocks_for(T * d, kBlock), kBlock, 0, st>>>(T, d, r, G, dg, dH);
     if (dW) {
         // dW_sa = dY_sa^T H   (contraction over positions)
-        transpose_bf16(dY, (long)nrd, (int)T, (int)nrd, dYt, Tp, Tp, st);   // dYt[nrd, Tp]
-        transpose_bf16(H, d, (int)T, d, Ht, Tp, Tp, st);                    // Ht[d, Tp]
-        launch_gemm_nt<Cfg>("gemm_dw", dYt, Tp, (int)nrd, Ht, Tp, d, Tp, EpiStoreF32{dW, (long)d, (int)nrd, d, 0}, st);
+        transpose_bf16(dY, (long)nrd, (int)T, (int)nrd, dYt, ldT, Tp, st);  // dYt[nrd, Tp]
+        transpose_bf16(H, d, (int)T, d, Ht, ldT, Tp, st);                   // Ht[d, Tp]
+        launch_gemm_nt<Cfg>("gemm_dw", dYt, ldT, (int)nrd, Ht, ldT, d, Tp, EpiStoreF32{dW, (long)d, (int)nrd, d, 0}, st);
     }
-    if (dG) k_dgate_weights<<<blocks_for((size_t)r * d, kBlock), kBlock, 0, st>>>(T, d, r, H, dg, dG);
+    if (dG) {
+        float *part = at<float>(ws, b.dGpart);
+        const unsigned chunks = (unsigned)((T + kGateChunk - 1) / kGateChunk);
+        k_dgate_partial<<<dim3(blocks_for((size_t)d, kBlock), chunks), kBlock, 0, st>>>(T, d, r, H, dg, part);
+        k_dgate_reduce<<<blocks_for((size_t)r * d, kBlock), kBlock, 0, st>>>((int)chunks, d, r, part, dG);
+    }
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 

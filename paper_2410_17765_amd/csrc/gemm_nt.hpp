@@ -538,6 +538,61 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
     }
 }
 
+// Transposed bf16 output: dst[col * ld + row] = value(i, j, v, row, col).  A lane owns four consecutive
+// rows of one column per accumulator group, so the sub-tile is laid out column-major in LDS (64 rows at
+// a time, 8-byte writes) and leaves as 16-byte pieces of 128-byte column segments.
+// row_limit and ld are multiples of 8; rows are written up to row_limit, columns up to col_limit.
+template <class Cfg, class F>
+__device__ __forceinline__ void store_tile_bf16_transposed(char *smem, int wave, int lane, int row0, int col0,
+                                                           int row_limit, int col_limit, bf16_t *__restrict__ dst,
+                                                           long ld, F value)
+{
+    static_assert(Cfg::TM % 2 == 0, "two 32-row blocks per pass");
+    constexpr int CS = 64 * 2 + 16;                     // padded column stride in bytes (64 rows)
+    static_assert(Cfg::WM * Cfg::WN * Cfg::WTN * CS <= Cfg::LDS_BYTES, "staging fits");
+    char *stage = smem + wave * (Cfg::WTN * CS);
+    __syncthreads();
+#pragma unroll
+    for (int ip = 0; ip < Cfg::TM / 2; ++ip) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii) {
+            const int i = ip * 2 + ii;
+#pragma unroll
+            for (int j = 0; j < Cfg::TN; ++j) {
+                const int c = j * 32 + (lane & 31);
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int r = 8 * gq + 4 * (lane >> 5);          // first of four consecutive rows
+                    unsigned lo, hi;
+                    {
+                        const bf16_t a = value(i, j, gq * 4 + 0, row0 + i * 32 + r + 0, col0 + c);
+                        const bf16_t b = value(i, j, gq * 4 + 1, row0 + i * 32 + r + 1, col0 + c);
+                        lo = (unsigned)a | ((unsigned)b << 16);
+                    }
+                    {
+                        const bf16_t a = value(i, j, gq * 4 + 2, row0 + i * 32 + r + 2, col0 + c);
+                        const bf16_t b = value(i, j, gq * 4 + 3, row0 + i * 32 + r + 3, col0 + c);
+                        hi = (unsigned)a | ((unsigned)b << 16);
+                    }
+                    typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+                    u32x2_t pk = {lo, hi};
+                    *reinterpret_cast<u32x2_t *>(stage + c * CS + (ii * 32 + r) * 2) = pk;
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < Cfg::WTN / 8; ++p) {
+            const int c = p * 8 + (lane >> 3), ch = lane & 7;
+            const u32x4_t val = *reinterpret_cast<const u32x4_t *>(stage + c * CS + ch * 16);
+            const int grow = row0 + ip * 64 + ch * 8, gcol = col0 + c;
+            if (grow < row_limit && gcol < col_limit)
+                *reinterpret_cast<u32x4_t *>(dst + (size_t)gcol * ld + grow) = val;
+        }
+        __syncthreads();
+    }
+}
+
 // fp32 variant: dst = value, or dst += value when `accumulate` is set (16-byte loads and stores).
 template <class Cfg, class F>
 __device__ __forceinline__ void store_tile_f32(char *smem, int wave, int lane, int row0, int col0, int row_limit,
