@@ -106,28 +106,23 @@ struct EpiDz {
     long ldz;
     bf16_t *dZt;         // [V, Mcp] or null
     long ldzt;
-    const float *lse;    // chunk-relative
-    const float *coef;   // chunk-relative; already zero for dropped factors
-    const int32_t *X;    // whole array
-    size_t m0;           // first row of the chunk
-    int r;
+    const float4 *rowinfo;   // chunk-relative: {lse, coef (zero for dropped factors), target as int bits, -}
     int Mc, Mcp, V, Vp;
     template <class C>
     __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
     {
-        const float *__restrict__ lse_ = lse;
-        const float *__restrict__ coef_ = coef;
-        const int32_t *__restrict__ X_ = X;
-        // turn the logits into their gradients in place (per-row quantities are loaded once per row)
+        const float4 *__restrict__ info = rowinfo;
+        // turn the logits into their gradients in place, one 32-row block at a time (the compiler
+        // barrier keeps the per-row loads of later blocks from being hoisted and spilling registers)
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i)
+        for (int i = 0; i < C::TM; ++i) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = row0 + acc_row(i, v, lane);
-                const int rr = row < Mc ? row : Mc - 1;
-                const float l = lse_[rr];
-                const float cf = row < Mc ? coef_[rr] : 0.f;
-                const int x = X_[(m0 + rr) / r];
+                const float4 ri = info[row < Mc ? row : Mc - 1];
+                const float l = ri.x;
+                const float cf = row < Mc ? ri.y : 0.f;
+                const int x = __float_as_int(ri.z);
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j) {
                     const int col = col0 + acc_col(j, lane);
@@ -135,6 +130,8 @@ struct EpiDz {
                     acc[i][j][v] = col < V ? g : 0.f;
                 }
             }
+            asm volatile("" ::: "memory");
+        }
         auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
         store_tile_bf16<C>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
         if (dZt) store_tile_bf16_transposed<C>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
@@ -346,10 +343,10 @@ __global__ void __launch_bounds__(kWave) k_draft_pick(int V, int seg_cols, const
     }
 }
 
-// coef[m] = up_t * gamma[t, a] (zero for dropped factors); dg[t, a] = up_t (w - gamma)
+// Per head row {lse, coef = up_t * gamma[t, a] (zero for dropped factors), target}; dg[t, a] = up_t (w - gamma)
 __global__ void k_bwd_coefficients(size_t M, int n, int r, const float *__restrict__ w, const float *__restrict__ gamma,
-                                   const float *__restrict__ dloss, float scale, const int32_t *__restrict__ X,
-                                   float *__restrict__ coef, float *__restrict__ dg)
+                                   const float *__restrict__ lse, const float *__restrict__ dloss, float scale,
+                                   const int32_t *__restrict__ X, float4 *__restrict__ rowinfo, float *__restrict__ dg)
 {
     const size_t m = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (m >= M) return;
@@ -357,7 +354,8 @@ __global__ void k_bwd_coefficients(size_t M, int n, int r, const float *__restri
     const int a = (int)(m % r);
     const float up = dloss ? dloss[t] * scale : scale;
     const float gm = gamma[t * r + a];
-    coef[m] = (X[m / r] >= 0) ? up * gm : 0.f;
+    const int x = X[m / r];
+    rowinfo[m] = make_float4(lse[m], (x >= 0) ? up * gm : 0.f, __int_as_float(x), 0.f);
     if ((m / r) % n == 0) dg[t * r + a] = up * (w[t * r + a] - gm);
 }
 
@@ -459,7 +457,7 @@ inline BwdWs bwd_ws(const cp_head_desc &ds)
     b.ldV = b.Vp + 64; b.ldT = b.Tp + 64; b.ldM = b.chunk_p + 64; b.ldN = nrd + 64;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    b.coef = take(M * 4);
+    b.coef = take(M * 16);
     b.dg = take(T * ds.r * 4);
     b.dGpart = take(((T + kGateChunk - 1) / kGateChunk) * ds.r * ds.d * 4);
     b.Ut = take((size_t)ds.d * b.ldV * 2);
@@ -561,14 +559,15 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     const size_t T = (size_t)ds.T, M = T * n * r;
     const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
     const bf16_t *Y = at<bf16_t>(ctx, cl.Y);
-    float *coef = at<float>(ws, b.coef), *dg = at<float>(ws, b.dg);
+    float4 *rowinfo = at<float4>(ws, b.coef);
+    float *dg = at<float>(ws, b.dg);
     bf16_t *Ut = at<bf16_t>(ws, b.Ut), *Wt = at<bf16_t>(ws, b.Wt), *Ht = at<bf16_t>(ws, b.Ht);
     bf16_t *dY = at<bf16_t>(ws, b.dY), *dYt = at<bf16_t>(ws, b.dYt);
     bf16_t *dZ = at<bf16_t>(ws, b.dZ), *dZt = at<bf16_t>(ws, b.dZt), *Yt = at<bf16_t>(ws, b.Yt);
     const int Vp = (int)b.Vp, Tp = (int)b.Tp;
     const long ldV = (long)b.ldV, ldT = (long)b.ldT, ldM = (long)b.ldM, ldN = (long)b.ldN;
 
-    k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, dloss, scale, X, coef, dg);
+    k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, lse, dloss, scale, X, rowinfo, dg);
     transpose_bf16(U, d, V, d, Ut, ldV, Vp, st);                      // Ut[d, Vp]
 
     int first = 1;
@@ -579,9 +578,7 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
         // recompute z for the chunk; the epilogue turns it into dz (bf16); the tiles over V also
         // cover the padding columns V..Vp-1, which the epilogue zero-fills
         launch_gemm_nt<Cfg>("gemm_z_dz", Yc, d, Mc, U, d, V, d,
-                            EpiDz{dZ, (long)Vp, dU ? dZt : nullptr, ldM, lse + m0, coef + m0, X, m0, r, Mc, Mcp, V,
-                                  Vp},
-                            st);
+                            EpiDz{dZ, (long)Vp, dU ? dZt : nullptr, ldM, rowinfo + m0, Mc, Mcp, V, Vp}, st);
         // dY = dz U   (contraction over the vocabulary)
         launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st);
         if (dU) {

@@ -62,7 +62,11 @@ __device__ __forceinline__ bool tile_of_block(int bid, int nblocks, int tiles_m,
     const int per_xcd = nblocks >> 3;
     const int lid = (bid & 7) * per_xcd + (bid >> 3);
     if (lid >= tiles_m * tiles_n) return false;
+#ifdef CPH_GM
+    constexpr int GM = CPH_GM;
+#else
     constexpr int GM = 8;
+#endif
     const int per_group = GM * tiles_n;
     const int group = lid / per_group;
     const int first_m = group * GM;
@@ -423,45 +427,56 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // No load is ever issued for a tile past the end of K: a late arrival would land in LDS while the
+    // epilogue is using it.  The last two K-steps are therefore peeled off with their loads removed.
     const int KT = g.K / BK;
 #pragma unroll
     for (int q = 0; q < NLOAD; ++q) load_one(0, 0, q);
+    if (KT > 1) {
 #pragma unroll
-    for (int q = 0; q < NLOAD / 2; ++q) load_one(1, 1, q);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (NLOAD / 2));   // vmcnt(NLOAD/2): tile 0 has landed
+        for (int q = 0; q < NLOAD / 2; ++q) load_one(1, 1, q);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (NLOAD / 2));   // vmcnt(NLOAD/2): tile 0 has landed
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < NFRAG; ++q) frag_one(smem, 0, 0, q);
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        const char *st = smem + cur * Cfg::STAGE_BYTES;
-        const char *nx = smem + (cur ^ 1) * Cfg::STAGE_BYTES;
-        CPH_PHASE(0, st, 1, true, kt + 1, cur ^ 1, NLOAD / 2)
-        CPH_PHASE(1, st, 2, false, 0, 0, 0)
-        CPH_PHASE(0, st, 3, false, 0, 0, 0)
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): tile kt+1 is complete in the other stage
-        __syncthreads();
-        CPH_PHASE(1, nx, 0, true, kt + 2, cur, 0)
+#define CPH_K_STEP_DIRECT(KT_, LOAD_NEXT, LOAD_AFTER)                                              \
+    {                                                                                              \
+        const int cur = (KT_) & 1;                                                                 \
+        const char *st = smem + cur * Cfg::STAGE_BYTES;                                            \
+        const char *nx = smem + (cur ^ 1) * Cfg::STAGE_BYTES;                                      \
+        CPH_PHASE(0, st, 1, LOAD_NEXT, (KT_) + 1, cur ^ 1, NLOAD / 2)                              \
+        CPH_PHASE(1, st, 2, false, 0, 0, 0)                                                        \
+        CPH_PHASE(0, st, 3, false, 0, 0, 0)                                                        \
+        __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): tile kt+1 is complete in the other stage */ \
+        __syncthreads();                                                                           \
+        CPH_PHASE(1, nx, 0, LOAD_AFTER, (KT_) + 2, cur, 0)                                         \
     }
+    int kt = 0;
+    for (; kt < KT - 2; ++kt) CPH_K_STEP_DIRECT(kt, true, true)
+    if (kt == KT - 2) {
+        CPH_K_STEP_DIRECT(kt, true, false)
+        ++kt;
+    }
+    CPH_K_STEP_DIRECT(kt, false, false)
+#undef CPH_K_STEP_DIRECT
 #undef CPH_PHASE
 #undef CPH_PIN
 }
 
 // Generic kernel: main loop + epilogue functor.  Epi::operator() receives the accumulators of one
 // wavefront together with the global row/column of its sub-tile's origin.
-#ifdef CPH_DBG_CLOCK
-__device__ long long g_dbg_clk[2];
-#endif
+// One workgroup per output tile.  (A persistent variant that walks several tiles per workgroup was
+// measured: the extra live state made the compiler spill accumulators and it ran slower.)
 template <class Cfg, class Epi>
 __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi epi)
 {
     __shared__ __attribute__((aligned(16))) char smem[Cfg::LDS_BYTES];
     int tm, tn;
     if (!tile_of_block(blockIdx.x, gridDim.x, g.tiles_m, g.tiles_n, tm, tn)) return;
-#ifdef CPH_DBG_CLOCK
-    const long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
-#endif
     f32x16_t acc[Cfg::TM][Cfg::TN];
 #if defined(CPH_MAINLOOP_SIMPLE)
     gemm_nt_mainloop<Cfg>(g, tm, tn, smem, acc);
@@ -474,12 +489,6 @@ __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi ep
     const int row0 = tm * Cfg::BM + (wave / Cfg::WN) * Cfg::WTM;
     const int col0 = tn * Cfg::BN + (wave % Cfg::WN) * Cfg::WTN;
     epi.template run<Cfg>(acc, row0, col0, lane, wave, tn, smem);
-#ifdef CPH_DBG_CLOCK
-    if (blockIdx.x == 8 * 100 && threadIdx.x == 0) {
-        g_dbg_clk[0] = clock64() - dbg_c0;
-        g_dbg_clk[1] = wall_clock64() - dbg_w0;
-    }
-#endif
 }
 
 template <class Cfg, class Epi>
