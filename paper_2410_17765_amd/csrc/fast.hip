@@ -63,9 +63,36 @@ struct EpiStoreF32 {
     }
 };
 
+// Cross-lane steps of the row statistics, as data-parallel-primitive moves (no LDS traffic):
+// quad swaps, mirror inside 8 and inside 16 lanes give every lane of a 16-lane row the row's value;
+// the last lane of rows 0 and 2 is then broadcast into rows 1 and 3.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_move(float old, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = fmaxf(v, dpp_move<0xB1>(v, v));    // lane ^ 1
+    v = fmaxf(v, dpp_move<0x4E>(v, v));    // lane ^ 2
+    v = fmaxf(v, dpp_move<0x141>(v, v));   // mirror within 8
+    v = fmaxf(v, dpp_move<0x140>(v, v));   // mirror within 16
+    return v;
+}
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_move<0xB1>(v, v);
+    v += dpp_move<0x4E>(v, v);
+    v += dpp_move<0x141>(v, v);
+    v += dpp_move<0x140>(v, v);
+    return v;
+}
+
 // Running statistics of the logits (eq. 5 in log space): for every row of the wavefront's
 // sub-tile the maximum and the sum of exp(z - max) over its columns.  One (max, sum) pair per
 // row and per (tile column, wavefront column) goes to `part`; the logits themselves are dropped.
+// Each 16-lane row first forms its own (max, sum); the two rows that share an output row are merged
+// in lanes 16..31 / 48..63, whose first lane writes the pair.
 struct EpiRowStats {
     float2 *part;   // [M, parts]
     int parts;      // tiles_n * WN
@@ -74,6 +101,9 @@ struct EpiRowStats {
     __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int tn, char *) const
     {
         const int slot = tn * C::WN + (wave % C::WN);
+        bool valid[C::TN];
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j) valid[j] = col0 + acc_col(j, lane) < V;
 #pragma unroll
         for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -81,18 +111,23 @@ struct EpiRowStats {
                 float mx = -INFINITY;
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j)
-                    if (col0 + acc_col(j, lane) < V) mx = fmaxf(mx, acc[i][j][v]);
-#pragma unroll
-                for (int off = 16; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+                    if (valid[j]) mx = fmaxf(mx, acc[i][j][v]);
+                mx = row16_max(mx);
                 const float ref = (mx == -INFINITY) ? 0.f : mx;
                 float s = 0.f;
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j)
-                    if (col0 + acc_col(j, lane) < V) s += __expf(acc[i][j][v] - ref);
-#pragma unroll
-                for (int off = 16; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
+                    if (valid[j]) s += __expf(acc[i][j][v] - ref);
+                s = row16_sum(s);
+                // rows 1 and 3 of the wavefront fetch the pair of rows 0 and 2 and merge
+                const float mo = dpp_move<0x142, 0xA>(-INFINITY, mx);
+                const float so = dpp_move<0x142, 0xA>(0.f, s);
+                const float mm = fmaxf(mx, mo);
+                const float mref = (mm == -INFINITY) ? 0.f : mm;
+                const float ss = s * __expf(ref - mref) + so * __expf(((mo == -INFINITY) ? 0.f : mo) - mref);
                 const int r = row0 + acc_row(i, v, lane);
-                if ((lane & 31) == 0 && r < M) part[(size_t)r * parts + slot] = make_float2(mx, s);
+                if ((lane & 31) == 16 && r < M)
+                    part[(size_t)r * parts + slot] = make_float2(mm, (mm == -INFINITY) ? 0.f : ss);
             }
     }
 };
