@@ -250,14 +250,10 @@ __global__ void __launch_bounds__(kBlock) k_row_finish(size_t M, int d, int r, i
     if (lane == 0) C_out[m] = (x >= 0) ? zt - lse : 0.f;
 }
 
-// Token draw for (b, s) from the statistics of head row (b, s, a*) ("Sampling method"), in three
-// small kernels.  The GEMM left one (max, sum exp) pair per 128-column segment of the vocabulary.
-//  1. k_draft_segment: the segment masses sum_j exp(max_j - lse) are accumulated in vocabulary order
-//     in fp64 (lane-local runs, then a wavefront scan) until the running sum passes u;
-//  2. k_draft_logits: the 128 logits of that segment are recomputed, one wavefront per column
-//     (fp32 dot products of U rows with the bf16 y);
-//  3. k_draft_pick: the scan continues token by token inside the segment.
-// Convention: first index whose running sum exceeds u; V-1 if none does.
+// ------------------------------------------------------------------------------------------
+// draft step ("Sampling method"): small kernels around the two streaming GEMMs
+// ------------------------------------------------------------------------------------------
+
 __device__ __forceinline__ double wave_scan_inclusive(double v, int lane)
 {
 #pragma unroll
@@ -268,20 +264,93 @@ __device__ __forceinline__ double wave_scan_inclusive(double v, int lane)
     return v;
 }
 
-__global__ void __launch_bounds__(kWave) k_draft_segment(int n, int r, int parts, const float2 *__restrict__ part,
-                                                         const float *__restrict__ lse,
-                                                         const int32_t *__restrict__ alpha,
-                                                         const float *__restrict__ uniforms, int32_t *__restrict__ seg_out,
-                                                         double *__restrict__ base_out)
+// fp32 dot product of two bf16 vectors of length d (a multiple of 64) over one wavefront, 16-byte loads
+__device__ __forceinline__ float wave_dot_bf16(const bf16_t *__restrict__ a, const bf16_t *__restrict__ b, int d, int lane)
 {
+    const u32x4_t *pa = reinterpret_cast<const u32x4_t *>(a);
+    const u32x4_t *pb = reinterpret_cast<const u32x4_t *>(b);
+    float acc = 0.f;
+    for (int k = lane; k < d / 8; k += kWave) {
+        const u32x4_t x = pa[k], y = pb[k];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc += __uint_as_float(x[e] << 16) * __uint_as_float(y[e] << 16);
+            acc += __uint_as_float(x[e] & 0xFFFF0000u) * __uint_as_float(y[e] & 0xFFFF0000u);
+        }
+    }
+    return wave_sum(acc);
+}
+
+// gate (eq. 7) and the expert draw: log w = log_softmax(G h); a* = first a whose running sum of w
+// (fp64) exceeds u, clamped to r-1.  One wavefront per row of the batch.
+__global__ void __launch_bounds__(kWave) k_draft_gate_pick(int d, int n, int r, const bf16_t *__restrict__ H,
+                                                           const bf16_t *__restrict__ G,
+                                                           const float *__restrict__ uniforms, float *__restrict__ logw,
+                                                           int32_t *__restrict__ alpha)
+{
+    __shared__ float w_s[kWave];
+    const size_t b = blockIdx.x;
+    const int lane = threadIdx.x;
+    float mine = -INFINITY;
+    for (int a = 0; a < r; ++a) {
+        const float p = wave_dot_bf16(G + (size_t)a * d, H + b * d, d, lane);
+        if (lane == a) mine = p;
+    }
+    const float mx = wave_max(mine);
+    const float s = wave_sum(lane < r ? expf(mine - mx) : 0.f);
+    const float lse = mx + logf(s);
+    if (lane < r) {
+        logw[b * r + lane] = mine - lse;
+        w_s[lane] = expf(mine - lse);
+    }
+    __syncthreads();
+    if (lane == 0) {
+        const double u = (double)uniforms[b * (1 + n)];
+        double c = 0.0;
+        int pick = r - 1;
+        bool found = false;
+        for (int a = 0; a < r; ++a) {
+            c += (double)w_s[a];
+            if (!found && c > u) { pick = a; found = true; }
+        }
+        alpha[b] = pick;
+    }
+}
+
+// Per (b, s): the log-normalisers of its r head rows from the per-segment statistics (eq. 5), then for
+// the drawn expert's row the segment of the vocabulary in which the running sum of probabilities
+// passes u: segment masses exp(max_j - lse) * sum_j accumulated in vocabulary order in fp64
+// (lane-local runs, then a wavefront scan).  seg = -1 if the sum never passes u.
+__global__ void __launch_bounds__(kBlock) k_draft_lse_segment(int n, int r, int parts, const float2 *__restrict__ part,
+                                                              const int32_t *__restrict__ alpha,
+                                                              const float *__restrict__ uniforms,
+                                                              float *__restrict__ lse_out, int32_t *__restrict__ seg_out,
+                                                              double *__restrict__ base_out)
+{
+    __shared__ float lse_s[64];
     const size_t bs = blockIdx.x;                 // b*n + s
     const size_t b = bs / n;
     const int s = (int)(bs % n);
-    const size_t m = bs * r + alpha[b];
-    const float l = lse[m];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int a = wave; a < r; a += kBlock / kWave) {
+        const float2 *pm = part + (bs * r + a) * parts;
+        float mx = -INFINITY, l = 0.f;
+        for (int p = lane; p < parts; p += kWave) {
+            const float2 q = pm[p];
+            if (q.x > mx) { l = l * __expf(mx - q.x) + q.y; mx = q.x; }
+            else if (q.x != -INFINITY) l += q.y * __expf(q.x - mx);
+        }
+        const float Mx = wave_max(mx);
+        const float L = wave_sum(mx == -INFINITY ? 0.f : l * __expf(mx - Mx));
+        const float lse = Mx + logf(L);
+        if (lane == 0) { lse_out[bs * r + a] = lse; lse_s[a] = lse; }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const int astar = alpha[b];
+    const float l = lse_s[astar];
     const double u = (double)uniforms[b * (1 + n) + 1 + s];
-    const float2 *pm = part + m * parts;
-    const int lane = threadIdx.x;
+    const float2 *pm = part + (bs * r + astar) * parts;
     const int per = (parts + kWave - 1) / kWave;  // consecutive segments per lane: lane order = vocabulary order
     const int lo = min(parts, lane * per), hi = min(parts, lo + per);
     double sum = 0.0;
@@ -291,7 +360,7 @@ __global__ void __launch_bounds__(kWave) k_draft_segment(int n, int r, int parts
     }
     const double incl = wave_scan_inclusive(sum, lane);
     const unsigned long long crossed = __ballot(incl > u);
-    if (crossed == 0ull) {                         // the running sum never passes u
+    if (crossed == 0ull) {
         if (lane == 0) { seg_out[bs] = -1; base_out[bs] = 0.0; }
         return;
     }
@@ -310,59 +379,47 @@ __global__ void __launch_bounds__(kWave) k_draft_segment(int n, int r, int parts
     }
 }
 
-__global__ void __launch_bounds__(kBlock) k_draft_logits(int d, int V, int n, int r, int seg_cols,
-                                                         const float *__restrict__ lse, const bf16_t *__restrict__ Y,
-                                                         const bf16_t *__restrict__ U, const int32_t *__restrict__ alpha,
-                                                         const int32_t *__restrict__ seg_in, float *__restrict__ p_out)
+// Per (b, s): recompute the logits of the chosen segment (one wavefront per column, fp32 dot products
+// of U rows with the bf16 y) and continue the scan token by token: first index whose running sum
+// exceeds u; the last token of the segment if rounding between the two passes leaves none; V-1 if
+// the running sum over the whole vocabulary never passed u.
+constexpr int kPickBlock = 1024;
+__global__ void __launch_bounds__(kPickBlock) k_draft_logits_pick(int d, int V, int n, int r, int seg_cols,
+                                                                  const float *__restrict__ lse,
+                                                                  const bf16_t *__restrict__ Y,
+                                                                  const bf16_t *__restrict__ U,
+                                                                  const int32_t *__restrict__ alpha,
+                                                                  const int32_t *__restrict__ seg_in,
+                                                                  const double *__restrict__ base_in,
+                                                                  const float *__restrict__ uniforms,
+                                                                  int32_t *__restrict__ tokens)
 {
-    const int blocks_per_row = seg_cols / (kBlock / kWave);
-    const size_t bs = blockIdx.x / blocks_per_row;
-    const int c = (blockIdx.x % blocks_per_row) * (kBlock / kWave) + (threadIdx.x >> 6);
-    const int seg = seg_in[bs];
-    if (seg < 0) return;
-    const int v = seg * seg_cols + c;
-    const int lane = threadIdx.x & 63;
-    float p = 0.f;
-    if (v < V) {
-        const size_t m = bs * r + alpha[bs / n];
-        const u32x4_t *urow = reinterpret_cast<const u32x4_t *>(U + (size_t)v * d);
-        const u32x4_t *yrow = reinterpret_cast<const u32x4_t *>(Y + m * d);
-        float acc = 0.f;
-        for (int k = lane; k < d / 8; k += kWave) {      // 8 bf16 per 16-byte load
-            const u32x4_t a = urow[k], bq = yrow[k];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                acc += __uint_as_float(a[e] << 16) * __uint_as_float(bq[e] << 16);
-                acc += __uint_as_float(a[e] & 0xFFFF0000u) * __uint_as_float(bq[e] & 0xFFFF0000u);
-            }
-        }
-        acc = wave_sum(acc);
-        p = expf(acc - lse[m]);
-    }
-    if (lane == 0) p_out[bs * seg_cols + c] = p;
-}
-
-__global__ void __launch_bounds__(kWave) k_draft_pick(int V, int seg_cols, const int32_t *__restrict__ seg_in,
-                                                      const double *__restrict__ base_in,
-                                                      const float *__restrict__ p_in, const float *__restrict__ uniforms,
-                                                      int n, int32_t *__restrict__ tokens)
-{
+    __shared__ float p_s[256];
     const size_t bs = blockIdx.x;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int seg = seg_in[bs];
     if (seg < 0) {
-        if (lane == 0) tokens[bs] = V - 1;
+        if (threadIdx.x == 0) tokens[bs] = V - 1;
         return;
     }
-    const double u = (double)uniforms[(bs / n) * (1 + n) + 1 + (bs % n)];
+    const size_t m = bs * r + alpha[bs / n];
+    const float l = lse[m];
     const int v0 = seg * seg_cols, cols = min(seg_cols, V - v0);
+    for (int c = wave; c < seg_cols; c += kPickBlock / kWave) {
+        float p = 0.f;
+        if (c < cols) p = expf(wave_dot_bf16(U + (size_t)(v0 + c) * d, Y + m * d, d, lane) - l);
+        if (lane == 0) p_s[c] = p;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const double u = (double)uniforms[(bs / n) * (1 + n) + 1 + (bs % n)];
     const int per = (seg_cols + kWave - 1) / kWave;
     const int lo = lane * per;
     double sum = 0.0;
-    for (int i = lo; i < lo + per && i < cols; ++i) sum += (double)p_in[bs * seg_cols + i];
+    for (int i = lo; i < lo + per && i < cols; ++i) sum += (double)p_s[i];
     const double incl = base_in[bs] + wave_scan_inclusive(sum, lane);
     const unsigned long long crossed = __ballot(incl > u);
-    if (crossed == 0ull) {                         // rounding between the two passes: stay in the segment
+    if (crossed == 0ull) {
         if (lane == 0) tokens[bs] = v0 + cols - 1;
         return;
     }
@@ -371,11 +428,39 @@ __global__ void __launch_bounds__(kWave) k_draft_pick(int V, int seg_cols, const
         double c = incl - sum;
         int tok = v0 + min(cols, lo + per) - 1;
         for (int i = lo; i < lo + per && i < cols; ++i) {
-            c += (double)p_in[bs * seg_cols + i];
+            c += (double)p_s[i];
             if (c > u) { tok = v0 + i; break; }
         }
         tokens[bs] = tok;
     }
+}
+
+// logq[b] = logsumexp_a( log w_a + sum_s (z_sa[tok_s] - lse_sa) ): eq. 9 at the drawn tuple over all experts
+__global__ void __launch_bounds__(kBlock) k_draft_logq(int d, int n, int r, const float *__restrict__ logw,
+                                                       const float *__restrict__ lse, const bf16_t *__restrict__ Y,
+                                                       const bf16_t *__restrict__ U, const int32_t *__restrict__ tokens,
+                                                       float *__restrict__ logq)
+{
+    __shared__ float C_s[64 * 64];
+    const size_t b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nr = n * r;
+    for (int j = wave; j < nr; j += kBlock / kWave) {
+        const size_t m = b * nr + j;
+        const int tok = tokens[b * n + j / r];
+        const float zt = wave_dot_bf16(U + (size_t)tok * d, Y + m * d, d, lane);
+        if (lane == 0) C_s[j] = zt - lse[m];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    float a = -INFINITY;
+    if (lane < r) {
+        a = logw[b * r + lane];
+        for (int s = 0; s < n; ++s) a += C_s[s * r + lane];
+    }
+    const float mx = wave_max(a);
+    const float sum = wave_sum(lane < r ? expf(a - mx) : 0.f);
+    if (lane == 0) logq[b] = mx + logf(sum);
 }
 
 // Per head row {lse, coef = up_t * gamma[t, a] (zero for dropped factors), target}; dg[t, a] = up_t (w - gamma)
@@ -518,27 +603,27 @@ inline bool dims_fit(const cp_head_desc &ds)
 
 }  // namespace
 
+// rows of a 64-row tile: the draft GEMMs with at most this many rows stream their big operand with
+// two 80 KB workgroups per compute unit instead of one 128 KB workgroup
+typedef TileCfg<64, 256, 1, 4> CfgSkinny;
+
 struct DraftWs {
-    size_t logw, w, Y, part, lse, C, nll, seg, base, p, total;
-    int parts;
+    size_t logw, Y, part, lse, seg, base, total;
+    int parts_max;
 };
 inline DraftWs draft_ws(const cp_head_desc &ds)
 {
     DraftWs f;
     const size_t M = (size_t)ds.T * ds.n * ds.r;
-    f.parts = ((ds.V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+    f.parts_max = ((ds.V + Cfg::BN - 1) / Cfg::BN) * CfgSkinny::WN;   // the finer of the two segmentations
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     f.logw = take((size_t)ds.T * ds.r * 4);
-    f.w = take((size_t)ds.T * ds.r * 4);
     f.Y = take(M * ds.d * 2);
-    f.part = take(M * f.parts * sizeof(float2));
+    f.part = take(M * f.parts_max * sizeof(float2));
     f.lse = take(M * 4);
-    f.C = take(M * 4);
-    f.nll = take((size_t)ds.T * 4);
     f.seg = take((size_t)ds.T * ds.n * 4);
     f.base = take((size_t)ds.T * ds.n * 8);
-    f.p = take((size_t)ds.T * ds.n * Cfg::WTN * 4);
     f.total = off;
     return f;
 }
@@ -648,44 +733,50 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
 {
     if (ds.T == 0) return CP_HEAD_OK;
     if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
-    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv;
+    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
     const DraftWs f = draft_ws(ds);
     const int B = (int)ds.T, d = ds.d, V = ds.V, n = ds.n, r = ds.r;
     const size_t M = (size_t)B * n * r;
     const int nrd = n * r * d;
-    float *logw = at<float>(ws, f.logw), *w = at<float>(ws, f.w), *lse = at<float>(ws, f.lse);
-    float *C = at<float>(ws, f.C);
+    float *logw = at<float>(ws, f.logw), *lse = at<float>(ws, f.lse);
     bf16_t *Y = at<bf16_t>(ws, f.Y);
     float2 *part = at<float2>(ws, f.part);
+    int32_t *seg = at<int32_t>(ws, f.seg);
+    double *base = at<double>(ws, f.base);
+    const unsigned rows = (unsigned)(B * n);
 
-    launch_gate(ds, Hv, Gv, logw, w, st);                                                  // eq. 7
-    launch_pick_alpha(ds, w, uniforms, alpha, st);                                         // a* ~ w
-    // y = W_sa h, rounded to bf16 (part of the draft distribution's definition); streams W once
-    launch_gemm_nt<Cfg>("draft_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
-    // z = U y for all B*n*r rows with running statistics; streams U once, logits are not stored
-    launch_gemm_nt<Cfg>("draft_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);
     {
-        ProfileScope prof("draft_row_lse", (double)M * f.parts * 8, st);
-        k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, r, f.parts, part, Y, nullptr, U, nullptr,
-                                                                       lse, nullptr);
+        ProfileScope prof("draft_gate_pick", (double)B * r * d * 2, st);
+        k_draft_gate_pick<<<(unsigned)B, kWave, 0, st>>>(d, n, r, H, G, uniforms, logw, alpha);   // eq. 7, a* ~ w
+    }
+    // y = W_sa h, rounded to bf16 (part of the draft distribution's definition); streams W once
+    if (B <= CfgSkinny::BM)
+        launch_gemm_nt<CfgSkinny>("draft_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
+    else
+        launch_gemm_nt<Cfg>("draft_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
+    // z = U y for all B*n*r rows with running statistics; streams U once, logits are not stored
+    int parts, seg_cols;
+    if (M <= (size_t)CfgSkinny::BM) {
+        parts = ((V + CfgSkinny::BN - 1) / CfgSkinny::BN) * CfgSkinny::WN;
+        seg_cols = CfgSkinny::WTN;
+        launch_gemm_nt<CfgSkinny>("draft_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
+    } else {
+        parts = ((V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+        seg_cols = Cfg::WTN;
+        launch_gemm_nt<Cfg>("draft_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
     }
     {
-        ProfileScope prof("draft_token", (double)B * n * Cfg::WTN * d * 2, st);
-        int32_t *seg = at<int32_t>(ws, f.seg);
-        double *base = at<double>(ws, f.base);
-        float *pseg = at<float>(ws, f.p);
-        const unsigned rows = (unsigned)(B * n);
-        k_draft_segment<<<rows, kWave, 0, st>>>(n, r, f.parts, part, lse, alpha, uniforms, seg, base);
-        k_draft_logits<<<rows * (Cfg::WTN / (kBlock / kWave)), kBlock, 0, st>>>(d, V, n, r, Cfg::WTN, lse, Y, U, alpha,
-                                                                                seg, pseg);
-        k_draft_pick<<<rows, kWave, 0, st>>>(V, Cfg::WTN, seg, base, pseg, uniforms, n, tokens);
+        ProfileScope prof("draft_lse_segment", (double)M * parts * 8, st);
+        k_draft_lse_segment<<<rows, kBlock, 0, st>>>(n, r, parts, part, alpha, uniforms, lse, seg, base);
+    }
+    {
+        ProfileScope prof("draft_logits_pick", (double)rows * seg_cols * d * 2, st);
+        k_draft_logits_pick<<<rows, kPickBlock, 0, st>>>(d, V, n, r, seg_cols, lse, Y, U, alpha, seg, base, uniforms,
+                                                        tokens);
     }
     if (logq) {
         ProfileScope prof("draft_logq", (double)M * d * 4, st);
-        // eq. 9 at the drawn tuple, over all experts: the loss kernels with the tokens as targets
-        k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, r, f.parts, nullptr, Y, nullptr, U, tokens,
-                                                                       lse, C);
-        launch_mixture(ds, logw, C, logq, nullptr, 1.f, st);
+        k_draft_logq<<<(unsigned)B, kBlock, 0, st>>>(d, n, r, logw, lse, Y, U, tokens, logq);
     }
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }

@@ -353,7 +353,12 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     constexpr int NLOAD = Cfg::A_PASSES + Cfg::B_PASSES;     // direct loads per wavefront and K-step
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
     static_assert(BK == 64, "four phases of k = 16");
-    static_assert(NMFMA % NFRAG == 0 && NLOAD % 2 == 0 && NLOAD / 2 <= NFRAG, "schedule slots");
+#ifdef CPH_LOADS_EARLY
+    constexpr int NEARLY = CPH_LOADS_EARLY;                  // loads of tile kt+2 issued right after the barrier
+#else
+    constexpr int NEARLY = NLOAD / 2;
+#endif
+    static_assert(NEARLY >= 0 && NEARLY <= NLOAD && NFRAG <= NMFMA, "schedule slots");
     typedef __attribute__((address_space(3))) void lds_void;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -409,15 +414,16 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
 #define CPH_PIN() __builtin_amdgcn_sched_barrier(0)
     // one phase: MFMAs on fragment buffer BUF, fragments of (ST, KK) into the other buffer and,
     // if LOAD_KT >= 0, the loads LOAD_Q0 .. LOAD_Q0 + NLOAD/2 - 1 of tile LOAD_KT into LOAD_STAGE
-#define CPH_PHASE(BUF, ST, KK, DO_LOAD, LOAD_KT, LOAD_STAGE, LOAD_Q0)                              \
-    _Pragma("unroll") for (int q = 0; q < NFRAG; ++q) {                                            \
-        _Pragma("unroll") for (int e = 0; e < NMFMA / NFRAG; ++e) {                                \
-            mfma_one(BUF, q * (NMFMA / NFRAG) + e);                                                \
-            if (e == 0 && (DO_LOAD) && q < NLOAD / 2) { CPH_PIN(); load_one(LOAD_KT, LOAD_STAGE, (LOAD_Q0) + q); } \
-            CPH_PIN();                                                                             \
-        }                                                                                          \
-        frag_one(ST, KK, (BUF) ^ 1, q);                                                            \
+#define CPH_PHASE(BUF, ST, KK, DO_LOAD, LOAD_KT, LOAD_STAGE, LOAD_Q0, LOAD_CNT)                    \
+    _Pragma("unroll") for (int m = 0; m < NMFMA; ++m) {                                            \
+        mfma_one(BUF, m);                                                                          \
         CPH_PIN();                                                                                 \
+        if ((DO_LOAD) && (LOAD_CNT) > 0) {                                                         \
+            _Pragma("unroll") for (int q = 0; q < (LOAD_CNT); ++q)                                 \
+                if ((q * NMFMA) / ((LOAD_CNT) > 0 ? (LOAD_CNT) : 1) == m) { load_one(LOAD_KT, LOAD_STAGE, (LOAD_Q0) + q); CPH_PIN(); } \
+        }                                                                                          \
+        _Pragma("unroll") for (int q = 0; q < NFRAG; ++q)                                          \
+            if (((q + 1) * NMFMA) / NFRAG - 1 == m) { frag_one(ST, KK, (BUF) ^ 1, q); CPH_PIN(); } \
     }
 
 #pragma unroll
@@ -434,8 +440,8 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     for (int q = 0; q < NLOAD; ++q) load_one(0, 0, q);
     if (KT > 1) {
 #pragma unroll
-        for (int q = 0; q < NLOAD / 2; ++q) load_one(1, 1, q);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (NLOAD / 2));   // vmcnt(NLOAD/2): tile 0 has landed
+        for (int q = 0; q < NEARLY; ++q) load_one(1, 1, q);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (NEARLY & 15) | ((NEARLY >> 4) << 14));   // vmcnt(NEARLY): tile 0 has landed
     } else {
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
@@ -448,12 +454,12 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
         const int cur = (KT_) & 1;                                                                 \
         const char *st = smem + cur * Cfg::STAGE_BYTES;                                            \
         const char *nx = smem + (cur ^ 1) * Cfg::STAGE_BYTES;                                      \
-        CPH_PHASE(0, st, 1, LOAD_NEXT, (KT_) + 1, cur ^ 1, NLOAD / 2)                              \
-        CPH_PHASE(1, st, 2, false, 0, 0, 0)                                                        \
-        CPH_PHASE(0, st, 3, false, 0, 0, 0)                                                        \
+        CPH_PHASE(0, st, 1, LOAD_NEXT, (KT_) + 1, cur ^ 1, NEARLY, NLOAD - NEARLY)                 \
+        CPH_PHASE(1, st, 2, false, 0, 0, 0, 0)                                                     \
+        CPH_PHASE(0, st, 3, false, 0, 0, 0, 0)                                                     \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): tile kt+1 is complete in the other stage */ \
         __syncthreads();                                                                           \
-        CPH_PHASE(1, nx, 0, LOAD_AFTER, (KT_) + 2, cur, 0)                                         \
+        CPH_PHASE(1, nx, 0, LOAD_AFTER, (KT_) + 2, cur, 0, NEARLY)                                 \
     }
     int kt = 0;
     for (; kt < KT - 2; ++kt) CPH_K_STEP_DIRECT(kt, true, true)
