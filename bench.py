@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per two threads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
+    ap.add_argument("--no-draft", action="store_true", help="loss workloads: skip the appended draft-step measurements")
     return ap.parse_args()
 
 
@@ -136,10 +137,24 @@ def bench_loss(args):
                      "rate": (k[3] / (k[2] * 1e-3) / 1e12) if k[2] > 0 else None,
                      "rate_unit": "TFLOP/s" if k[0].startswith("gemm_") else "TB/s"} for k in kernels],
     }
+    del ws, ctx, dW, dH, dU, H, h
+    torch.cuda.empty_cache()
+    if not args.no_draft:
+        # the forward-only draft step of the same method (its own workload shape), as extra context
+        out["draft"] = []
+        for B in (1, 8, 64):
+            a = argparse.Namespace(**vars(args))
+            a.batch, a.steps, a.warmup = B, 20, 3
+            dr = bench_draft(a)
+            out["draft"].append({"B": B, "ms_per_step": dr["ms_per_step"], "ms_per_step_graph": dr["ms_per_step_graph"],
+                                 "hbm_gbs": dr["roofline"]["achieved"], "frac_of_hbm_peak": dr["roofline"]["frac"],
+                                 "config": dr["config"]})
     if not args.no_cpu_baseline:
-        del ws, ctx, dW
         out["cpu_baseline"] = cpu_baseline_loss(cfg, inp, args.cpu_positions)
     return out
+
+
+_DRAFT_CACHE = {}
 
 
 def bench_draft(args):
@@ -149,9 +164,13 @@ def bench_draft(args):
     cfg = synth.CONFIGS["draft"].with_(T=args.batch)
     binding.lib()
     dev = torch.device("cuda:0")
-    inp = synth.make_inputs(cfg)
-    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
-    H = head.to_device(inp["H"], cfg.dtype)
+    if "head" not in _DRAFT_CACHE:      # the weights do not depend on the batch size
+        full = synth.CONFIGS["draft"].with_(T=64)
+        inp = synth.make_inputs(full)
+        _DRAFT_CACHE["head"] = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+        _DRAFT_CACHE["H"] = inp["H"]
+    h = _DRAFT_CACHE["head"]
+    H = head.to_device(_DRAFT_CACHE["H"][:cfg.T], cfg.dtype)
     u = torch.from_numpy(synth.uniforms(cfg.T, cfg.n)).to(dev)
     ds = h.desc(cfg.T)
     ws = torch.empty(binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT), dtype=torch.uint8, device=dev)

@@ -282,46 +282,40 @@ __device__ __forceinline__ float wave_dot_bf16(const bf16_t *__restrict__ a, con
 }
 
 // gate (eq. 7) and the expert draw: log w = log_softmax(G h); a* = first a whose running sum of w
-// (fp64) exceeds u, clamped to r-1.  One wavefront per row of the batch.
-__global__ void __launch_bounds__(kWave) k_draft_gate_pick(int d, int n, int r, const bf16_t *__restrict__ H,
-                                                           const bf16_t *__restrict__ G,
-                                                           const float *__restrict__ uniforms, float *__restrict__ logw,
-                                                           int32_t *__restrict__ alpha)
+// (fp64) exceeds u, clamped to r-1.  One block per row of the batch, one wavefront per expert.
+constexpr int kWideBlock = 1024;
+__global__ void __launch_bounds__(kWideBlock) k_draft_gate_pick(int d, int n, int r, const bf16_t *__restrict__ H,
+                                                                const bf16_t *__restrict__ G,
+                                                                const float *__restrict__ uniforms,
+                                                                float *__restrict__ logw, int32_t *__restrict__ alpha)
 {
-    __shared__ float w_s[kWave];
+    __shared__ float g_s[kWave];
     const size_t b = blockIdx.x;
-    const int lane = threadIdx.x;
-    float mine = -INFINITY;
-    for (int a = 0; a < r; ++a) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int a = wave; a < r; a += kWideBlock / kWave) {
         const float p = wave_dot_bf16(G + (size_t)a * d, H + b * d, d, lane);
-        if (lane == a) mine = p;
+        if (lane == 0) g_s[a] = p;
     }
+    __syncthreads();
+    if (wave != 0) return;
+    const float mine = lane < r ? g_s[lane] : -INFINITY;
     const float mx = wave_max(mine);
     const float s = wave_sum(lane < r ? expf(mine - mx) : 0.f);
     const float lse = mx + logf(s);
-    if (lane < r) {
-        logw[b * r + lane] = mine - lse;
-        w_s[lane] = expf(mine - lse);
-    }
-    __syncthreads();
-    if (lane == 0) {
-        const double u = (double)uniforms[b * (1 + n)];
-        double c = 0.0;
-        int pick = r - 1;
-        bool found = false;
-        for (int a = 0; a < r; ++a) {
-            c += (double)w_s[a];
-            if (!found && c > u) { pick = a; found = true; }
-        }
-        alpha[b] = pick;
-    }
+    const float w = lane < r ? expf(mine - lse) : 0.f;
+    if (lane < r) logw[b * r + lane] = mine - lse;
+    // inclusive running sum of w in expert order, fp64
+    const double incl = wave_scan_inclusive((double)w, lane);
+    const double u = (double)uniforms[b * (1 + n)];
+    const unsigned long long crossed = __ballot(lane < r && incl > u);
+    if (lane == 0) alpha[b] = crossed ? __ffsll((long long)crossed) - 1 : r - 1;
 }
 
 // Per (b, s): the log-normalisers of its r head rows from the per-segment statistics (eq. 5), then for
 // the drawn expert's row the segment of the vocabulary in which the running sum of probabilities
 // passes u: segment masses exp(max_j - lse) * sum_j accumulated in vocabulary order in fp64
 // (lane-local runs, then a wavefront scan).  seg = -1 if the sum never passes u.
-__global__ void __launch_bounds__(kBlock) k_draft_lse_segment(int n, int r, int parts, const float2 *__restrict__ part,
+__global__ void __launch_bounds__(kWideBlock) k_draft_lse_segment(int n, int r, int parts, const float2 *__restrict__ part,
                                                               const int32_t *__restrict__ alpha,
                                                               const float *__restrict__ uniforms,
                                                               float *__restrict__ lse_out, int32_t *__restrict__ seg_out,
@@ -332,7 +326,7 @@ __global__ void __launch_bounds__(kBlock) k_draft_lse_segment(int n, int r, int 
     const size_t b = bs / n;
     const int s = (int)(bs % n);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int a = wave; a < r; a += kBlock / kWave) {
+    for (int a = wave; a < r; a += kWideBlock / kWave) {
         const float2 *pm = part + (bs * r + a) * parts;
         float mx = -INFINITY, l = 0.f;
         for (int p = lane; p < parts; p += kWave) {
@@ -405,10 +399,33 @@ __global__ void __launch_bounds__(kPickBlock) k_draft_logits_pick(int d, int V, 
     const size_t m = bs * r + alpha[bs / n];
     const float l = lse[m];
     const int v0 = seg * seg_cols, cols = min(seg_cols, V - v0);
-    for (int c = wave; c < seg_cols; c += kPickBlock / kWave) {
-        float p = 0.f;
-        if (c < cols) p = expf(wave_dot_bf16(U + (size_t)(v0 + c) * d, Y + m * d, d, lane) - l);
-        if (lane == 0) p_s[c] = p;
+    // a wavefront owns up to four columns at a time and walks k for all of them together
+    constexpr int NW = kPickBlock / kWave, CW = 4;
+    const u32x4_t *yrow = reinterpret_cast<const u32x4_t *>(Y + m * d);
+    for (int c0 = wave * CW; c0 < seg_cols; c0 += NW * CW) {
+        float acc[CW] = {0.f, 0.f, 0.f, 0.f};
+        const u32x4_t *urow[CW];
+#pragma unroll
+        for (int e = 0; e < CW; ++e)
+            urow[e] = reinterpret_cast<const u32x4_t *>(U + (size_t)(v0 + min(c0 + e, cols - 1)) * d);
+        for (int k = lane; k < d / 8; k += kWave) {
+            const u32x4_t yv = yrow[k];
+            u32x4_t uv[CW];
+#pragma unroll
+            for (int e = 0; e < CW; ++e) uv[e] = urow[e][k];
+#pragma unroll
+            for (int e = 0; e < CW; ++e)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc[e] += __uint_as_float(uv[e][q] << 16) * __uint_as_float(yv[q] << 16);
+                    acc[e] += __uint_as_float(uv[e][q] & 0xFFFF0000u) * __uint_as_float(yv[q] & 0xFFFF0000u);
+                }
+        }
+#pragma unroll
+        for (int e = 0; e < CW; ++e) {
+            const float z = wave_sum(acc[e]);
+            if (lane == 0 && c0 + e < seg_cols) p_s[c0 + e] = (c0 + e < cols) ? expf(z - l) : 0.f;
+        }
     }
     __syncthreads();
     if (wave != 0) return;
@@ -436,7 +453,7 @@ __global__ void __launch_bounds__(kPickBlock) k_draft_logits_pick(int d, int V, 
 }
 
 // logq[b] = logsumexp_a( log w_a + sum_s (z_sa[tok_s] - lse_sa) ): eq. 9 at the drawn tuple over all experts
-__global__ void __launch_bounds__(kBlock) k_draft_logq(int d, int n, int r, const float *__restrict__ logw,
+__global__ void __launch_bounds__(kWideBlock) k_draft_logq(int d, int n, int r, const float *__restrict__ logw,
                                                        const float *__restrict__ lse, const bf16_t *__restrict__ Y,
                                                        const bf16_t *__restrict__ U, const int32_t *__restrict__ tokens,
                                                        float *__restrict__ logq)
@@ -445,7 +462,7 @@ __global__ void __launch_bounds__(kBlock) k_draft_logq(int d, int n, int r, cons
     const size_t b = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nr = n * r;
-    for (int j = wave; j < nr; j += kBlock / kWave) {
+    for (int j = wave; j < nr; j += kWideBlock / kWave) {
         const size_t m = b * nr + j;
         const int tok = tokens[b * n + j / r];
         const float zt = wave_dot_bf16(U + (size_t)tok * d, Y + m * d, d, lane);
@@ -747,7 +764,7 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
 
     {
         ProfileScope prof("draft_gate_pick", (double)B * r * d * 2, st);
-        k_draft_gate_pick<<<(unsigned)B, kWave, 0, st>>>(d, n, r, H, G, uniforms, logw, alpha);   // eq. 7, a* ~ w
+        k_draft_gate_pick<<<(unsigned)B, kWideBlock, 0, st>>>(d, n, r, H, G, uniforms, logw, alpha);   // eq. 7, a* ~ w
     }
     // y = W_sa h, rounded to bf16 (part of the draft distribution's definition); streams W once
     if (B <= CfgSkinny::BM)
@@ -767,7 +784,7 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
     }
     {
         ProfileScope prof("draft_lse_segment", (double)M * parts * 8, st);
-        k_draft_lse_segment<<<rows, kBlock, 0, st>>>(n, r, parts, part, alpha, uniforms, lse, seg, base);
+        k_draft_lse_segment<<<rows, kWideBlock, 0, st>>>(n, r, parts, part, alpha, uniforms, lse, seg, base);
     }
     {
         ProfileScope prof("draft_logits_pick", (double)rows * seg_cols * d * 2, st);
@@ -776,7 +793,7 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
     }
     if (logq) {
         ProfileScope prof("draft_logq", (double)M * d * 4, st);
-        k_draft_logq<<<(unsigned)B, kBlock, 0, st>>>(d, n, r, logw, lse, Y, U, tokens, logq);
+        k_draft_logq<<<(unsigned)B, kWideBlock, 0, st>>>(d, n, r, logw, lse, Y, U, tokens, logq);
     }
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
