@@ -491,5 +491,123 @@ int CPO(sequential_conditional)(const cpo_shape *sh, const in_t *H, const in_t *
     return 0;
 }
 
+/*
+ * First-token marginal (eq. 11) in log space: logp[b, v] = log sum_a w_a P^(1)(v | a).
+ * logp[B,V].
+ */
+int CPO(first_token_logprob)(const cpo_shape *sh, const in_t *H, const in_t *W, const in_t *U, const in_t *G,
+                             double *logp)
+{
+    const int d = sh->d, V = sh->V, r = sh->r;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *y = malloc(sizeof(double) * d), *z = malloc(sizeof(double) * (size_t)r * V);
+        double *logw = malloc(sizeof(double) * r), *t = malloc(sizeof(double) * r);
+        if (!y || !z || !logw || !t) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t b = 0; b < sh->T; ++b) {
+                const in_t *h = H + (size_t)b * d;
+                gate_logw(sh, h, G, logw);
+                for (int al = 0; al < r; ++al) {
+                    double *za = z + (size_t)al * V;
+                    head_y(sh, h, W, 0, al, y);
+                    head_z(sh, U, y, za);
+                    double l = logsumexp(za, V);
+                    for (int v = 0; v < V; ++v) za[v] -= l;          /* log P^(1)(v | al) */
+                }
+                for (int v = 0; v < V; ++v) {
+                    for (int al = 0; al < r; ++al) t[al] = logw[al] + z[(size_t)al * V + v];
+                    logp[(size_t)b * V + v] = logsumexp(t, r);
+                }
+            }
+        }
+        free(y); free(z); free(logw); free(t);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * The paper's sequential scheme ("Sampling method", eq. 11-13 with the reading documented at
+ * sequential_conditional): x_1 is drawn from the first-token marginal, then each x_s from
+ *   P(x_s | x_<s) = sum_a qhat_a P^(s)(x_s | a),   qhat = softmax(q),
+ *   q_a = log w_a + sum_{k<s} log P^(k)(x_k | a)
+ * ("updating the unnormalized logits of the experts").  One uniform per token: uniforms[B,n].
+ * tokens[B,n]; logq[B] (may be NULL) = logsumexp_a q_a after the last draw, the joint
+ * log-probability (eq. 9) of the drawn tuple; cdf[B,n,V] (may be NULL): the running sums used.
+ * Inverse-CDF convention as in draft_sample.
+ */
+int CPO(draft_sample_sequential)(const cpo_shape *sh, const in_t *H, const in_t *W, const in_t *U, const in_t *G,
+                                 const double *uniforms, int32_t *tokens, double *logq, double *cdf)
+{
+    const int d = sh->d, V = sh->V, n = sh->n, r = sh->r;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *y = malloc(sizeof(double) * d), *lp = malloc(sizeof(double) * (size_t)r * V);
+        double *p = malloc(sizeof(double) * V), *q = malloc(sizeof(double) * r);
+        if (!y || !lp || !p || !q) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t b = 0; b < sh->T; ++b) {
+                const in_t *h = H + (size_t)b * d;
+                gate_logw(sh, h, G, q);
+                for (int s = 0; s < n; ++s) {
+                    for (int al = 0; al < r; ++al) {
+                        double *za = lp + (size_t)al * V;
+                        head_y(sh, h, W, s, al, y);
+                        head_z(sh, U, y, za);
+                        double l = logsumexp(za, V);
+                        for (int v = 0; v < V; ++v) za[v] -= l;      /* log P^(s)(v | al) */
+                    }
+                    double qn = logsumexp(q, r);
+                    for (int v = 0; v < V; ++v) {
+                        double acc = 0.0;
+                        for (int al = 0; al < r; ++al) acc += exp(q[al] - qn + lp[(size_t)al * V + v]);
+                        p[v] = acc;
+                    }
+                    int tok = inverse_cdf(p, V, uniforms[(size_t)b * n + s], cdf ? cdf + ((size_t)b * n + s) * V : NULL);
+                    tokens[(size_t)b * n + s] = tok;
+                    for (int al = 0; al < r; ++al) q[al] += lp[(size_t)al * V + tok];
+                }
+                if (logq) logq[b] = logsumexp(q, r);
+            }
+        }
+        free(y); free(lp); free(p); free(q);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Auxiliary balancing statistic (eq. 10): counts[a] = number of positions whose largest gate weight is
+ * expert a (first index on ties), and L_aux = sum_a (counts[a]/T - 1/r)^2.
+ */
+int CPO(aux_balance)(const cpo_shape *sh, const in_t *H, const in_t *G, int64_t *counts, double *laux)
+{
+    const int d = sh->d, r = sh->r;
+    double *logw = malloc(sizeof(double) * r);
+    if (!logw) return -1;
+    for (int a = 0; a < r; ++a) counts[a] = 0;
+    for (int64_t t = 0; t < sh->T; ++t) {
+        gate_logw(sh, H + (size_t)t * d, G, logw);
+        int best = 0;
+        for (int a = 1; a < r; ++a) if (logw[a] > logw[best]) best = a;
+        counts[best] += 1;
+    }
+    double acc = 0.0;
+    for (int a = 0; a < r; ++a) {
+        double dev = (sh->T > 0 ? (double)counts[a] / (double)sh->T : 0.0) - 1.0 / r;
+        acc += dev * dev;
+    }
+    *laux = acc;
+    free(logw);
+    return 0;
+}
+
 /* For tests of the rounding helper. */
 double CPO(round_to_bf16)(double v) { return round_to_bf16(v); }

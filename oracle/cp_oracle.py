@@ -184,6 +184,54 @@ def sequential_conditional(H, W, U, G, t: int, prefix):
     return prob
 
 
+def first_token_logprob(H, W, U, G, round_y: bool = False):
+    """logp[B,V]: log of the first-token marginal (eq. 11)."""
+    kind, (H, W, U, G) = _prep(H, W, U, G)
+    sh = _shape(H, W, U, round_y)
+    out = np.empty((sh.T, sh.V), dtype=np.float64)
+    fn = getattr(_lib(kind), f"cpo_{kind}_first_token_logprob")
+    fn.restype = ctypes.c_int
+    if fn(ctypes.byref(sh), _p(H), _p(W), _p(U), _p(G), _p(out)) != 0:
+        raise RuntimeError("oracle first_token_logprob failed")
+    return out
+
+
+def draft_sample_sequential(H, W, U, G, uniforms, round_y: bool = True, want_cdf: bool = False):
+    """The paper's sequential scheme: (tokens[B,n], logq[B]) [+ cdf[B,n,V]] from uniforms[B,n]."""
+    kind, (H, W, U, G) = _prep(H, W, U, G)
+    sh = _shape(H, W, U, round_y)
+    u = np.ascontiguousarray(uniforms, dtype=np.float64)
+    assert u.shape == (sh.T, sh.n)
+    tokens = np.empty((sh.T, sh.n), dtype=np.int32)
+    logq = np.empty(sh.T, dtype=np.float64)
+    cdf = np.empty((sh.T, sh.n, sh.V)) if want_cdf else None
+    fn = getattr(_lib(kind), f"cpo_{kind}_draft_sample_sequential")
+    fn.restype = ctypes.c_int
+    if fn(ctypes.byref(sh), _p(H), _p(W), _p(U), _p(G), _p(u), _p(tokens), _p(logq), _p(cdf)) != 0:
+        raise RuntimeError("oracle draft_sample_sequential failed")
+    return (tokens, logq, cdf) if want_cdf else (tokens, logq)
+
+
+def aux_balance(H, G):
+    """(counts[r] int64, L_aux) of eq. 10 for the positions in H."""
+    H = np.asarray(H)
+    G = np.asarray(G)
+    if H.dtype == np.float32 and G.dtype == np.float32:
+        kind, dt = "f32", np.float32
+    else:
+        kind, dt = "f64", np.float64
+    H = np.ascontiguousarray(H, dtype=dt)
+    G = np.ascontiguousarray(G, dtype=dt)
+    sh = _Shape(H.shape[0], H.shape[1], 1, 1, G.shape[0], 0)
+    counts = np.zeros(G.shape[0], dtype=np.int64)
+    laux = ctypes.c_double(0.0)
+    fn = getattr(_lib(kind), f"cpo_{kind}_aux_balance")
+    fn.restype = ctypes.c_int
+    if fn(ctypes.byref(sh), _p(H), _p(G), _p(counts), ctypes.byref(laux)) != 0:
+        raise RuntimeError("oracle aux_balance failed")
+    return counts, laux.value
+
+
 def round_to_bf16(v: float) -> float:
     fn = _lib("f64").cpo_f64_round_to_bf16
     fn.restype = ctypes.c_double

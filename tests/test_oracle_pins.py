@@ -359,3 +359,76 @@ def test_rounded_y_changes_loss_by_the_expected_amount(oracle):
     diff = np.abs(l0 - l1)
     # bf16 rounding of y perturbs each target logit by about 2^-9 |z|: visible, but small
     assert 1e-5 < diff.max() < 3e-2
+
+
+# ---------------------------------------------------------------------------
+# next rows: first-token marginal, the paper's sequential scheme, eq. 10
+# ---------------------------------------------------------------------------
+
+def test_first_token_logprob(oracle):
+    # eq. 11 in log space: a distribution over V, equal to the s = 0 conditional and to the library composition
+    H, W, U, G, X = small_problem(seed=51)
+    lp = oracle.first_token_logprob(H, W, U, G)
+    np.testing.assert_allclose(np.exp(lp).sum(axis=1), 1.0, atol=1e-12)
+    for t in range(H.shape[0]):
+        np.testing.assert_allclose(np.exp(lp[t]), oracle.sequential_conditional(H, W, U, G, t, []), rtol=1e-12)
+    logw = sps.log_softmax(H @ G.T, axis=-1)
+    Z = np.einsum("vk,tak->tav", U, np.einsum("akj,tj->tak", W[0], H))
+    ref = sps.logsumexp(logw[:, :, None] + sps.log_softmax(Z, axis=-1), axis=1)
+    np.testing.assert_allclose(lp, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_sequential_scheme_uses_the_pinned_conditionals(oracle):
+    H, W, U, G, _ = small_problem(T=3, seed=52)
+    n = W.shape[0]
+    rng = np.random.default_rng(53)
+    u = rng.random((3, n))
+    tokens, logq, cdf = oracle.draft_sample_sequential(H, W, U, G, u, round_y=False, want_cdf=True)
+    for t in range(3):
+        for s in range(n):
+            cond = oracle.sequential_conditional(H, W, U, G, t, list(tokens[t, :s]))
+            np.testing.assert_allclose(np.diff(cdf[t, s], prepend=0.0), cond, atol=1e-13)
+            v = tokens[t, s]
+            assert cdf[t, s, v] > u[t, s] and (v == 0 or cdf[t, s, v - 1] <= u[t, s])
+    # the accumulated expert log-weights end as the joint log-probability of the drawn tuple (eq. 9)
+    np.testing.assert_allclose(logq, -oracle.loss_fwd(H, W, U, G, tokens), rtol=1e-12)
+
+
+def test_sequential_scheme_samples_the_joint(oracle):
+    V, n, r, d = 4, 2, 3, 8
+    H, W, U, G, _ = small_problem(T=1, d=d, V=V, n=n, r=r, seed=43)
+    U = U * 2.0
+    B = 40000
+    rng = np.random.Generator(np.random.Philox(78))
+    u = rng.random((B, n))
+    tokens, _ = oracle.draft_sample_sequential(np.tile(H[0], (B, 1)), W, U, G, u, round_y=False)
+    tuples = np.array(list(itertools.product(range(V), repeat=n)), dtype=np.int32)
+    joint = np.exp(-oracle.loss_fwd(np.tile(H[0], (len(tuples), 1)), W, U, G, tuples))
+    counts = np.bincount(tokens[:, 0] * V + tokens[:, 1], minlength=V * V)
+    _, p = scipy.stats.chisquare(counts, joint * B)
+    assert p > 1e-3
+    # boundaries of the inverse CDF
+    t0, _ = oracle.draft_sample_sequential(H, W, U, G, np.zeros((1, n)), round_y=False)
+    t1, _ = oracle.draft_sample_sequential(H, W, U, G, np.full((1, n), np.nextafter(1.0, 0.0)), round_y=False)
+    assert (t0 == 0).all() and (t1 == V - 1).all()
+
+
+def test_aux_balance(oracle):
+    # eq. 10 on hand-built gates: G = 5 I picks the largest coordinate of h
+    r, d = 4, 4
+    G = 5.0 * np.eye(r, d)
+    H = np.array([[3, 0, 0, 0], [0, 2, 0, 0], [0, 0, 1, 0], [0, 0, 0, 4], [9, 1, 0, 0], [1, 1, 0, 0]], dtype=np.float64)
+    counts, laux = oracle.aux_balance(H, G)
+    assert counts.tolist() == [3, 1, 1, 1]          # the tie in the last row goes to the first index
+    np.testing.assert_allclose(laux, (3 / 6 - 0.25) ** 2 + 3 * (1 / 6 - 0.25) ** 2, rtol=1e-14)
+    # perfectly balanced use gives zero, a single expert gives (1 - 1/r)^2 + (r - 1)/r^2
+    counts, laux = oracle.aux_balance(np.eye(4), G)
+    assert counts.tolist() == [1, 1, 1, 1] and laux == 0.0
+    counts, laux = oracle.aux_balance(np.tile([1.0, 0, 0, 0], (7, 1)), G)
+    assert counts.tolist() == [7, 0, 0, 0]
+    np.testing.assert_allclose(laux, (1 - 1 / r) ** 2 + (r - 1) / r ** 2, rtol=1e-14)
+    # against the gate weights of the forward pass
+    Hs, W, U, Gs, X = small_problem(T=40, seed=54)
+    counts, _ = oracle.aux_balance(Hs, Gs)
+    _, logw, _, _ = oracle.loss_fwd(Hs, W, U, Gs, X, details=True)
+    assert counts.tolist() == np.bincount(np.argmax(logw, axis=1), minlength=Gs.shape[0]).tolist()
