@@ -493,10 +493,11 @@ int CPO(sequential_conditional)(const cpo_shape *sh, const in_t *H, const in_t *
 
 /*
  * First-token marginal (eq. 11) in log space: logp[b, v] = log sum_a w_a P^(1)(v | a).
- * logp[B,V].
+ * logp[B,V].  y_nudge[B,r,d] (may be NULL) is added to the first head's y before rounding, as in
+ * draft_sample (the two admissible roundings of an element on a rounding tie).
  */
 int CPO(first_token_logprob)(const cpo_shape *sh, const in_t *H, const in_t *W, const in_t *U, const in_t *G,
-                             double *logp)
+                             const double *y_nudge, double *logp)
 {
     const int d = sh->d, V = sh->V, r = sh->r;
     int fail = 0;
@@ -514,7 +515,7 @@ int CPO(first_token_logprob)(const cpo_shape *sh, const in_t *H, const in_t *W, 
                 gate_logw(sh, h, G, logw);
                 for (int al = 0; al < r; ++al) {
                     double *za = z + (size_t)al * V;
-                    head_y(sh, h, W, 0, al, y);
+                    head_y_ex(sh, h, W, 0, al, y_nudge ? y_nudge + ((size_t)b * r + al) * d : NULL, NULL, y);
                     head_z(sh, U, y, za);
                     double l = logsumexp(za, V);
                     for (int v = 0; v < V; ++v) za[v] -= l;          /* log P^(1)(v | al) */
@@ -538,10 +539,11 @@ int CPO(first_token_logprob)(const cpo_shape *sh, const in_t *H, const in_t *W, 
  * ("updating the unnormalized logits of the experts").  One uniform per token: uniforms[B,n].
  * tokens[B,n]; logq[B] (may be NULL) = logsumexp_a q_a after the last draw, the joint
  * log-probability (eq. 9) of the drawn tuple; cdf[B,n,V] (may be NULL): the running sums used.
- * Inverse-CDF convention as in draft_sample.
+ * Inverse-CDF convention as in draft_sample; y_nudge[B,n,r,d] (may be NULL) as in draft_sample.
  */
 int CPO(draft_sample_sequential)(const cpo_shape *sh, const in_t *H, const in_t *W, const in_t *U, const in_t *G,
-                                 const double *uniforms, int32_t *tokens, double *logq, double *cdf)
+                                 const double *uniforms, const double *y_nudge, int32_t *tokens, double *logq,
+                                 double *cdf)
 {
     const int d = sh->d, V = sh->V, n = sh->n, r = sh->r;
     int fail = 0;
@@ -560,7 +562,8 @@ int CPO(draft_sample_sequential)(const cpo_shape *sh, const in_t *H, const in_t 
                 for (int s = 0; s < n; ++s) {
                     for (int al = 0; al < r; ++al) {
                         double *za = lp + (size_t)al * V;
-                        head_y(sh, h, W, s, al, y);
+                        head_y_ex(sh, h, W, s, al,
+                                  y_nudge ? y_nudge + (((size_t)b * n + s) * r + al) * d : NULL, NULL, y);
                         head_z(sh, U, y, za);
                         double l = logsumexp(za, V);
                         for (int v = 0; v < V; ++v) za[v] -= l;      /* log P^(s)(v | al) */

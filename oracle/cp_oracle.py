@@ -168,10 +168,10 @@ def draft_sample(H, W, U, G, uniforms, round_y: bool = True, alpha_in=None, want
     return tuple(out)
 
 
-def sequential_conditional(H, W, U, G, t: int, prefix):
+def sequential_conditional(H, W, U, G, t: int, prefix, round_y: bool = False):
     """P(x_s | prefix) over the vocabulary for position t, s = len(prefix) (paper's sequential scheme)."""
     kind, (H, W, U, G) = _prep(H, W, U, G)
-    sh = _shape(H, W, U, False)
+    sh = _shape(H, W, U, round_y)
     prefix = np.ascontiguousarray(prefix, dtype=np.int32)
     prob = np.empty(sh.V, dtype=np.float64)
     fn = getattr(_lib(kind), f"cpo_{kind}_sequential_conditional")
@@ -184,20 +184,23 @@ def sequential_conditional(H, W, U, G, t: int, prefix):
     return prob
 
 
-def first_token_logprob(H, W, U, G, round_y: bool = False):
-    """logp[B,V]: log of the first-token marginal (eq. 11)."""
+def first_token_logprob(H, W, U, G, round_y: bool = False, y_nudge=None):
+    """logp[B,V]: log of the first-token marginal (eq. 11).  y_nudge[B,r,d] is added to y before rounding."""
     kind, (H, W, U, G) = _prep(H, W, U, G)
     sh = _shape(H, W, U, round_y)
     out = np.empty((sh.T, sh.V), dtype=np.float64)
+    nudge = None if y_nudge is None else np.ascontiguousarray(y_nudge, dtype=np.float64)
+    assert nudge is None or nudge.shape == (sh.T, sh.r, sh.d)
     fn = getattr(_lib(kind), f"cpo_{kind}_first_token_logprob")
     fn.restype = ctypes.c_int
-    if fn(ctypes.byref(sh), _p(H), _p(W), _p(U), _p(G), _p(out)) != 0:
+    if fn(ctypes.byref(sh), _p(H), _p(W), _p(U), _p(G), _p(nudge), _p(out)) != 0:
         raise RuntimeError("oracle first_token_logprob failed")
     return out
 
 
-def draft_sample_sequential(H, W, U, G, uniforms, round_y: bool = True, want_cdf: bool = False):
-    """The paper's sequential scheme: (tokens[B,n], logq[B]) [+ cdf[B,n,V]] from uniforms[B,n]."""
+def draft_sample_sequential(H, W, U, G, uniforms, round_y: bool = True, want_cdf: bool = False, y_nudge=None):
+    """The paper's sequential scheme: (tokens[B,n], logq[B]) [+ cdf[B,n,V]] from uniforms[B,n].
+    y_nudge[B,n,r,d] is added to y before rounding."""
     kind, (H, W, U, G) = _prep(H, W, U, G)
     sh = _shape(H, W, U, round_y)
     u = np.ascontiguousarray(uniforms, dtype=np.float64)
@@ -205,9 +208,11 @@ def draft_sample_sequential(H, W, U, G, uniforms, round_y: bool = True, want_cdf
     tokens = np.empty((sh.T, sh.n), dtype=np.int32)
     logq = np.empty(sh.T, dtype=np.float64)
     cdf = np.empty((sh.T, sh.n, sh.V)) if want_cdf else None
+    nudge = None if y_nudge is None else np.ascontiguousarray(y_nudge, dtype=np.float64)
+    assert nudge is None or nudge.shape == (sh.T, sh.n, sh.r, sh.d)
     fn = getattr(_lib(kind), f"cpo_{kind}_draft_sample_sequential")
     fn.restype = ctypes.c_int
-    if fn(ctypes.byref(sh), _p(H), _p(W), _p(U), _p(G), _p(u), _p(tokens), _p(logq), _p(cdf)) != 0:
+    if fn(ctypes.byref(sh), _p(H), _p(W), _p(U), _p(G), _p(u), _p(nudge), _p(tokens), _p(logq), _p(cdf)) != 0:
         raise RuntimeError("oracle draft_sample_sequential failed")
     return (tokens, logq, cdf) if want_cdf else (tokens, logq)
 

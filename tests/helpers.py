@@ -38,6 +38,27 @@ def _near_ties(y):
     return idx, nudge
 
 
+def tie_variants(y_exact, limit=3):
+    """All ways of rounding the elements of y_exact (any shape, exact fp64 values) that sit on a bf16
+    rounding tie: yields (flips, nudge) with nudge shaped like y_exact, the unflipped variant first.
+    If more than `limit` elements are on a tie, the `limit` closest to their midpoints are tried."""
+    import itertools
+    y = np.asarray(y_exact, dtype=np.float64)
+    idx, nudge = _near_ties(y.reshape(-1))
+    yield 0, np.zeros(y.shape)
+    if len(idx) == 0:
+        return
+    if len(idx) > limit:
+        keep = np.argsort(np.abs(nudge) / np.abs(y.reshape(-1)[idx]))[:limit]   # ~ distance in ulps
+        idx, nudge = idx[keep], nudge[keep]
+    for k in range(1, len(idx) + 1):
+        for subset in itertools.combinations(range(len(idx)), k):
+            nd = np.zeros(y.size)
+            for j in subset:
+                nd[idx[j]] = nudge[j]
+            yield k, nd.reshape(y.shape)
+
+
 def _valid_under_rounding_ties(oracle, H, W, U, G, u, b, s, a, v, y_exact):
     """The draw v for (b, s) under expert a is admissible if it is band-valid for some way of rounding
     the (at most 3) elements of y that sit on a rounding tie.  Returns the number of flipped elements
