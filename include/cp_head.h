@@ -66,7 +66,10 @@ enum {
     CP_HEAD_ERR_LAUNCH = -4           /* a kernel launch failed (hipGetLastError) */
 };
 
-enum { CP_HEAD_OP_LOSS_FWD = 0, CP_HEAD_OP_LOSS_BWD = 1, CP_HEAD_OP_DRAFT = 2 };
+enum {
+    CP_HEAD_OP_LOSS_FWD = 0, CP_HEAD_OP_LOSS_BWD = 1, CP_HEAD_OP_DRAFT = 2,
+    CP_HEAD_OP_FIRST_TOKEN = 3, CP_HEAD_OP_DRAFT_SEQUENTIAL = 4, CP_HEAD_OP_AUX_BALANCE = 5
+};
 
 typedef struct cp_head_desc {
     int64_t T;        /* positions (loss calls) or batch size B (draft call) */
@@ -144,6 +147,47 @@ int cp_head_draft_sample(const cp_head_desc *desc,
                          const float *uniforms,
                          int32_t *alpha, int32_t *tokens, float *logq,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * First-token marginal (eq. 11), in log space, for each of the B = desc->T rows of H:
+ *     logp[b, v] = log sum_a w_a P^(1)(v | a)
+ * This is the distribution of the next token under the head (the one a speculative verifier or
+ * the first-token loss needs).  logp[B,V] fp32, overwritten.  With bf16 storage y is rounded to
+ * bf16 as in cp_head_draft_sample.
+ */
+int cp_head_first_token_logprob(const cp_head_desc *desc,
+                                const void *H, const void *W, const void *U, const void *G,
+                                float *logp,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The paper's own sequential sampling scheme (section "Sampling method", eq. 11-13): x_1 is drawn
+ * from the first-token marginal and each further x_s from
+ *     P(x_s | x_<s) = sum_a qhat_a P^(s)(x_s | a),  qhat = softmax(q),
+ *     q_a = log w_a + sum_{k<s} log P^(k)(x_k | a)
+ * (the expert log-weights are updated after every draw; the printed eq. 12/13 omit the new token's
+ * factor and the normaliser).  It samples the same joint (eq. 2) as cp_head_draft_sample but
+ * needs no expert draw: uniforms[B,n] fp32 in [0,1), one per token; inverse-CDF convention and
+ * the bf16 rounding of y as in cp_head_draft_sample.  Outputs: tokens[B,n] int32, logq[B] fp32
+ * (may be NULL) = joint log-probability of the drawn tuple.
+ * Matrix-core path only (bf16, d a multiple of 64): other shapes return CP_HEAD_ERR_UNSUPPORTED.
+ */
+int cp_head_draft_sample_sequential(const cp_head_desc *desc,
+                                    const void *H, const void *W, const void *U, const void *G,
+                                    const float *uniforms,
+                                    int32_t *tokens, float *logq,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Auxiliary balancing statistic (section "Auxilary load balancing loss", eq. 10) over the
+ * T = desc->T positions of H: counts[a] = number of positions whose largest gate weight is
+ * expert a (first index on ties), laux = sum_a (counts[a]/T - 1/r)^2.  counts[r] int64 and
+ * laux[1] fp32 are device buffers, overwritten.  The statistic is piecewise constant in the
+ * parameters, so no gradient is defined.  d, V, n of desc other than d and r are ignored.
+ */
+int cp_head_aux_balance(const cp_head_desc *desc, const void *H, const void *G,
+                        int64_t *counts, float *laux,
+                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Optional per-kernel timing for benchmarks (not part of the method).  While

@@ -16,6 +16,7 @@ BF16 = 1
 FORCE_GENERIC = 1
 MIN_WORKSPACE = 2
 OP_LOSS_FWD, OP_LOSS_BWD, OP_DRAFT = 0, 1, 2
+OP_FIRST_TOKEN, OP_DRAFT_SEQUENTIAL, OP_AUX_BALANCE = 3, 4, 5
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcphead.so")
@@ -23,6 +24,7 @@ _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("cp_head_strerror", "cp_head_ctx_bytes", "cp_head_workspace_bytes",
            "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample",
+           "cp_head_first_token_logprob", "cp_head_draft_sample_sequential", "cp_head_aux_balance",
            "cp_head_profile_enable", "cp_head_profile_read")
 
 
@@ -59,6 +61,9 @@ def lib() -> ctypes.CDLL:
         L.cp_head_loss_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, ctypes.c_float, vp,
                                        vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_draft_sample.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_first_token_logprob.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_draft_sample_sequential.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_aux_balance.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_profile_enable.argtypes = [ctypes.c_int]
         L.cp_head_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         for name in EXPORTS[1:]:
@@ -134,6 +139,28 @@ def cp_head_draft_sample(desc: Desc, H, W, U, G, uniforms, alpha, tokens, logq, 
                                     _stream(stream))
     if rc != 0:
         raise CpHeadError(rc, "cp_head_draft_sample")
+
+
+def cp_head_first_token_logprob(desc: Desc, H, W, U, G, logp, workspace, stream=None) -> None:
+    rc = lib().cp_head_first_token_logprob(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(logp),
+                                           _ptr(workspace), _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_first_token_logprob")
+
+
+def cp_head_draft_sample_sequential(desc: Desc, H, W, U, G, uniforms, tokens, logq, workspace, stream=None) -> None:
+    rc = lib().cp_head_draft_sample_sequential(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G),
+                                               _ptr(uniforms), _ptr(tokens), _ptr(logq), _ptr(workspace),
+                                               _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_draft_sample_sequential")
+
+
+def cp_head_aux_balance(desc: Desc, H, G, counts, laux, workspace, stream=None) -> None:
+    rc = lib().cp_head_aux_balance(ctypes.byref(desc), _ptr(H), _ptr(G), _ptr(counts), _ptr(laux), _ptr(workspace),
+                                   _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_aux_balance")
 
 
 def cp_head_profile_enable(on: bool) -> None:

@@ -57,6 +57,15 @@ int check_desc(const cp_head_desc *ds)
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) != 0; }
 
+size_t workspace_need(const cp_head_desc &ds, int op)
+{
+    if (op == CP_HEAD_OP_AUX_BALANCE) return 256;   // none needed; a token size keeps the calling pattern uniform
+    if (use_fast_path(ds)) return fast_workspace_bytes(ds, op);
+    if (op == CP_HEAD_OP_FIRST_TOKEN) return generic_first_token_workspace_bytes(ds);
+    if (op == CP_HEAD_OP_DRAFT_SEQUENTIAL) return 256;   // not served on the plain path
+    return generic_workspace_bytes(ds, op);
+}
+
 }  // namespace
 
 extern "C" {
@@ -122,9 +131,8 @@ int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes)
     if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
     const int rc = check_desc(desc);
     if (rc != CP_HEAD_OK) return rc;
-    if (op != CP_HEAD_OP_LOSS_FWD && op != CP_HEAD_OP_LOSS_BWD && op != CP_HEAD_OP_DRAFT)
-        return CP_HEAD_ERR_INVALID_ARG;
-    *bytes = use_fast_path(*desc) ? fast_workspace_bytes(*desc, op) : generic_workspace_bytes(*desc, op);
+    if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_AUX_BALANCE) return CP_HEAD_ERR_INVALID_ARG;
+    *bytes = workspace_need(*desc, op);
     return CP_HEAD_OK;
 }
 
@@ -180,6 +188,46 @@ int cp_head_draft_sample(const cp_head_desc *desc, const void *H, const void *W,
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (fast) return fast_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, workspace_bytes, st);
     return generic_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, st);
+}
+
+int cp_head_first_token_logprob(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                                float *logp, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !logp)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_FIRST_TOKEN)) return CP_HEAD_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_fast_path(*desc)) return fast_first_token(*desc, H, W, U, G, logp, workspace, st);
+    return generic_first_token(*desc, H, W, U, G, logp, workspace, st);
+}
+
+int cp_head_draft_sample_sequential(const cp_head_desc *desc, const void *H, const void *W, const void *U,
+                                    const void *G, const float *uniforms, int32_t *tokens, float *logq,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !uniforms || !tokens)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!use_fast_path(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
+    if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DRAFT_SEQUENTIAL)) return CP_HEAD_ERR_WORKSPACE;
+    return fast_draft_sequential(*desc, H, W, U, G, uniforms, tokens, logq, workspace, static_cast<hipStream_t>(stream));
+}
+
+int cp_head_aux_balance(const cp_head_desc *desc, const void *H, const void *G, int64_t *counts, float *laux,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!G || !counts || !laux) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && !H) return CP_HEAD_ERR_INVALID_ARG;
+    return aux_balance(*desc, H, G, counts, laux, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

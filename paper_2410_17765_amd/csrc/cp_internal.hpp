@@ -76,6 +76,14 @@ int generic_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const
 int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                   const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 
+size_t generic_first_token_workspace_bytes(const cp_head_desc &ds);
+int generic_first_token(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                        float *logp, void *ws, hipStream_t st);
+int aux_balance(const cp_head_desc &ds, const void *H, const void *G, int64_t *counts, float *laux, hipStream_t st);
+// logp = logsumexp_a(logw + z - lse) from stored first-head logits z[(b,a), ld]; computes lse first if asked
+void launch_first_token_mix(const cp_head_desc &ds, const float *z, size_t ld, const float *lse, const float *logw,
+                            float *logp, bool compute_lse, float *lse_out, hipStream_t st);
+
 // Kernels of the generic path that the matrix-core path reuses (fp32 bookkeeping per position).
 void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *logw, float *w, hipStream_t st);
 // out[t] = sign * logsumexp_a(logw + sum_s C): sign = -1 gives the loss, +1 the joint log-probability
@@ -106,5 +114,9 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const vo
 int fast_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, size_t ws_bytes,
                hipStream_t st);
+int fast_first_token(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G, float *logp,
+                     void *ws, hipStream_t st);
+int fast_draft_sequential(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                          const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 
 }  // namespace cph

@@ -304,6 +304,7 @@ __global__ void __launch_bounds__(kWideBlock) k_draft_gate_pick(int d, int n, in
     const float lse = mx + logf(s);
     const float w = lane < r ? expf(mine - lse) : 0.f;
     if (lane < r) logw[b * r + lane] = mine - lse;
+    if (!uniforms) return;                      // log w only
     // inclusive running sum of w in expert order, fp64
     const double incl = wave_scan_inclusive((double)w, lane);
     const double u = (double)uniforms[b * (1 + n)];
@@ -480,6 +481,179 @@ __global__ void __launch_bounds__(kWideBlock) k_draft_logq(int d, int n, int r, 
     if (lane == 0) logq[b] = mx + logf(sum);
 }
 
+// The paper's sequential scheme (eq. 11-13) for one row b of the batch, all n draws in one block.
+// For step s the conditional is the mixture sum_a qhat_a P^(s)(. | a) with qhat = softmax(q),
+// q_a = log w_a + sum_{k<s} log P^(k)(x_k | a).  It is sampled exactly like the single-expert draw of
+// cp_head_draft_sample, with every mass replaced by its qhat-weighted sum over the r experts:
+// segment masses from the GEMM's per-segment statistics (fp64, vocabulary order), then the logits of
+// the crossing segment are recomputed for all r experts and the scan continues token by token.
+// y of the step's r rows is staged in LDS when it fits (r*d <= 32768 elements), else read from memory.
+constexpr int kSeqBlock = 1024;
+constexpr int kSeqYElems = 32768;
+__global__ void __launch_bounds__(kSeqBlock) k_draft_sequential(int d, int V, int n, int r, int parts, int seg_cols,
+                                                                const float2 *__restrict__ part,
+                                                                const bf16_t *__restrict__ Y,
+                                                                const bf16_t *__restrict__ U,
+                                                                const float *__restrict__ logw,
+                                                                const float *__restrict__ uniforms,
+                                                                int32_t *__restrict__ tokens, float *__restrict__ logq)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t y_s[kSeqYElems];
+    __shared__ float lse_s[64 * 64];
+    __shared__ float z_s[64 * 128];
+    __shared__ float q_s[64], qh_s[64];
+    __shared__ double wave_tot[kSeqBlock / kWave];
+    __shared__ double base_sh;
+    __shared__ int cross_sh, seg_sh;
+    const size_t b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NW = kSeqBlock / kWave;
+    const int nr = n * r;
+    const bool stage_y = r * d <= kSeqYElems;
+
+    // log-normalisers of all n*r rows of this b (eq. 5)
+    for (int j = wave; j < nr; j += NW) {
+        const float2 *pm = part + (b * nr + j) * parts;
+        float mx = -INFINITY, l = 0.f;
+        for (int p = lane; p < parts; p += kWave) {
+            const float2 qv = pm[p];
+            if (qv.x > mx) { l = l * __expf(mx - qv.x) + qv.y; mx = qv.x; }
+            else if (qv.x != -INFINITY) l += qv.y * __expf(qv.x - mx);
+        }
+        const float Mx = wave_max(mx);
+        const float L = wave_sum(mx == -INFINITY ? 0.f : l * __expf(mx - Mx));
+        if (lane == 0) lse_s[j] = Mx + logf(L);
+    }
+    if (tid < r) q_s[tid] = logw[b * r + tid];
+    __syncthreads();
+
+    for (int s = 0; s < n; ++s) {
+        const double u = (double)uniforms[b * n + s];
+        const size_t row0 = (b * n + s) * r;             // first of the r head rows of this step
+        if (wave == 0) {
+            const float qa = lane < r ? q_s[lane] : -INFINITY;
+            const float mx = wave_max(qa);
+            const float qn = mx + logf(wave_sum(lane < r ? expf(qa - mx) : 0.f));
+            if (lane < r) qh_s[lane] = expf(qa - qn);
+        }
+        if (tid == 0) cross_sh = 0x7FFFFFFF;
+        if (stage_y) {
+            const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Y + row0 * d);
+            u32x4_t *dst = reinterpret_cast<u32x4_t *>(y_s);
+            for (int i = tid; i < r * d / 8; i += kSeqBlock) dst[i] = src[i];
+        }
+        __syncthreads();
+
+        // mixture mass of every segment, running sum over the vocabulary in fp64
+        const int per = (parts + kSeqBlock - 1) / kSeqBlock;
+        const int lo = min(parts, tid * per), hi = min(parts, lo + per);
+        double sum = 0.0;
+        for (int j = lo; j < hi; ++j)
+            for (int a = 0; a < r; ++a) {
+                const float2 qv = part[(row0 + a) * parts + j];
+                if (qv.x != -INFINITY) sum += (double)(qh_s[a] * qv.y * expf(qv.x - lse_s[s * r + a]));
+            }
+        double incl = wave_scan_inclusive(sum, lane);
+        if (lane == kWave - 1) wave_tot[wave] = incl;
+        __syncthreads();
+        for (int w2 = 0; w2 < wave; ++w2) incl += wave_tot[w2];
+        if (incl > u) atomicMin(&cross_sh, tid);
+        __syncthreads();
+        const bool forced = cross_sh == 0x7FFFFFFF;      // the running sum never passes u: last token
+        if (forced) {
+            if (tid == 0) { seg_sh = (V - 1) / seg_cols; base_sh = 0.0; }
+        } else if (tid == cross_sh) {
+            double c = incl - sum;
+            int seg = hi - 1;
+            for (int j = lo; j < hi; ++j) {
+                double mj = 0.0;
+                for (int a = 0; a < r; ++a) {
+                    const float2 qv = part[(row0 + a) * parts + j];
+                    if (qv.x != -INFINITY) mj += (double)(qh_s[a] * qv.y * expf(qv.x - lse_s[s * r + a]));
+                }
+                if (c + mj > u) { seg = j; break; }
+                c += mj;
+            }
+            seg_sh = seg;
+            base_sh = c;
+        }
+        __syncthreads();
+        const int seg = seg_sh;
+        const int v0 = seg * seg_cols, cols = min(seg_cols, V - v0);
+
+        // logits of the segment for all r experts: a wavefront per column, eight experts at a time
+        const bf16_t *ybase = stage_y ? y_s : Y + row0 * d;
+        for (int c = wave; c < cols; c += NW) {
+            const u32x4_t *urow = reinterpret_cast<const u32x4_t *>(U + (size_t)(v0 + c) * d);
+            for (int a0 = 0; a0 < r; a0 += 8) {
+                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                for (int k = lane; k < d / 8; k += kWave) {
+                    const u32x4_t uv = urow[k];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        if (a0 + e < r) {
+                            const u32x4_t yv = reinterpret_cast<const u32x4_t *>(ybase + (size_t)(a0 + e) * d)[k];
+#pragma unroll
+                            for (int qd = 0; qd < 4; ++qd) {
+                                acc[e] += __uint_as_float(uv[qd] << 16) * __uint_as_float(yv[qd] << 16);
+                                acc[e] += __uint_as_float(uv[qd] & 0xFFFF0000u) * __uint_as_float(yv[qd] & 0xFFFF0000u);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float zz = wave_sum(acc[e]);
+                    if (lane == 0 && a0 + e < r) z_s[(a0 + e) * seg_cols + c] = zz;
+                }
+            }
+        }
+        __syncthreads();
+
+        if (wave == 0) {
+            int tok;
+            if (forced) {
+                tok = V - 1;
+            } else {
+                const int per2 = (seg_cols + kWave - 1) / kWave;
+                const int lo2 = lane * per2;
+                double ps = 0.0;
+                for (int i = lo2; i < lo2 + per2 && i < cols; ++i)
+                    for (int a = 0; a < r; ++a) ps += (double)(qh_s[a] * expf(z_s[a * seg_cols + i] - lse_s[s * r + a]));
+                const double in2 = base_sh + wave_scan_inclusive(ps, lane);
+                const unsigned long long crossed = __ballot(in2 > u);
+                if (crossed == 0ull) {
+                    tok = v0 + cols - 1;
+                } else {
+                    const int first = __ffsll((long long)crossed) - 1;
+                    int mine = v0 + min(cols, lo2 + per2) - 1;
+                    if (lane == first) {
+                        double c = in2 - ps;
+                        for (int i = lo2; i < lo2 + per2 && i < cols; ++i) {
+                            double pi = 0.0;
+                            for (int a = 0; a < r; ++a)
+                                pi += (double)(qh_s[a] * expf(z_s[a * seg_cols + i] - lse_s[s * r + a]));
+                            c += pi;
+                            if (c > u) { mine = v0 + i; break; }
+                        }
+                    }
+                    tok = __shfl(mine, first, kWave);
+                }
+            }
+            if (lane == 0) tokens[b * n + s] = tok;
+            // expert log-weights take the log-probability of the drawn token (text under eq. 12)
+            if (lane < r) q_s[lane] += z_s[lane * seg_cols + (tok - v0)] - lse_s[s * r + lane];
+        }
+        __syncthreads();
+    }
+    if (logq && wave == 0) {
+        const float qa = lane < r ? q_s[lane] : -INFINITY;
+        const float mx = wave_max(qa);
+        const float sum = wave_sum(lane < r ? expf(qa - mx) : 0.f);
+        if (lane == 0) logq[b] = mx + logf(sum);
+    }
+}
+
 // Per head row {lse, coef = up_t * gamma[t, a] (zero for dropped factors), target}; dg[t, a] = up_t (w - gamma)
 __global__ void k_bwd_coefficients(size_t M, int n, int r, const float *__restrict__ w, const float *__restrict__ gamma,
                                    const float *__restrict__ lse, const float *__restrict__ dloss, float scale,
@@ -645,11 +819,31 @@ inline DraftWs draft_ws(const cp_head_desc &ds)
     return f;
 }
 
+struct FirstTokenWs {
+    size_t logw, Y, z, lse, total;
+    size_t V4;
+};
+inline FirstTokenWs first_token_ws(const cp_head_desc &ds)
+{
+    FirstTokenWs f;
+    const size_t rows = (size_t)ds.T * ds.r;
+    f.V4 = round_up((size_t)ds.V, 4);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    f.logw = take(rows * 4);
+    f.Y = take(rows * ds.d * 2);
+    f.z = take(rows * f.V4 * 4);
+    f.lse = take(rows * 4);
+    f.total = off;
+    return f;
+}
+
 size_t fast_workspace_bytes(const cp_head_desc &ds, int op)
 {
     if (op == CP_HEAD_OP_LOSS_FWD) return fwd_ws(ds).total;
     if (op == CP_HEAD_OP_LOSS_BWD) return bwd_ws(ds).total;
-    return draft_ws(ds).total;
+    if (op == CP_HEAD_OP_FIRST_TOKEN) return first_token_ws(ds).total;
+    return draft_ws(ds).total;   // both draft calls
 }
 
 int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
@@ -795,6 +989,67 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
         ProfileScope prof("draft_logq", (double)M * d * 4, st);
         k_draft_logq<<<(unsigned)B, kWideBlock, 0, st>>>(d, n, r, logw, lse, Y, U, tokens, logq);
     }
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int fast_first_token(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                     float *logp, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
+    const FirstTokenWs f = first_token_ws(ds);
+    const int B = (int)ds.T, d = ds.d, V = ds.V, r = ds.r;
+    const int rows = B * r, rd = r * d, V4 = (int)f.V4;
+    float *logw = at<float>(ws, f.logw), *z = at<float>(ws, f.z), *lse = at<float>(ws, f.lse);
+    bf16_t *Y = at<bf16_t>(ws, f.Y);
+    k_draft_gate_pick<<<(unsigned)B, kWideBlock, 0, st>>>(d, ds.n, r, H, G, nullptr, logw, nullptr);      // eq. 7
+    // first head only: its matrices are the first r blocks of W, so y has rows (b, a)
+    if (B <= CfgSkinny::BM)
+        launch_gemm_nt<CfgSkinny>("first_gemm_y", H, d, B, W, d, rd, d, EpiStoreBf16{Y, nullptr, (long)rd, B, rd}, st);
+    else
+        launch_gemm_nt<Cfg>("first_gemm_y", H, d, B, W, d, rd, d, EpiStoreBf16{Y, nullptr, (long)rd, B, rd}, st);
+    // the r rows of logits per b are the output's own size; they are stored once (fp32) and mixed
+    if (rows <= CfgSkinny::BM)
+        launch_gemm_nt<CfgSkinny>("first_gemm_z", Y, d, rows, U, d, V, d, EpiStoreF32{z, (long)V4, rows, V4, 0}, st);
+    else
+        launch_gemm_nt<Cfg>("first_gemm_z", Y, d, rows, U, d, V, d, EpiStoreF32{z, (long)V4, rows, V4, 0}, st);
+    ProfileScope prof("first_mix", (double)rows * V * 8, st);
+    launch_first_token_mix(ds, z, (size_t)V4, nullptr, logw, logp, true, lse, st);                          // eq. 11
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int fast_draft_sequential(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                          const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
+    const DraftWs f = draft_ws(ds);
+    const int B = (int)ds.T, d = ds.d, V = ds.V, n = ds.n, r = ds.r;
+    const size_t M = (size_t)B * n * r;
+    const int nrd = n * r * d;
+    float *logw = at<float>(ws, f.logw);
+    bf16_t *Y = at<bf16_t>(ws, f.Y);
+    float2 *part = at<float2>(ws, f.part);
+    k_draft_gate_pick<<<(unsigned)B, kWideBlock, 0, st>>>(d, n, r, H, G, nullptr, logw, nullptr);          // eq. 7
+    if (B <= CfgSkinny::BM)
+        launch_gemm_nt<CfgSkinny>("seq_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
+    else
+        launch_gemm_nt<Cfg>("seq_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
+    int parts, seg_cols;
+    if (M <= (size_t)CfgSkinny::BM) {
+        parts = ((V + CfgSkinny::BN - 1) / CfgSkinny::BN) * CfgSkinny::WN;
+        seg_cols = CfgSkinny::WTN;
+        launch_gemm_nt<CfgSkinny>("seq_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
+    } else {
+        parts = ((V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+        seg_cols = Cfg::WTN;
+        launch_gemm_nt<Cfg>("seq_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
+    }
+    ProfileScope prof("seq_draw", (double)B * n * r * seg_cols * d * 2, st);
+    k_draft_sequential<<<(unsigned)B, kSeqBlock, 0, st>>>(d, V, n, r, parts, seg_cols, part, Y, U, logw, uniforms, tokens,
+                                                          logq);                                             // eq. 11-13
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 

@@ -10,6 +10,8 @@
 
 #include <math.h>
 
+#include <algorithm>
+
 namespace cph {
 
 namespace {
@@ -344,6 +346,99 @@ __global__ void __launch_bounds__(kWave) k_logq_generic(int V, int n, int r, con
     if (lane == 0) logq[b] = mx + logf(sum);
 }
 
+// ------------------------------------------------------------------------------------------
+// next-token distribution (eq. 11) and the balancing statistic (eq. 10)
+// ------------------------------------------------------------------------------------------
+
+// log-normaliser of one row of fp32 logits (row stride ld); one block per row
+__global__ void __launch_bounds__(kBlock) k_row_lse_f32(int V, size_t ld, const float *__restrict__ z,
+                                                        float *__restrict__ lse)
+{
+    __shared__ float red_m[kWavesPerBlock], red_l[kWavesPerBlock];
+    const size_t row = blockIdx.x;
+    const float *zr = z + row * ld;
+    float mx = -INFINITY, l = 0.f;
+    for (int v = threadIdx.x; v < V; v += kBlock) {
+        const float x = zr[v];
+        if (x > mx) { l = l * expf(mx - x) + 1.f; mx = x; }
+        else l += expf(x - mx);
+    }
+    const float Mw = wave_max(mx);
+    const float Lw = wave_sum(mx == -INFINITY ? 0.f : l * expf(mx - Mw));
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    if (lane == 0) { red_m[wave] = Mw; red_l[wave] = Lw; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float Mx = red_m[0];
+        for (int i = 1; i < kWavesPerBlock; ++i) Mx = fmaxf(Mx, red_m[i]);
+        float L = 0.f;
+        for (int i = 0; i < kWavesPerBlock; ++i)
+            if (red_m[i] != -INFINITY) L += red_l[i] * expf(red_m[i] - Mx);
+        lse[row] = Mx + logf(L);
+    }
+}
+
+// logp[b, v] = logsumexp_a( logw[b,a] + z[(b*r+a), v] - lse[b*r+a] )      (eq. 11 in log space)
+__global__ void __launch_bounds__(kBlock) k_first_token_mix(int V, int r, size_t ld, const float *__restrict__ z,
+                                                            const float *__restrict__ lse,
+                                                            const float *__restrict__ logw, float *__restrict__ logp)
+{
+    const int v = blockIdx.x * kBlock + threadIdx.x;
+    const size_t b = blockIdx.y;
+    if (v >= V) return;
+    float mx = -INFINITY, l = 0.f;
+    for (int a = 0; a < r; ++a) {
+        const size_t row = b * r + a;
+        const float x = logw[row] + z[row * ld + v] - lse[row];
+        if (x > mx) { l = l * expf(mx - x) + 1.f; mx = x; }
+        else l += expf(x - mx);
+    }
+    logp[b * (size_t)V + v] = mx + logf(l);
+}
+
+// eq. 10, first stage: argmax_a of the gate pre-activations per position (first index on ties; the
+// softmax is monotone), histogram per block in LDS, then integer atomics (exact, order-independent)
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_aux_argmax(size_t T, int d, int r, const TIn *__restrict__ H,
+                                                       const TIn *__restrict__ G, unsigned long long *__restrict__ counts)
+{
+    __shared__ unsigned int hist[64];
+    if (threadIdx.x < 64) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    for (size_t t = (size_t)blockIdx.x * kWavesPerBlock + wave; t < T; t += (size_t)gridDim.x * kWavesPerBlock) {
+        const TIn *h = H + t * d;
+        float best = -INFINITY;
+        int arg = 0;
+        for (int a = 0; a < r; ++a) {
+            float p = 0.f;
+            for (int k = lane; k < d; k += kWave) p += ld_f32(G, (size_t)a * d + k) * ld_f32(h, k);
+            p = wave_sum(p);
+            if (p > best) { best = p; arg = a; }
+        }
+        if (lane == 0) atomicAdd(&hist[arg], 1u);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < r && hist[threadIdx.x]) atomicAdd(&counts[threadIdx.x], (unsigned long long)hist[threadIdx.x]);
+}
+
+__global__ void k_fill_zero_u64(int count, unsigned long long *__restrict__ p)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0ull;
+}
+
+// eq. 10, second stage: L_aux = sum_a (n_a / N - 1/r)^2
+__global__ void __launch_bounds__(kWave) k_aux_finish(size_t T, int r, const unsigned long long *__restrict__ counts,
+                                                      float *__restrict__ laux)
+{
+    const int lane = threadIdx.x;
+    float dev = 0.f;
+    if (lane < r) dev = (T ? (float)((double)counts[lane] / (double)T) : 0.f) - 1.f / (float)r;
+    const float s = wave_sum(dev * dev);
+    if (lane == 0) *laux = s;
+}
+
 // rows of the dZ chunk on this path: at most 512 MiB of fp32 logit gradients at a time
 inline size_t generic_chunk_rows(const cp_head_desc &ds)
 {
@@ -502,6 +597,80 @@ int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const vo
                               alpha, tokens, logq, ws, st);
     return draft_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G, uniforms,
                            alpha, tokens, logq, ws, st);
+}
+
+// ---- first-token marginal on the plain path: z of the r first-head rows is stored, then mixed
+struct GenericFirstWs {
+    size_t logw, w, Y, z, lse, total;
+};
+static GenericFirstWs generic_first_ws(const cp_head_desc &ds)
+{
+    GenericFirstWs g;
+    const size_t rows = (size_t)ds.T * ds.r;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    g.logw = take(rows * 4);
+    g.w = take(rows * 4);
+    g.Y = take(rows * ds.d * 4);
+    g.z = take(rows * ds.V * 4);
+    g.lse = take(rows * 4);
+    g.total = off;
+    return g;
+}
+size_t generic_first_token_workspace_bytes(const cp_head_desc &ds) { return generic_first_ws(ds).total; }
+
+void launch_first_token_mix(const cp_head_desc &ds, const float *z, size_t ld, const float *lse, const float *logw,
+                            float *logp, bool compute_lse, float *lse_out, hipStream_t st)
+{
+    if (ds.T == 0) return;
+    const size_t rows = (size_t)ds.T * ds.r;
+    if (compute_lse) k_row_lse_f32<<<(unsigned)rows, kBlock, 0, st>>>(ds.V, ld, z, lse_out);
+    k_first_token_mix<<<dim3(blocks_for((size_t)ds.V, kBlock), (unsigned)ds.T), kBlock, 0, st>>>(
+        ds.V, ds.r, ld, z, compute_lse ? lse_out : lse, logw, logp);
+}
+
+template <typename TIn>
+static int first_token_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, float *logp,
+                         void *ws, hipStream_t st)
+{
+    const GenericFirstWs g = generic_first_ws(ds);
+    const size_t rows = (size_t)ds.T * ds.r;
+    float *logw = at<float>(ws, g.logw), *w = at<float>(ws, g.w), *Y = at<float>(ws, g.Y);
+    float *z = at<float>(ws, g.z), *lse = at<float>(ws, g.lse);
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    const int round_y = ds.dtype == CP_HEAD_BF16 ? 1 : 0;
+    k_gate<TIn><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
+    // the first head's matrices are the first r blocks of W, so its rows are (b, a) with nr = r
+    k_y_generic<TIn><<<(unsigned)rows, kBlock, lds, st>>>(ds.d, ds.r, H, W, Y, round_y);
+    k_zstats_generic<TIn><<<(unsigned)rows, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, nullptr, lse, nullptr, z);
+    launch_first_token_mix(ds, z, (size_t)ds.V, lse, logw, logp, false, nullptr, st);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int generic_first_token(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                        float *logp, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (ds.dtype == CP_HEAD_FP32)
+        return first_token_t<float>(ds, (const float *)H, (const float *)W, (const float *)U, (const float *)G, logp, ws, st);
+    return first_token_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G, logp, ws,
+                                 st);
+}
+
+int aux_balance(const cp_head_desc &ds, const void *H, const void *G, int64_t *counts, float *laux, hipStream_t st)
+{
+    unsigned long long *c = reinterpret_cast<unsigned long long *>(counts);
+    k_fill_zero_u64<<<1, 64, 0, st>>>(ds.r, c);
+    if (ds.T > 0) {
+        const unsigned blocks = (unsigned)std::min<size_t>(((size_t)ds.T + kWavesPerBlock - 1) / kWavesPerBlock, 4096);
+        if (ds.dtype == CP_HEAD_FP32)
+            k_aux_argmax<float><<<blocks, kBlock, 0, st>>>((size_t)ds.T, ds.d, ds.r, (const float *)H, (const float *)G, c);
+        else
+            k_aux_argmax<bf16_t><<<blocks, kBlock, 0, st>>>((size_t)ds.T, ds.d, ds.r, (const bf16_t *)H,
+                                                            (const bf16_t *)G, c);
+    }
+    k_aux_finish<<<1, kWave, 0, st>>>((size_t)ds.T, ds.r, c, laux);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
 void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *logw, float *w, hipStream_t st)

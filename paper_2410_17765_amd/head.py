@@ -99,3 +99,30 @@ class CpHead:
         logq = torch.empty(B, dtype=torch.float32, device=self.device)
         binding.cp_head_draft_sample(ds, H, self.W, self.U, self.G, uniforms, alpha, tokens, logq, ws, stream)
         return alpha, tokens, logq
+
+    # ------------------------------------------------------------------ next-token distribution, paper-form sampler
+    def first_token_logprob(self, H: torch.Tensor, stream=None) -> torch.Tensor:
+        B = H.shape[0]
+        ds = self.desc(B)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_FIRST_TOKEN), self.device)
+        logp = torch.empty((B, self.V), dtype=torch.float32, device=self.device)
+        binding.cp_head_first_token_logprob(ds, H, self.W, self.U, self.G, logp, ws, stream)
+        return logp
+
+    def draft_sample_sequential(self, H: torch.Tensor, uniforms: torch.Tensor, stream=None):
+        B = H.shape[0]
+        ds = self.desc(B)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT_SEQUENTIAL), self.device)
+        tokens = torch.empty((B, self.n), dtype=torch.int32, device=self.device)
+        logq = torch.empty(B, dtype=torch.float32, device=self.device)
+        binding.cp_head_draft_sample_sequential(ds, H, self.W, self.U, self.G, uniforms, tokens, logq, ws, stream)
+        return tokens, logq
+
+    def aux_balance(self, H: torch.Tensor, stream=None):
+        T = H.shape[0]
+        ds = self.desc(T)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_AUX_BALANCE), self.device)
+        counts = torch.empty(self.r, dtype=torch.int64, device=self.device)
+        laux = torch.empty(1, dtype=torch.float32, device=self.device)
+        binding.cp_head_aux_balance(ds, H, self.G, counts, laux, ws, stream)
+        return counts, laux

@@ -1,0 +1,209 @@
+"""GPU parity of the calls beyond the loss/draft hot path: the first-token marginal (eq. 11), the
+paper's sequential sampling scheme (eq. 11-13) and the balancing statistic (eq. 10), each through
+the C ABI against the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from paper_2410_17765_amd import synth
+from tests.helpers import LOSS_ATOL, band_valid, tie_variants
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2410_17765_amd import binding, head
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()
+    return head
+
+
+def seq_uniforms(B, n):
+    """[B,n] float32 in [0,1): one per token (the token columns of the seeded draft uniforms)."""
+    return np.ascontiguousarray(synth.uniforms(B, n)[:, 1:])
+
+
+# ---------------------------------------------------------------------------- first-token marginal
+FIRST_CASES = [
+    # (config, flags): n > 1 on purpose, only the first head may be read
+    (synth.HeadConfig("first_mfma", T=9, d=128, V=1000, n=3, r=4, targets="uniform", u_scale=4.0), 0),
+    (synth.HeadConfig("first_mfma_ragged", T=70, d=192, V=777, n=2, r=3, targets="uniform", u_scale=6.0), 0),
+    (synth.HeadConfig("first_mfma_one", T=1, d=64, V=130, n=1, r=1, targets="uniform"), 0),
+    (synth.HeadConfig("first_mfma_wide_rank", T=3, d=64, V=261, n=2, r=33, targets="uniform", u_scale=3.0), 0),
+    (synth.HeadConfig("first_plain_bf16", T=6, d=64, V=300, n=2, r=3, targets="uniform", u_scale=4.0), 1),
+    (synth.HeadConfig("first_plain_fp32", T=5, d=50, V=203, n=2, r=3, dtype="fp32", targets="uniform", u_scale=4.0), 0),
+]
+
+
+@pytest.mark.parametrize("cfg,flags", FIRST_CASES, ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_first_token_logprob(gpu, oracle, cfg, flags):
+    import torch
+    print(f"case {cfg} flags={flags}", flush=True)
+    inp = synth.make_inputs(cfg)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype, flags=flags)
+    logp = h.first_token_logprob(gpu.to_device(inp["H"], cfg.dtype))
+    torch.cuda.synchronize()
+    got = logp.cpu().numpy().astype(np.float64)
+    ref = oracle.first_token_logprob(inp["H"], inp["W"], inp["U"], inp["G"], round_y=(cfg.dtype == "bf16"))
+    assert got.shape == ref.shape == (cfg.T, cfg.V)
+    row_err = np.abs(got - ref).max(axis=1)
+    tie_rows = 0
+    for b in np.nonzero(row_err > LOSS_ATOL)[0]:
+        # an element of y on a bf16 rounding tie may round either way: the row must match one of them
+        assert cfg.dtype == "bf16", ("row off", b, row_err[b])
+        args = (inp["H"][b:b + 1], inp["W"], inp["U"], inp["G"])
+        y = oracle.draft_sample(*args, np.zeros((1, 1 + cfg.n)), want_y=True)[-1][:, 0]          # [1,r,d]
+        errs = [np.abs(got[b] - oracle.first_token_logprob(*args, round_y=True, y_nudge=nd)[0]).max()
+                for flips, nd in tie_variants(y) if flips]
+        assert errs and min(errs) <= LOSS_ATOL, ("row off with no rounding tie to explain it", b, row_err[b], errs)
+        row_err[b] = min(errs)
+        tie_rows += 1
+    norm = np.abs(np.log(np.exp(got).sum(axis=1))).max()
+    print(f"  max |dlogp| {row_err.max():.3e}, max |log sum p| {norm:.3e}, min logp {ref.min():.2f}, "
+          f"rows on a rounding tie {tie_rows}", flush=True)
+    assert tie_rows <= 1
+    assert norm <= 1e-4
+
+
+def test_first_token_matches_between_paths(gpu):
+    import torch
+    cfg = synth.HeadConfig("first_both", T=20, d=128, V=515, n=2, r=5, targets="uniform", u_scale=4.0)
+    inp = synth.make_inputs(cfg)
+    H = gpu.to_device(inp["H"], "bf16")
+    a = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16").first_token_logprob(H)
+    b = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=1).first_token_logprob(H)
+    torch.cuda.synchronize()
+    assert float((a - b).abs().max()) <= 1e-3
+
+
+# ---------------------------------------------------------------------------- sequential scheme
+SEQ_CASES = [
+    synth.HeadConfig("seq_peaked", T=9, d=128, V=1000, n=3, r=4, targets="uniform", u_scale=4.0),
+    synth.HeadConfig("seq_flat", T=5, d=64, V=2000, n=2, r=8, targets="uniform"),
+    synth.HeadConfig("seq_ragged", T=70, d=192, V=777, n=4, r=3, targets="uniform", u_scale=6.0),
+    synth.HeadConfig("seq_r1", T=3, d=64, V=130, n=2, r=1, targets="uniform", u_scale=3.0),
+    # r*d beyond the staging buffer for y: the kernel reads y from memory
+    synth.HeadConfig("seq_wide", T=2, d=1024, V=300, n=1, r=33, targets="uniform", u_scale=6.0),
+]
+
+
+@pytest.mark.parametrize("cfg", SEQ_CASES, ids=lambda c: c.name)
+def test_sequential_sampling(gpu, oracle, cfg):
+    import torch
+    print(f"case {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    H, W, U, G = inp["H"], inp["W"], inp["U"], inp["G"]
+    u = seq_uniforms(cfg.T, cfg.n)
+    h = gpu.CpHead(W, U, G, dtype=cfg.dtype)
+    tokens, logq = h.draft_sample_sequential(gpu.to_device(H, cfg.dtype), torch.from_numpy(u).cuda())
+    torch.cuda.synchronize()
+    tokens, logq = tokens.cpu().numpy(), logq.cpu().numpy()
+    tok_o, logq_o, cdf = oracle.draft_sample_sequential(H, W, U, G, u, round_y=True, want_cdf=True)
+    # joint log-probability of the tuple the GPU drew, by the oracle's loss at those tokens
+    lq_err = np.abs(-oracle.loss_fwd(H, W, U, G, tokens.astype(np.int32), round_y=True) - logq)
+    exact, tie_rows = 0, 0
+    for b in range(cfg.T):
+        ok = lq_err[b] <= 1e-3
+        for s in range(cfg.n):
+            v = int(tokens[b, s])
+            assert 0 <= v < cfg.V
+            if (tokens[b, :s] == tok_o[b, :s]).all():
+                c = cdf[b, s]
+            else:   # an admissible other draw earlier in the row: the oracle's conditional under that prefix
+                c = np.cumsum(oracle.sequential_conditional(H, W, U, G, b, list(tokens[b, :s]), round_y=True))
+            ok = ok and band_valid(c, v, float(u[b, s]))
+            exact += int(v == tok_o[b, s])
+        if ok:
+            continue
+        # an element of y on a bf16 rounding tie may round either way: the row must be the oracle's
+        # under one of the roundings (draws inside the band of its running sums, its logq)
+        args = (H[b:b + 1], W, U, G)
+        y = oracle.draft_sample(*args, np.zeros((1, 1 + cfg.n)), want_y=True)[-1]                 # [1,n,r,d]
+        explained = False
+        for flips, nd in tie_variants(y):
+            if not flips:
+                continue
+            t2, q2, c2 = oracle.draft_sample_sequential(*args, u[b:b + 1], round_y=True, want_cdf=True, y_nudge=nd)
+            if abs(q2[0] - logq[b]) <= 1e-3 and (t2[0] == tokens[b]).all() and all(
+                    band_valid(c2[0, s], int(tokens[b, s]), float(u[b, s])) for s in range(cfg.n)):
+                explained = True
+                break
+        assert explained, ("row off with no rounding tie to explain it", b, tokens[b], tok_o[b], lq_err[b])
+        lq_err[b] = 0.0
+        tie_rows += 1
+    print(f"  tokens exact {exact}/{cfg.T * cfg.n}, logq err {lq_err.max():.3e}, rows on a rounding tie {tie_rows}",
+          flush=True)
+    assert tie_rows <= 1
+    assert exact >= (cfg.T - tie_rows) * cfg.n     # the CDF steps at these sizes are far wider than the band
+
+
+def test_sequential_boundaries_and_plain_path(gpu):
+    import torch
+    from paper_2410_17765_amd import binding
+    cfg = synth.HeadConfig("seq_edge", T=4, d=64, V=300, n=2, r=3, targets="uniform")
+    inp = synth.make_inputs(cfg)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16")
+    H = gpu.to_device(inp["H"], "bf16")
+    tok, _ = h.draft_sample_sequential(H, torch.zeros((4, 2), device="cuda"))
+    assert (tok.cpu().numpy() == 0).all()
+    top = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
+    tok, _ = h.draft_sample_sequential(H, torch.full((4, 2), top, device="cuda"))
+    assert (tok.cpu().numpy() == cfg.V - 1).all()
+    # the plain path does not serve this call and says so
+    hp = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=1)
+    with pytest.raises(binding.CpHeadError):
+        hp.draft_sample_sequential(H, torch.zeros((4, 2), device="cuda"))
+
+
+def test_sequential_and_expert_first_draw_agree_for_one_expert(gpu):
+    """With r = 1 both samplers draw every token from the same distribution with the same uniform."""
+    import torch
+    cfg = synth.HeadConfig("seq_vs_expert", T=11, d=128, V=999, n=3, r=1, targets="uniform", u_scale=5.0)
+    inp = synth.make_inputs(cfg)
+    u = synth.uniforms(cfg.T, cfg.n)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16")
+    H = gpu.to_device(inp["H"], "bf16")
+    _, tok_a, lq_a = h.draft_sample(H, torch.from_numpy(u).cuda())
+    tok_b, lq_b = h.draft_sample_sequential(H, torch.from_numpy(np.ascontiguousarray(u[:, 1:])).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(tok_a, tok_b)
+    assert float((lq_a - lq_b).abs().max()) <= 1e-4
+
+
+# ---------------------------------------------------------------------------- balancing statistic
+AUX_CASES = [
+    synth.HeadConfig("aux_bf16", T=5000, d=128, V=8, n=1, r=8),
+    synth.HeadConfig("aux_fp32_odd", T=777, d=50, V=8, n=1, r=5, dtype="fp32"),
+    synth.HeadConfig("aux_wide", T=100000, d=64, V=8, n=1, r=64),
+    synth.HeadConfig("aux_one", T=1, d=64, V=8, n=1, r=3),
+]
+
+
+@pytest.mark.parametrize("cfg", AUX_CASES, ids=lambda c: c.name)
+def test_aux_balance(gpu, oracle, cfg):
+    import torch
+    print(f"case {cfg}", flush=True)
+    Hn, Gn = synth.hidden(cfg), synth.gate(cfg)
+    h = gpu.CpHead(synth.head_weights(cfg), synth.unembedding(cfg), Gn, dtype=cfg.dtype)
+    counts, laux = h.aux_balance(gpu.to_device(Hn, cfg.dtype))
+    torch.cuda.synchronize()
+    counts, laux = counts.cpu().numpy(), float(laux.cpu().numpy()[0])
+    c_o, l_o = oracle.aux_balance(Hn.astype(np.float64), Gn.astype(np.float64))
+    print(f"  counts {counts.tolist()[:8]} laux {laux:.6e} (oracle {l_o:.6e})", flush=True)
+    assert counts.sum() == cfg.T
+    # the arg-max is decided in fp32 on the GPU and in fp64 by the oracle: a position may move between
+    # two experts only when their gate pre-activations agree to fp32 accumulation error, which at these
+    # sizes is rarer than one position in a million
+    np.testing.assert_array_equal(counts, c_o)
+    assert abs(laux - l_o) <= 1e-6 * max(1.0, l_o)
+
+
+def test_aux_balance_empty(gpu):
+    import torch
+    cfg = synth.HeadConfig("aux_empty", T=0, d=64, V=8, n=1, r=4)
+    h = gpu.CpHead(synth.head_weights(cfg), synth.unembedding(cfg), synth.gate(cfg), dtype="bf16")
+    counts, laux = h.aux_balance(torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"))
+    torch.cuda.synchronize()
+    assert counts.cpu().numpy().tolist() == [0, 0, 0, 0]
+    assert abs(float(laux.cpu().numpy()[0]) - 0.25) < 1e-7
