@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads) or 'draft'")
+    ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token'")
     ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per two threads)")
@@ -157,7 +157,10 @@ def bench_loss(args):
 _DRAFT_CACHE = {}
 
 
-def bench_draft(args):
+def bench_draft(args, mode="draft"):
+    """Latency of one forward-only step at the draft workload's shape.  mode: "draft" (expert first),
+    "draft_sequential" (the paper-form sampler, eq. 11-13) or "first_token" (eq. 11 over the vocabulary)."""
+    import numpy as np
     import torch
     from paper_2410_17765_amd import binding, head, synth
 
@@ -171,14 +174,30 @@ def bench_draft(args):
         _DRAFT_CACHE["H"] = inp["H"]
     h = _DRAFT_CACHE["head"]
     H = head.to_device(_DRAFT_CACHE["H"][:cfg.T], cfg.dtype)
-    u = torch.from_numpy(synth.uniforms(cfg.T, cfg.n)).to(dev)
+    un = synth.uniforms(cfg.T, cfg.n)
     ds = h.desc(cfg.T)
-    ws = torch.empty(binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT), dtype=torch.uint8, device=dev)
-    alpha = torch.empty(cfg.T, dtype=torch.int32, device=dev)
-    tokens = torch.empty((cfg.T, cfg.n), dtype=torch.int32, device=dev)
-    logq = torch.empty(cfg.T, dtype=torch.float32, device=dev)
+    op = {"draft": binding.OP_DRAFT, "draft_sequential": binding.OP_DRAFT_SEQUENTIAL,
+          "first_token": binding.OP_FIRST_TOKEN}[mode]
+    ws = torch.empty(binding.cp_head_workspace_bytes(ds, op), dtype=torch.uint8, device=dev)
+    alpha = torch.zeros(cfg.T, dtype=torch.int32, device=dev)          # not every mode writes all three
+    tokens = torch.zeros((cfg.T, cfg.n), dtype=torch.int32, device=dev)
+    logq = torch.zeros(cfg.T, dtype=torch.float32, device=dev)
+    weight_bytes = 2.0 * cfg.n * cfg.r * cfg.d * cfg.d + 2.0 * cfg.V * cfg.d
+    if mode == "draft":
+        u = torch.from_numpy(un).to(dev)
+        call = lambda st: binding.cp_head_draft_sample(ds, H, h.W, h.U, h.G, u, alpha, tokens, logq, ws, st)
+    elif mode == "draft_sequential":
+        u = torch.from_numpy(np.ascontiguousarray(un[:, 1:])).to(dev)
+        call = lambda st: binding.cp_head_draft_sample_sequential(ds, H, h.W, h.U, h.G, u, tokens, logq, ws, st)
+    else:
+        # only the first head's matrices are read; the [B,V] output and the stored logits of its r rows are
+        # written once and the logits read twice (log-normaliser, mixture)
+        logp = torch.empty((cfg.T, cfg.V), dtype=torch.float32, device=dev)
+        weight_bytes = 2.0 * cfg.r * cfg.d * cfg.d + 2.0 * cfg.V * cfg.d + 4.0 * cfg.T * cfg.V * (1 + 3 * cfg.r)
+        call = lambda st: binding.cp_head_first_token_logprob(ds, H, h.W, h.U, h.G, logp, ws, st)
+        logq = logp     # the output whose graph replays are compared below
     stream = torch.cuda.current_stream().cuda_stream
-    step = lambda: binding.cp_head_draft_sample(ds, H, h.W, h.U, h.G, u, alpha, tokens, logq, ws, stream)
+    step = lambda: call(stream)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -195,7 +214,7 @@ def bench_draft(args):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
-            binding.cp_head_draft_sample(ds, H, h.W, h.U, h.G, u, alpha, tokens, logq, ws, side.cuda_stream)
+            call(side.cuda_stream)
     graph_ok = True
     for _ in range(3):
         alpha.zero_(); tokens.zero_(); logq.zero_()
@@ -214,13 +233,13 @@ def bench_draft(args):
     torch.cuda.synchronize()
     binding.cp_head_profile_enable(False)
     kernels = binding.cp_head_profile_read()
-    weight_bytes = 2.0 * cfg.n * cfg.r * cfg.d * cfg.d + 2.0 * cfg.V * cfg.d
     gbs = weight_bytes / (ms * 1e-3) / 1e9
     return {
-        "metric": "CP-head draft step latency", "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "metric": {"draft": "CP-head draft step latency", "draft_sequential": "CP-head sequential draft step latency",
+                   "first_token": "CP-head first-token marginal latency"}[mode], "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "draft", "B": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r},
+        "config": {"workload": mode, "B": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r},
         "ms_per_step_graph": ms_graph, "graph_replays_match_eager": graph_ok,
         "graph_gbs": weight_bytes / (ms_graph * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -234,7 +253,10 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus above 1 is not supported", file=sys.stderr)
         sys.exit(2)
-    out = bench_draft(args) if args.workload == "draft" else bench_loss(args)
+    if args.workload in ("draft", "draft_sequential", "first_token"):
+        out = bench_draft(args, args.workload)
+    else:
+        out = bench_loss(args)
     print(json.dumps(out))
 
 

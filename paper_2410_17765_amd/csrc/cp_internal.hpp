@@ -80,9 +80,9 @@ size_t generic_first_token_workspace_bytes(const cp_head_desc &ds);
 int generic_first_token(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                         float *logp, void *ws, hipStream_t st);
 int aux_balance(const cp_head_desc &ds, const void *H, const void *G, int64_t *counts, float *laux, hipStream_t st);
-// logp = logsumexp_a(logw + z - lse) from stored first-head logits z[(b,a), ld]; computes lse first if asked
+// logp = logsumexp_a(logw + z - lse) from stored first-head logits z[(b,a), ld] and their log-normalisers
 void launch_first_token_mix(const cp_head_desc &ds, const float *z, size_t ld, const float *lse, const float *logw,
-                            float *logp, bool compute_lse, float *lse_out, hipStream_t st);
+                            float *logp, hipStream_t st);
 
 // Kernels of the generic path that the matrix-core path reuses (fp32 bookkeeping per position).
 void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *logw, float *w, hipStream_t st);

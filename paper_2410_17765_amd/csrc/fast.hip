@@ -481,6 +481,90 @@ __global__ void __launch_bounds__(kWideBlock) k_draft_logq(int d, int n, int r, 
     if (lane == 0) logq[b] = mx + logf(sum);
 }
 
+// Log-normaliser (eq. 5) of one row from its per-segment statistics, by one wavefront.
+__device__ __forceinline__ float row_lse_from_parts(const float2 *__restrict__ pm, int parts, int lane)
+{
+    // four independent loads per lane and step: the chain of rescalings is short, the loads overlap
+    float mx = -INFINITY, l = 0.f;
+    for (int p0 = 0; p0 < parts; p0 += 4 * kWave) {
+        float2 qv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int p = p0 + i * kWave + lane;
+            qv[i] = p < parts ? pm[p] : make_float2(-INFINITY, 0.f);
+        }
+        const float m4 = fmaxf(fmaxf(qv[0].x, qv[1].x), fmaxf(qv[2].x, qv[3].x));
+        if (m4 == -INFINITY) continue;
+        const float mn = fmaxf(mx, m4);
+        float add = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) add += qv[i].y * __expf(qv[i].x - mn);     // exp(-inf) = 0 for empty segments
+        l = l * __expf(mx - mn) + add;
+        mx = mn;
+    }
+    const float Mx = wave_max(mx);
+    const float L = wave_sum(mx == -INFINITY ? 0.f : l * __expf(mx - Mx));
+    return Mx + logf(L);
+}
+
+__global__ void __launch_bounds__(kBlock) k_lse_from_parts(size_t rows, int parts, const float2 *__restrict__ part,
+                                                           float *__restrict__ lse)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t row = (size_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float v = row_lse_from_parts(part + row * parts, parts, lane);
+    if (lane == 0) lse[row] = v;
+}
+
+// (max, sum of exp(z - max)) of one chunk of kStatCols columns of one row of stored fp32 logits
+// (row stride ld, a multiple of 4): the per-segment statistics of eq. 5 for logits that are kept.
+constexpr int kStatCols = 4096;
+__global__ void __launch_bounds__(kBlock) k_row_stats_f32(int V, size_t ld, int parts, const float *__restrict__ z,
+                                                          float2 *__restrict__ part)
+{
+    __shared__ float red_m[kBlock / kWave], red_l[kBlock / kWave];
+    const size_t row = blockIdx.x;
+    const int c0 = blockIdx.y * kStatCols;
+    const float *zr = z + row * ld;
+    float4 x[kStatCols / 4 / kBlock];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kStatCols / 4 / kBlock; ++i) {
+        const int c = c0 + (i * kBlock + threadIdx.x) * 4;
+        x[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        if (c + 3 < V) {
+            x[i] = *reinterpret_cast<const float4 *>(zr + c);
+        } else if (c < V) {
+            x[i].x = zr[c];
+            if (c + 1 < V) x[i].y = zr[c + 1];
+            if (c + 2 < V) x[i].z = zr[c + 2];
+        }
+        mx = fmaxf(fmaxf(mx, fmaxf(x[i].x, x[i].y)), fmaxf(x[i].z, x[i].w));
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    mx = wave_max(mx);
+    if (lane == 0) red_m[wave] = mx;
+    __syncthreads();
+    float Mx = red_m[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / kWave; ++w) Mx = fmaxf(Mx, red_m[w]);
+    const float ref = (Mx == -INFINITY) ? 0.f : Mx;
+    float l = 0.f;
+#pragma unroll
+    for (int i = 0; i < kStatCols / 4 / kBlock; ++i)
+        l += __expf(x[i].x - ref) + __expf(x[i].y - ref) + __expf(x[i].z - ref) + __expf(x[i].w - ref);
+    l = wave_sum(l);
+    if (lane == 0) red_l[wave] = l;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < kBlock / kWave; ++w) L += red_l[w];
+        part[row * parts + blockIdx.y] = make_float2(Mx, (Mx == -INFINITY) ? 0.f : L);
+    }
+}
+
 // The paper's sequential scheme (eq. 11-13) for one row b of the batch, all n draws in one block.
 // For step s the conditional is the mixture sum_a qhat_a P^(s)(. | a) with qhat = softmax(q),
 // q_a = log w_a + sum_{k<s} log P^(k)(x_k | a).  It is sampled exactly like the single-expert draw of
@@ -513,16 +597,8 @@ __global__ void __launch_bounds__(kSeqBlock) k_draft_sequential(int d, int V, in
 
     // log-normalisers of all n*r rows of this b (eq. 5)
     for (int j = wave; j < nr; j += NW) {
-        const float2 *pm = part + (b * nr + j) * parts;
-        float mx = -INFINITY, l = 0.f;
-        for (int p = lane; p < parts; p += kWave) {
-            const float2 qv = pm[p];
-            if (qv.x > mx) { l = l * __expf(mx - qv.x) + qv.y; mx = qv.x; }
-            else if (qv.x != -INFINITY) l += qv.y * __expf(qv.x - mx);
-        }
-        const float Mx = wave_max(mx);
-        const float L = wave_sum(mx == -INFINITY ? 0.f : l * __expf(mx - Mx));
-        if (lane == 0) lse_s[j] = Mx + logf(L);
+        const float v = row_lse_from_parts(part + (b * nr + j) * parts, parts, lane);
+        if (lane == 0) lse_s[j] = v;
     }
     if (tid < r) q_s[tid] = logw[b * r + tid];
     __syncthreads();
@@ -581,31 +657,46 @@ __global__ void __launch_bounds__(kSeqBlock) k_draft_sequential(int d, int V, in
         const int seg = seg_sh;
         const int v0 = seg * seg_cols, cols = min(seg_cols, V - v0);
 
-        // logits of the segment for all r experts: a wavefront per column, eight experts at a time
+        // logits of the segment for all r experts: a wavefront walks k for four columns and up to
+        // eight experts together (the four loads of U per step are independent and stay in flight)
         const bf16_t *ybase = stage_y ? y_s : Y + row0 * d;
-        for (int c = wave; c < cols; c += NW) {
-            const u32x4_t *urow = reinterpret_cast<const u32x4_t *>(U + (size_t)(v0 + c) * d);
-            for (int a0 = 0; a0 < r; a0 += 8) {
-                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                for (int k = lane; k < d / 8; k += kWave) {
-                    const u32x4_t uv = urow[k];
+        constexpr int CW = 4, EW = 8;
+        for (int c0 = wave * CW; c0 < cols; c0 += NW * CW) {
+            const u32x4_t *urow[CW];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        if (a0 + e < r) {
-                            const u32x4_t yv = reinterpret_cast<const u32x4_t *>(ybase + (size_t)(a0 + e) * d)[k];
+            for (int e = 0; e < CW; ++e)
+                urow[e] = reinterpret_cast<const u32x4_t *>(U + (size_t)(v0 + min(c0 + e, cols - 1)) * d);
+            for (int a0 = 0; a0 < r; a0 += EW) {
+                float acc[EW][CW];
+#pragma unroll
+                for (int e = 0; e < EW; ++e)
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) acc[e][c] = 0.f;
+#pragma unroll 1
+                for (int k = lane; k < d / 8; k += kWave) {
+                    u32x4_t uv[CW];
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) uv[c] = urow[c][k];
+#pragma unroll
+                    for (int e = 0; e < EW; ++e) {
+                        // experts past r repeat the last one (their sums are dropped below)
+                        const u32x4_t yv = reinterpret_cast<const u32x4_t *>(ybase + (size_t)min(a0 + e, r - 1) * d)[k];
+#pragma unroll
+                        for (int c = 0; c < CW; ++c)
 #pragma unroll
                             for (int qd = 0; qd < 4; ++qd) {
-                                acc[e] += __uint_as_float(uv[qd] << 16) * __uint_as_float(yv[qd] << 16);
-                                acc[e] += __uint_as_float(uv[qd] & 0xFFFF0000u) * __uint_as_float(yv[qd] & 0xFFFF0000u);
+                                acc[e][c] += __uint_as_float(uv[c][qd] << 16) * __uint_as_float(yv[qd] << 16);
+                                acc[e][c] += __uint_as_float(uv[c][qd] & 0xFFFF0000u) * __uint_as_float(yv[qd] & 0xFFFF0000u);
                             }
-                        }
                     }
                 }
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float zz = wave_sum(acc[e]);
-                    if (lane == 0 && a0 + e < r) z_s[(a0 + e) * seg_cols + c] = zz;
-                }
+                for (int e = 0; e < EW; ++e)
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) {
+                        const float zz = wave_sum(acc[e][c]);
+                        if (lane == 0 && a0 + e < r && c0 + c < cols) z_s[(a0 + e) * seg_cols + c0 + c] = zz;
+                    }
             }
         }
         __syncthreads();
@@ -820,8 +911,9 @@ inline DraftWs draft_ws(const cp_head_desc &ds)
 }
 
 struct FirstTokenWs {
-    size_t logw, Y, z, lse, total;
+    size_t logw, Y, z, lse, part, total;
     size_t V4;
+    int parts;
 };
 inline FirstTokenWs first_token_ws(const cp_head_desc &ds)
 {
@@ -834,6 +926,8 @@ inline FirstTokenWs first_token_ws(const cp_head_desc &ds)
     f.Y = take(rows * ds.d * 2);
     f.z = take(rows * f.V4 * 4);
     f.lse = take(rows * 4);
+    f.parts = (ds.V + kStatCols - 1) / kStatCols;
+    f.part = take(rows * f.parts * sizeof(float2));
     f.total = off;
     return f;
 }
@@ -1009,13 +1103,17 @@ int fast_first_token(const cp_head_desc &ds, const void *Hv, const void *Wv, con
         launch_gemm_nt<CfgSkinny>("first_gemm_y", H, d, B, W, d, rd, d, EpiStoreBf16{Y, nullptr, (long)rd, B, rd}, st);
     else
         launch_gemm_nt<Cfg>("first_gemm_y", H, d, B, W, d, rd, d, EpiStoreBf16{Y, nullptr, (long)rd, B, rd}, st);
-    // the r rows of logits per b are the output's own size; they are stored once (fp32) and mixed
+    // the r rows of logits per b are the output's own size: they are stored once (fp32), read once for
+    // their log-normalisers and once for the mixture
     if (rows <= CfgSkinny::BM)
         launch_gemm_nt<CfgSkinny>("first_gemm_z", Y, d, rows, U, d, V, d, EpiStoreF32{z, (long)V4, rows, V4, 0}, st);
     else
         launch_gemm_nt<Cfg>("first_gemm_z", Y, d, rows, U, d, V, d, EpiStoreF32{z, (long)V4, rows, V4, 0}, st);
-    ProfileScope prof("first_mix", (double)rows * V * 8, st);
-    launch_first_token_mix(ds, z, (size_t)V4, nullptr, logw, logp, true, lse, st);                          // eq. 11
+    ProfileScope prof("first_mix", (double)rows * V * 8 + (double)B * V * 4, st);
+    float2 *part = at<float2>(ws, f.part);
+    k_row_stats_f32<<<dim3((unsigned)rows, (unsigned)f.parts), kBlock, 0, st>>>(V, (size_t)V4, f.parts, z, part);
+    k_lse_from_parts<<<blocks_for((size_t)rows, kBlock / kWave), kBlock, 0, st>>>((size_t)rows, f.parts, part, lse);
+    launch_first_token_mix(ds, z, (size_t)V4, lse, logw, logp, st);                         // eq. 11
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 

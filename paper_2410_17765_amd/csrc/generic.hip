@@ -350,41 +350,13 @@ __global__ void __launch_bounds__(kWave) k_logq_generic(int V, int n, int r, con
 // next-token distribution (eq. 11) and the balancing statistic (eq. 10)
 // ------------------------------------------------------------------------------------------
 
-// log-normaliser of one row of fp32 logits (row stride ld); one block per row
-__global__ void __launch_bounds__(kBlock) k_row_lse_f32(int V, size_t ld, const float *__restrict__ z,
-                                                        float *__restrict__ lse)
-{
-    __shared__ float red_m[kWavesPerBlock], red_l[kWavesPerBlock];
-    const size_t row = blockIdx.x;
-    const float *zr = z + row * ld;
-    float mx = -INFINITY, l = 0.f;
-    for (int v = threadIdx.x; v < V; v += kBlock) {
-        const float x = zr[v];
-        if (x > mx) { l = l * expf(mx - x) + 1.f; mx = x; }
-        else l += expf(x - mx);
-    }
-    const float Mw = wave_max(mx);
-    const float Lw = wave_sum(mx == -INFINITY ? 0.f : l * expf(mx - Mw));
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    if (lane == 0) { red_m[wave] = Mw; red_l[wave] = Lw; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float Mx = red_m[0];
-        for (int i = 1; i < kWavesPerBlock; ++i) Mx = fmaxf(Mx, red_m[i]);
-        float L = 0.f;
-        for (int i = 0; i < kWavesPerBlock; ++i)
-            if (red_m[i] != -INFINITY) L += red_l[i] * expf(red_m[i] - Mx);
-        lse[row] = Mx + logf(L);
-    }
-}
-
 // logp[b, v] = logsumexp_a( logw[b,a] + z[(b*r+a), v] - lse[b*r+a] )      (eq. 11 in log space)
 __global__ void __launch_bounds__(kBlock) k_first_token_mix(int V, int r, size_t ld, const float *__restrict__ z,
                                                             const float *__restrict__ lse,
                                                             const float *__restrict__ logw, float *__restrict__ logp)
 {
-    const int v = blockIdx.x * kBlock + threadIdx.x;
-    const size_t b = blockIdx.y;
+    const int v = blockIdx.y * kBlock + threadIdx.x;
+    const size_t b = blockIdx.x;
     if (v >= V) return;
     float mx = -INFINITY, l = 0.f;
     for (int a = 0; a < r; ++a) {
@@ -620,13 +592,11 @@ static GenericFirstWs generic_first_ws(const cp_head_desc &ds)
 size_t generic_first_token_workspace_bytes(const cp_head_desc &ds) { return generic_first_ws(ds).total; }
 
 void launch_first_token_mix(const cp_head_desc &ds, const float *z, size_t ld, const float *lse, const float *logw,
-                            float *logp, bool compute_lse, float *lse_out, hipStream_t st)
+                            float *logp, hipStream_t st)
 {
     if (ds.T == 0) return;
-    const size_t rows = (size_t)ds.T * ds.r;
-    if (compute_lse) k_row_lse_f32<<<(unsigned)rows, kBlock, 0, st>>>(ds.V, ld, z, lse_out);
-    k_first_token_mix<<<dim3(blocks_for((size_t)ds.V, kBlock), (unsigned)ds.T), kBlock, 0, st>>>(
-        ds.V, ds.r, ld, z, compute_lse ? lse_out : lse, logw, logp);
+    k_first_token_mix<<<dim3((unsigned)ds.T, blocks_for((size_t)ds.V, kBlock)), kBlock, 0, st>>>(
+        ds.V, ds.r, ld, z, lse, logw, logp);
 }
 
 template <typename TIn>
@@ -643,7 +613,7 @@ static int first_token_t(const cp_head_desc &ds, const TIn *H, const TIn *W, con
     // the first head's matrices are the first r blocks of W, so its rows are (b, a) with nr = r
     k_y_generic<TIn><<<(unsigned)rows, kBlock, lds, st>>>(ds.d, ds.r, H, W, Y, round_y);
     k_zstats_generic<TIn><<<(unsigned)rows, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, nullptr, lse, nullptr, z);
-    launch_first_token_mix(ds, z, (size_t)ds.V, lse, logw, logp, false, nullptr, st);
+    launch_first_token_mix(ds, z, (size_t)ds.V, lse, logw, logp, st);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 

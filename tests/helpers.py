@@ -115,3 +115,45 @@ def check_draft(oracle, H, W, U, G, u, alpha_gpu, tokens_gpu, logq_gpu, round_y,
             assert err <= logq_atol, ("logq", err)
             stats["logq_err"] = float(err)
     return stats
+
+
+def check_sequential(oracle, H, W, U, G, u, tokens_gpu, logq_gpu, logq_atol=1e-3):
+    """Compare one call of the sequential sampler (one uniform per token, u[B,n]) with the oracle.
+    Every draw must lie inside the CDF band of the oracle's conditional under the prefix the GPU drew,
+    and logq must be the oracle's joint log-probability of the drawn tuple; a row that fails either is
+    accepted only if it is the oracle's row under another rounding of elements of y on a bf16 tie.
+    Returns match statistics."""
+    B, n = tokens_gpu.shape
+    V = U.shape[0]
+    tok_o, _, cdf = oracle.draft_sample_sequential(H, W, U, G, u, round_y=True, want_cdf=True)
+    lq_err = np.abs(-oracle.loss_fwd(H, W, U, G, tokens_gpu.astype(np.int32), round_y=True) - logq_gpu)
+    stats = {"tokens_exact": 0, "tokens_total": B * n, "tie_rows": 0}
+    for b in range(B):
+        ok = lq_err[b] <= logq_atol
+        for s in range(n):
+            v = int(tokens_gpu[b, s])
+            assert 0 <= v < V
+            if (tokens_gpu[b, :s] == tok_o[b, :s]).all():
+                c = cdf[b, s]
+            else:   # an admissible other draw earlier in the row: the oracle's conditional under that prefix
+                c = np.cumsum(oracle.sequential_conditional(H, W, U, G, b, list(tokens_gpu[b, :s]), round_y=True))
+            ok = ok and band_valid(c, v, float(u[b, s]))
+            stats["tokens_exact"] += int(v == tok_o[b, s])
+        if ok:
+            continue
+        args = (H[b:b + 1], W, U, G)
+        y = oracle.draft_sample(*args, np.zeros((1, 1 + n)), want_y=True)[-1]                     # [1,n,r,d]
+        explained = False
+        for flips, nd in tie_variants(y):
+            if not flips:
+                continue
+            t2, q2, c2 = oracle.draft_sample_sequential(*args, u[b:b + 1], round_y=True, want_cdf=True, y_nudge=nd)
+            if abs(q2[0] - logq_gpu[b]) <= logq_atol and (t2[0] == tokens_gpu[b]).all() and all(
+                    band_valid(c2[0, s], int(tokens_gpu[b, s]), float(u[b, s])) for s in range(n)):
+                explained = True
+                break
+        assert explained, ("row off with no rounding tie to explain it", b, tokens_gpu[b], tok_o[b], lq_err[b])
+        lq_err[b] = 0.0
+        stats["tie_rows"] += 1
+    stats["logq_err"] = float(lq_err.max()) if B else 0.0
+    return stats

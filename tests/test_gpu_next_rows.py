@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2410_17765_amd import synth
-from tests.helpers import LOSS_ATOL, band_valid, tie_variants
+from tests.helpers import LOSS_ATOL, check_sequential, tie_variants
 
 pytestmark = pytest.mark.gpu
 
@@ -99,43 +99,11 @@ def test_sequential_sampling(gpu, oracle, cfg):
     tokens, logq = h.draft_sample_sequential(gpu.to_device(H, cfg.dtype), torch.from_numpy(u).cuda())
     torch.cuda.synchronize()
     tokens, logq = tokens.cpu().numpy(), logq.cpu().numpy()
-    tok_o, logq_o, cdf = oracle.draft_sample_sequential(H, W, U, G, u, round_y=True, want_cdf=True)
-    # joint log-probability of the tuple the GPU drew, by the oracle's loss at those tokens
-    lq_err = np.abs(-oracle.loss_fwd(H, W, U, G, tokens.astype(np.int32), round_y=True) - logq)
-    exact, tie_rows = 0, 0
-    for b in range(cfg.T):
-        ok = lq_err[b] <= 1e-3
-        for s in range(cfg.n):
-            v = int(tokens[b, s])
-            assert 0 <= v < cfg.V
-            if (tokens[b, :s] == tok_o[b, :s]).all():
-                c = cdf[b, s]
-            else:   # an admissible other draw earlier in the row: the oracle's conditional under that prefix
-                c = np.cumsum(oracle.sequential_conditional(H, W, U, G, b, list(tokens[b, :s]), round_y=True))
-            ok = ok and band_valid(c, v, float(u[b, s]))
-            exact += int(v == tok_o[b, s])
-        if ok:
-            continue
-        # an element of y on a bf16 rounding tie may round either way: the row must be the oracle's
-        # under one of the roundings (draws inside the band of its running sums, its logq)
-        args = (H[b:b + 1], W, U, G)
-        y = oracle.draft_sample(*args, np.zeros((1, 1 + cfg.n)), want_y=True)[-1]                 # [1,n,r,d]
-        explained = False
-        for flips, nd in tie_variants(y):
-            if not flips:
-                continue
-            t2, q2, c2 = oracle.draft_sample_sequential(*args, u[b:b + 1], round_y=True, want_cdf=True, y_nudge=nd)
-            if abs(q2[0] - logq[b]) <= 1e-3 and (t2[0] == tokens[b]).all() and all(
-                    band_valid(c2[0, s], int(tokens[b, s]), float(u[b, s])) for s in range(cfg.n)):
-                explained = True
-                break
-        assert explained, ("row off with no rounding tie to explain it", b, tokens[b], tok_o[b], lq_err[b])
-        lq_err[b] = 0.0
-        tie_rows += 1
-    print(f"  tokens exact {exact}/{cfg.T * cfg.n}, logq err {lq_err.max():.3e}, rows on a rounding tie {tie_rows}",
-          flush=True)
-    assert tie_rows <= 1
-    assert exact >= (cfg.T - tie_rows) * cfg.n     # the CDF steps at these sizes are far wider than the band
+    stats = check_sequential(oracle, H, W, U, G, u, tokens, logq)
+    print(f"  {stats}", flush=True)
+    assert stats["tie_rows"] <= 1
+    # the CDF steps at these sizes are far wider than the band
+    assert stats["tokens_exact"] >= (cfg.T - stats["tie_rows"]) * cfg.n
 
 
 def test_sequential_boundaries_and_plain_path(gpu):
