@@ -16,6 +16,7 @@
  *   log factor      C_sa   = z_sa[x_s] - logsumexp_v z_sa[v]       (eq. 8)
  *   joint           L      = logsumexp_a( log w_a + sum_s C_sa )   (eq. 2, eq. 9)
  *   loss            loss   = -L   (per position, nats)
+ *   full head       z_sa   = F_sa h, F_sa of size V x d            (eq. 6 as printed; full_loss_*)
  *
  * The backward pass is the analytic derivative of the lines above (the paper
  * leaves it to automatic differentiation); it is pinned by finite differences
@@ -610,6 +611,160 @@ int CPO(aux_balance)(const cpo_shape *sh, const in_t *H, const in_t *G, int64_t 
     *laux = acc;
     free(logw);
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* full heads (eq. 6 as printed): one V x d matrix per (s, a), no shared unembedding */
+/* ------------------------------------------------------------------------- */
+
+/* z = F_sa h, F[n,r,V,d] */
+static void full_head_z(const cpo_shape *sh, const in_t *h, const in_t *F, int s, int a, double *z)
+{
+    const in_t *Fsa = F + ((size_t)s * sh->r + a) * sh->V * sh->d;
+    for (int v = 0; v < sh->V; ++v) {
+        double acc = 0.0;
+        for (int k = 0; k < sh->d; ++k) acc += (double)Fsa[(size_t)v * sh->d + k] * (double)h[k];
+        z[v] = acc;
+    }
+}
+
+/*
+ * Loss forward with full heads: P^(s)(. | a) = softmax(F_sa h) (eq. 6), the rest as in loss_fwd
+ * (eq. 7, 8, 9).  H[T,d] F[n,r,V,d] G[r,d] X[T,n]; loss[T]; optional logw[T,r], C[T,n,r], lse[T,n,r].
+ */
+int CPO(full_loss_fwd)(const cpo_shape *sh, const in_t *H, const in_t *F, const in_t *G, const int32_t *X,
+                       double *loss, double *logw_out, double *C_out, double *lse_out)
+{
+    if (sh->T < 0 || sh->d <= 0 || sh->V <= 0 || sh->n <= 0 || sh->r <= 0) return -1;
+    const int d = sh->d, V = sh->V, n = sh->n, r = sh->r;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *z = malloc(sizeof(double) * V), *logw = malloc(sizeof(double) * r), *a = malloc(sizeof(double) * r);
+        if (!z || !logw || !a) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t t = 0; t < sh->T; ++t) {
+                const in_t *h = H + (size_t)t * d;
+                gate_logw(sh, h, G, logw);
+                for (int al = 0; al < r; ++al) a[al] = logw[al];
+                for (int s = 0; s < n; ++s)
+                    for (int al = 0; al < r; ++al) {
+                        full_head_z(sh, h, F, s, al, z);
+                        double lse = logsumexp(z, V);
+                        int32_t x = X[(size_t)t * n + s];
+                        double C = (x >= 0) ? z[x] - lse : 0.0;       /* eq. 8 */
+                        a[al] += C;
+                        size_t idx = ((size_t)t * n + s) * r + al;
+                        if (C_out) C_out[idx] = C;
+                        if (lse_out) lse_out[idx] = lse;
+                    }
+                loss[t] = -logsumexp(a, r);                            /* eq. 9 */
+                if (logw_out) for (int al = 0; al < r; ++al) logw_out[(size_t)t * r + al] = logw[al];
+            }
+        }
+        free(z); free(logw); free(a);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Gradients of sum_t dloss[t] * loss[t] with full heads: with gamma, dz and dg as in loss_bwd,
+ *   dF_sa = sum_t dz_tsa (x) h_t ,  dG = sum_t dg_t (x) h_t ,  dh_t = sum_sa F_sa^T dz_tsa + G^T dg_t.
+ * dH[T,d], dF[n,r,V,d], dG[r,d] are overwritten; any may be NULL; dloss may be NULL (all ones).
+ * Stores dz for every (t, s, a): small T only.
+ */
+int CPO(full_loss_bwd)(const cpo_shape *sh, const in_t *H, const in_t *F, const in_t *G, const int32_t *X,
+                       const double *dloss, double *dH, double *dF, double *dG)
+{
+    const int d = sh->d, V = sh->V, n = sh->n, r = sh->r;
+    const int64_t T = sh->T;
+    const size_t nr = (size_t)n * r;
+    double *dz_all = malloc(sizeof(double) * ((size_t)T * nr * V + 1));
+    double *dg_all = malloc(sizeof(double) * ((size_t)T * r + 1));
+    if (!dz_all || !dg_all) { free(dz_all); free(dg_all); return -1; }
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *z = malloc(sizeof(double) * V), *logw = malloc(sizeof(double) * r), *a = malloc(sizeof(double) * r);
+        if (!z || !logw || !a) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t t = 0; t < T; ++t) {
+                const in_t *h = H + (size_t)t * d;
+                const double up = dloss ? dloss[t] : 1.0;
+                gate_logw(sh, h, G, logw);
+                for (int al = 0; al < r; ++al) a[al] = logw[al];
+                for (int s = 0; s < n; ++s)
+                    for (int al = 0; al < r; ++al) {
+                        double *dz = dz_all + (((size_t)t * n + s) * r + al) * V;
+                        full_head_z(sh, h, F, s, al, z);
+                        double l = logsumexp(z, V);
+                        for (int v = 0; v < V; ++v) dz[v] = z[v] - l;   /* log P^(s)(v | al) for now */
+                        int32_t x = X[(size_t)t * n + s];
+                        if (x >= 0) a[al] += dz[x];
+                    }
+                double L = logsumexp(a, r);
+                for (int al = 0; al < r; ++al) {
+                    double gamma = exp(a[al] - L);
+                    dg_all[(size_t)t * r + al] = up * (exp(logw[al]) - gamma);
+                    for (int s = 0; s < n; ++s) {
+                        double *dz = dz_all + (((size_t)t * n + s) * r + al) * V;
+                        int32_t x = X[(size_t)t * n + s];
+                        if (x < 0) {
+                            for (int v = 0; v < V; ++v) dz[v] = 0.0;
+                        } else {
+                            for (int v = 0; v < V; ++v) dz[v] = up * gamma * exp(dz[v]);
+                            dz[x] -= up * gamma;
+                        }
+                    }
+                }
+                if (dH) {
+                    double *dh = dH + (size_t)t * d;
+                    for (int j = 0; j < d; ++j) {
+                        double acc = 0.0;
+                        for (size_t sa = 0; sa < nr; ++sa) {
+                            const in_t *Fsa = F + sa * V * d;
+                            const double *dz = dz_all + ((size_t)t * nr + sa) * V;
+                            for (int v = 0; v < V; ++v) acc += (double)Fsa[(size_t)v * d + j] * dz[v];
+                        }
+                        for (int al = 0; al < r; ++al)
+                            acc += (double)G[(size_t)al * d + j] * dg_all[(size_t)t * r + al];
+                        dh[j] = acc;
+                    }
+                }
+            }
+        }
+        free(z); free(logw); free(a);
+    }
+    if (!fail && dF) {
+#pragma omp parallel for schedule(static)
+        for (int64_t sav = 0; sav < (int64_t)nr * V; ++sav) {   /* (s, al, v) */
+            size_t sa = (size_t)sav / V;
+            int v = (int)(sav % V);
+            double *out = dF + (size_t)sav * d;
+            for (int j = 0; j < d; ++j) out[j] = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double dzv = dz_all[((size_t)t * nr + sa) * V + v];
+                const in_t *h = H + (size_t)t * d;
+                for (int j = 0; j < d; ++j) out[j] += dzv * (double)h[j];
+            }
+        }
+    }
+    if (!fail && dG) {
+        for (int al = 0; al < r; ++al)
+            for (int j = 0; j < d; ++j) {
+                double acc = 0.0;
+                for (int64_t t = 0; t < T; ++t) acc += dg_all[(size_t)t * r + al] * (double)H[(size_t)t * d + j];
+                dG[(size_t)al * d + j] = acc;
+            }
+    }
+    free(dz_all); free(dg_all);
+    return fail ? -1 : 0;
 }
 
 /* For tests of the rounding helper. */

@@ -237,6 +237,46 @@ def aux_balance(H, G):
     return counts, laux.value
 
 
+def _prep_full(H, F, G):
+    kinds = {np.asarray(a).dtype for a in (H, F, G)}
+    kind, dt = ("f32", np.float32) if kinds == {np.dtype(np.float32)} else ("f64", np.float64)
+    H, F, G = (np.ascontiguousarray(a, dtype=dt) for a in (H, F, G))
+    n, r, V, d = F.shape
+    assert H.shape[1] == d and G.shape == (r, d)
+    return kind, H, F, G, _Shape(H.shape[0], d, V, n, r, 0)
+
+
+def full_loss_fwd(H, F, G, X, details: bool = False):
+    """Loss with full heads F[n,r,V,d] (eq. 6 as printed): loss[T] (and logw, C, lse with details)."""
+    kind, H, F, G, sh = _prep_full(H, F, G)
+    X = np.ascontiguousarray(X, dtype=np.int32)
+    assert X.shape == (sh.T, sh.n)
+    loss = np.empty(sh.T)
+    logw = np.empty((sh.T, sh.r)) if details else None
+    C = np.empty((sh.T, sh.n, sh.r)) if details else None
+    lse = np.empty((sh.T, sh.n, sh.r)) if details else None
+    fn = getattr(_lib(kind), f"cpo_{kind}_full_loss_fwd")
+    fn.restype = ctypes.c_int
+    if fn(ctypes.byref(sh), _p(H), _p(F), _p(G), _p(X), _p(loss), _p(logw), _p(C), _p(lse)) != 0:
+        raise RuntimeError("oracle full_loss_fwd failed")
+    return (loss, logw, C, lse) if details else loss
+
+
+def full_loss_bwd(H, F, G, X, dloss=None, want=("dH", "dF", "dG")):
+    """Gradients of sum_t dloss[t] * loss[t] with full heads: dict with dH[T,d], dF[n,r,V,d], dG[r,d]."""
+    kind, H, F, G, sh = _prep_full(H, F, G)
+    X = np.ascontiguousarray(X, dtype=np.int32)
+    dl = None if dloss is None else np.ascontiguousarray(dloss, dtype=np.float64)
+    out = {"dH": np.empty(H.shape) if "dH" in want else None,
+           "dF": np.empty(F.shape) if "dF" in want else None,
+           "dG": np.empty(G.shape) if "dG" in want else None}
+    fn = getattr(_lib(kind), f"cpo_{kind}_full_loss_bwd")
+    fn.restype = ctypes.c_int
+    if fn(ctypes.byref(sh), _p(H), _p(F), _p(G), _p(X), _p(dl), _p(out["dH"]), _p(out["dF"]), _p(out["dG"])) != 0:
+        raise RuntimeError("oracle full_loss_bwd failed")
+    return {k: v for k, v in out.items() if v is not None}
+
+
 def round_to_bf16(v: float) -> float:
     fn = _lib("f64").cpo_f64_round_to_bf16
     fn.restype = ctypes.c_double

@@ -432,3 +432,74 @@ def test_aux_balance(oracle):
     counts, _ = oracle.aux_balance(Hs, Gs)
     _, logw, _, _ = oracle.loss_fwd(Hs, W, U, Gs, X, details=True)
     assert counts.tolist() == np.bincount(np.argmax(logw, axis=1), minlength=Gs.shape[0]).tolist()
+
+
+# ---------------------------------------------------------------------------
+# full heads (eq. 6 as printed): one V x d matrix per (s, a)
+# ---------------------------------------------------------------------------
+
+def full_problem(T=5, d=7, V=6, n=2, r=3, seed=5):
+    rng = np.random.default_rng(seed)
+    H = rng.standard_normal((T, d))
+    F = rng.standard_normal((n, r, V, d)) * (1.2 / np.sqrt(d))
+    G = rng.standard_normal((r, d)) / np.sqrt(d)
+    X = rng.integers(0, V, size=(T, n)).astype(np.int32)
+    return H, F, G, X
+
+
+def test_full_heads_reduce_to_the_shared_unembedding_head(oracle):
+    # F_sa = U W_sa is the reduced head of "Fine tuning": both routines must agree, and the chain rule
+    # ties the gradients together: dW_sa = U^T dF_sa, dU = sum_sa dF_sa W_sa^T.
+    H, W, U, G, X = small_problem()
+    F = np.einsum("vk,sakj->savj", U, W)
+    X[1, 2] = -1
+    np.testing.assert_allclose(oracle.full_loss_fwd(H, F, G, X), oracle.loss_fwd(H, W, U, G, X), rtol=1e-12)
+    dl = np.random.default_rng(2).standard_normal(H.shape[0])
+    gf = oracle.full_loss_bwd(H, F, G, X, dl)
+    gr = oracle.loss_bwd(H, W, U, G, X, dl)
+    np.testing.assert_allclose(gf["dH"], gr["dH"], rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(gf["dG"], gr["dG"], rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(np.einsum("vk,savj->sakj", U, gf["dF"]), gr["dW"], rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(np.einsum("savj,sakj->vk", gf["dF"], W), gr["dU"], rtol=1e-10, atol=1e-13)
+
+
+def test_full_heads_rank_one_single_token_is_softmax_cross_entropy(oracle):
+    H, F, G, X = full_problem(n=1, r=1)
+    ref = -np.array([sps.log_softmax(F[0, 0] @ H[t])[X[t, 0]] for t in range(H.shape[0])])
+    np.testing.assert_allclose(oracle.full_loss_fwd(H, F, G, X), ref, rtol=1e-12)
+
+
+def test_full_heads_joint_sums_to_one(oracle):
+    H, F, G, _ = full_problem(T=1, V=5, n=3, r=2)
+    tuples = np.array(list(itertools.product(range(5), repeat=3)), dtype=np.int32)
+    loss = oracle.full_loss_fwd(np.tile(H, (len(tuples), 1)), F, G, tuples)
+    assert abs(np.exp(-loss).sum() - 1.0) < 1e-12
+
+
+@pytest.mark.parametrize("which", ["H", "F", "G"])
+def test_full_heads_gradients_match_central_differences(oracle, which):
+    H, F, G, X = full_problem()
+    X[0, 1] = -1
+    dl = np.random.default_rng(3).standard_normal(H.shape[0])
+    grads = oracle.full_loss_bwd(H, F, G, X, dl)
+    args = {"H": H, "F": F, "G": G}
+    rng = np.random.default_rng(4)
+    eps = 1e-6
+    for _ in range(12):
+        idx = tuple(rng.integers(0, s) for s in args[which].shape)
+        vals = []
+        for sign in (+1, -1):
+            pert = {k: v.copy() for k, v in args.items()}
+            pert[which][idx] += sign * eps
+            vals.append(float(dl @ oracle.full_loss_fwd(pert["H"], pert["F"], pert["G"], X)))
+        fd = (vals[0] - vals[1]) / (2 * eps)
+        np.testing.assert_allclose(grads["d" + which][idx], fd, rtol=2e-6, atol=2e-9)
+
+
+def test_full_heads_invariants(oracle):
+    H, F, G, X = full_problem()
+    X[:, 1] = -1                                     # the second factor is dropped everywhere
+    g = oracle.full_loss_bwd(H, F, G, X)
+    assert np.abs(g["dF"][1]).max() == 0.0
+    np.testing.assert_allclose(g["dF"][0].sum(axis=1), 0.0, atol=1e-13)      # sum_v dz_v = 0
+    np.testing.assert_allclose(g["dG"].sum(axis=0), 0.0, atol=1e-13)         # sum_a dg_a = 0
