@@ -68,7 +68,8 @@ enum {
 
 enum {
     CP_HEAD_OP_LOSS_FWD = 0, CP_HEAD_OP_LOSS_BWD = 1, CP_HEAD_OP_DRAFT = 2,
-    CP_HEAD_OP_FIRST_TOKEN = 3, CP_HEAD_OP_DRAFT_SEQUENTIAL = 4, CP_HEAD_OP_AUX_BALANCE = 5
+    CP_HEAD_OP_FIRST_TOKEN = 3, CP_HEAD_OP_DRAFT_SEQUENTIAL = 4, CP_HEAD_OP_AUX_BALANCE = 5,
+    CP_HEAD_OP_FULL_LOSS_FWD = 6, CP_HEAD_OP_FULL_LOSS_BWD = 7
 };
 
 typedef struct cp_head_desc {
@@ -188,6 +189,33 @@ int cp_head_draft_sample_sequential(const cp_head_desc *desc,
 int cp_head_aux_balance(const cp_head_desc *desc, const void *H, const void *G,
                         int64_t *counts, float *laux,
                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Full heads (eq. 6 as printed): every (s, a) has its own V x d matrix and there is no shared
+ * unembedding,
+ *     P^(s)(. | a) = softmax(F_sa h),      F[n,r,V,d] in the storage type of desc->dtype,
+ * the parameterisation the paper trains from scratch; gate, eq. 8 and eq. 9 as in cp_head_loss_fwd.
+ * cp_head_full_ctx_bytes sizes the `ctx` these two calls share (log-normalisers, gate weights,
+ * posterior); workspaces are sized by cp_head_workspace_bytes with CP_HEAD_OP_FULL_LOSS_FWD / _BWD.
+ * Forward: loss[T] fp32, overwritten.  Backward: gradients of sum_t dloss[t] * loss[t] (dloss and
+ * scale as in cp_head_loss_bwd); dH[T,d] (required), dF[n,r,V,d] and dG[r,d] (either may be NULL)
+ * are fp32 and overwritten.  Logits are recomputed head by head for a bounded chunk of positions;
+ * nothing of size T*n*r*V is ever stored.
+ * Matrix-core path only (bf16, d a multiple of 64): other shapes return CP_HEAD_ERR_UNSUPPORTED.
+ */
+int cp_head_full_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
+int cp_head_full_loss_fwd(const cp_head_desc *desc,
+                          const void *H, const void *F, const void *G,
+                          const int32_t *X,
+                          float *loss,
+                          void *ctx, void *workspace, size_t workspace_bytes, void *stream);
+int cp_head_full_loss_bwd(const cp_head_desc *desc,
+                          const void *H, const void *F, const void *G,
+                          const int32_t *X,
+                          const float *dloss, float scale,
+                          const void *ctx,
+                          float *dH, float *dF, float *dG,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Optional per-kernel timing for benchmarks (not part of the method).  While

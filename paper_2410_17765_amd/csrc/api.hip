@@ -60,6 +60,8 @@ bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) 
 size_t workspace_need(const cp_head_desc &ds, int op)
 {
     if (op == CP_HEAD_OP_AUX_BALANCE) return 256;   // none needed; a token size keeps the calling pattern uniform
+    if (op == CP_HEAD_OP_FULL_LOSS_FWD || op == CP_HEAD_OP_FULL_LOSS_BWD)   // not served on the plain path
+        return use_fast_path(ds) ? fast_workspace_bytes(ds, op) : 256;
     if (use_fast_path(ds)) return fast_workspace_bytes(ds, op);
     if (op == CP_HEAD_OP_FIRST_TOKEN) return generic_first_token_workspace_bytes(ds);
     if (op == CP_HEAD_OP_DRAFT_SEQUENTIAL) return 256;   // not served on the plain path
@@ -131,7 +133,7 @@ int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes)
     if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
     const int rc = check_desc(desc);
     if (rc != CP_HEAD_OK) return rc;
-    if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_AUX_BALANCE) return CP_HEAD_ERR_INVALID_ARG;
+    if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_FULL_LOSS_BWD) return CP_HEAD_ERR_INVALID_ARG;
     *bytes = workspace_need(*desc, op);
     return CP_HEAD_OK;
 }
@@ -228,6 +230,43 @@ int cp_head_aux_balance(const cp_head_desc *desc, const void *H, const void *G, 
     if (!G || !counts || !laux) return CP_HEAD_ERR_INVALID_ARG;
     if (desc->T > 0 && !H) return CP_HEAD_ERR_INVALID_ARG;
     return aux_balance(*desc, H, G, counts, laux, static_cast<hipStream_t>(stream));
+}
+
+int cp_head_full_ctx_bytes(const cp_head_desc *desc, size_t *bytes)
+{
+    if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
+    const int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    *bytes = fast_full_ctx_bytes(*desc);
+    return CP_HEAD_OK;
+}
+
+int cp_head_full_loss_fwd(const cp_head_desc *desc, const void *H, const void *F, const void *G, const int32_t *X,
+                          float *loss, void *ctx, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!F || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !X || !loss)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!use_fast_path(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
+    if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_FULL_LOSS_FWD)) return CP_HEAD_ERR_WORKSPACE;
+    return fast_full_loss_fwd(*desc, H, F, G, X, loss, ctx, workspace, static_cast<hipStream_t>(stream));
+}
+
+int cp_head_full_loss_bwd(const cp_head_desc *desc, const void *H, const void *F, const void *G, const int32_t *X,
+                          const float *dloss, float scale, const void *ctx, float *dH, float *dF, float *dG,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!F || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !X || !dH)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!use_fast_path(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
+    if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_FULL_LOSS_BWD)) return CP_HEAD_ERR_WORKSPACE;
+    return fast_full_loss_bwd(*desc, H, F, G, X, dloss, scale, ctx, dH, dF, dG, workspace,
+                              static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

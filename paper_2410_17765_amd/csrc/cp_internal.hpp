@@ -119,4 +119,11 @@ int fast_first_token(const cp_head_desc &ds, const void *H, const void *W, const
 int fast_draft_sequential(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                           const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 
+size_t fast_full_ctx_bytes(const cp_head_desc &ds);
+int fast_full_loss_fwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
+                       float *loss, void *ctx, void *ws, hipStream_t st);
+int fast_full_loss_bwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
+                       const float *dloss, float scale, const void *ctx, float *dH, float *dF, float *dG, void *ws,
+                       hipStream_t st);
+
 }  // namespace cph

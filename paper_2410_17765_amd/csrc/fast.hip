@@ -807,6 +807,52 @@ __global__ void k_dgate_reduce(int chunks, int d, int r, const float *__restrict
 }
 
 // ------------------------------------------------------------------------------------------
+// full heads (eq. 6 as printed: one V x d matrix F_sa per (s, a), no shared unembedding)
+// Per-row quantities of this variant are kept head-major, index sa * T + t: every (s, a) runs its own
+// products over the T positions, so its rows are contiguous for the epilogues above.
+// ------------------------------------------------------------------------------------------
+
+// One wavefront per (sa, t): log-normaliser from the statistics (eq. 5), target logit as an fp32 dot
+// product of F_sa[x] with h (both bf16, so the products are exact), C = z[x] - lse (eq. 8).
+__global__ void __launch_bounds__(kBlock) k_full_row_finish(size_t T, int d, int V, int n, int r, int parts,
+                                                            const float2 *__restrict__ part,
+                                                            const bf16_t *__restrict__ H, const bf16_t *__restrict__ F,
+                                                            const int32_t *__restrict__ X, float *__restrict__ lse_out,
+                                                            float *__restrict__ C_out)
+{
+    const size_t idx = (size_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    if (idx >= T * n * r) return;
+    const int lane = threadIdx.x & 63;
+    const size_t sa = idx / T, t = idx % T;
+    const int s = (int)(sa / r), a = (int)(sa % r);
+    const float lse = row_lse_from_parts(part + idx * parts, parts, lane);
+    const int x = X[t * n + s];
+    float zt = 0.f;
+    if (x >= 0) zt = wave_dot_bf16(F + (sa * V + x) * d, H + t * d, d, lane);
+    if (lane == 0) {
+        lse_out[idx] = lse;
+        C_out[(t * n + s) * r + a] = (x >= 0) ? zt - lse : 0.f;
+    }
+}
+
+// Per (sa, t): {lse, coef = up_t * gamma[t, a] (zero for dropped factors), target}; dg[t, a] = up_t (w - gamma)
+__global__ void k_full_bwd_coefficients(size_t T, int n, int r, const float *__restrict__ w,
+                                        const float *__restrict__ gamma, const float *__restrict__ lse,
+                                        const float *__restrict__ dloss, float scale, const int32_t *__restrict__ X,
+                                        float4 *__restrict__ rowinfo, float *__restrict__ dg)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= T * n * r) return;
+    const size_t sa = idx / T, t = idx % T;
+    const int s = (int)(sa / r), a = (int)(sa % r);
+    const float up = dloss ? dloss[t] * scale : scale;
+    const float gm = gamma[t * r + a];
+    const int x = X[t * n + s];
+    rowinfo[idx] = make_float4(lse[idx], (x >= 0) ? up * gm : 0.f, __int_as_float(x), 0.f);
+    if (s == 0) dg[t * r + a] = up * (w[t * r + a] - gm);
+}
+
+// ------------------------------------------------------------------------------------------
 // workspace layouts
 // ------------------------------------------------------------------------------------------
 
@@ -874,6 +920,79 @@ inline BwdWs bwd_ws(const cp_head_desc &ds)
     return b;
 }
 
+// Saved-for-backward buffer of the full-head calls: [lse nr*T f32, head-major][w T*r][gamma T*r]
+struct FullCtx {
+    size_t lse, w, gamma, total;
+};
+inline FullCtx full_ctx(const cp_head_desc &ds)
+{
+    FullCtx c;
+    const size_t M = (size_t)ds.T * ds.n * ds.r, Tr = (size_t)ds.T * ds.r;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    c.lse = take(M * 4);
+    c.w = take(Tr * 4);
+    c.gamma = take(Tr * 4);
+    c.total = off;
+    return c;
+}
+
+struct FullFwdWs {
+    size_t logw, C, part, total;
+    int parts;
+};
+inline FullFwdWs full_fwd_ws(const cp_head_desc &ds)
+{
+    FullFwdWs f;
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    f.parts = ((ds.V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    f.logw = take((size_t)ds.T * ds.r * 4);
+    f.C = take(M * 4);
+    f.part = take(M * f.parts * sizeof(float2));
+    f.total = off;
+    return f;
+}
+
+// Positions whose logit gradients (for one head at a time) are held together: about 2 GiB of bf16
+inline size_t full_chunk_rows(const cp_head_desc &ds)
+{
+    const size_t Vp = round_up((size_t)ds.V, 64);
+    size_t rows = ((size_t)1 << 31) / (Vp * 2);
+    rows = rows / Cfg::BM * Cfg::BM;
+    if (rows < (size_t)Cfg::BM || (ds.flags & CP_HEAD_MIN_WORKSPACE)) rows = Cfg::BM;
+    const size_t T = (size_t)ds.T;
+    return rows < T ? rows : (T ? T : 1);
+}
+
+struct FullBwdWs {
+    size_t coef, dg, dGpart, Ft, Ht, dZ, dZt, total;
+    size_t Vp, Tp, chunk, chunk_p;
+    size_t ldV, ldT, ldM;
+};
+inline FullBwdWs full_bwd_ws(const cp_head_desc &ds)
+{
+    FullBwdWs b;
+    const size_t T = (size_t)ds.T, M = T * ds.n * ds.r;
+    b.Vp = round_up((size_t)ds.V, 64);
+    b.Tp = round_up(T, 64);
+    b.chunk = full_chunk_rows(ds);
+    b.chunk_p = round_up(b.chunk, 64);
+    b.ldV = b.Vp + 64; b.ldT = b.Tp + 64; b.ldM = b.chunk_p + 64;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    b.coef = take(M * 16);
+    b.dg = take(T * ds.r * 4);
+    b.dGpart = take(((T + kGateChunk - 1) / kGateChunk) * ds.r * ds.d * 4);
+    b.Ft = take((size_t)ds.d * b.ldV * 2);
+    b.Ht = take((size_t)ds.d * b.ldT * 2);
+    b.dZ = take(b.chunk * b.Vp * 2);
+    b.dZt = take((size_t)ds.V * b.ldM * 2);
+    b.total = off;
+    return b;
+}
+
 inline bool dims_fit(const cp_head_desc &ds)
 {
     // the GEMM addresses rows of a tile with 32-bit byte offsets and counts rows in int
@@ -937,6 +1056,8 @@ size_t fast_workspace_bytes(const cp_head_desc &ds, int op)
     if (op == CP_HEAD_OP_LOSS_FWD) return fwd_ws(ds).total;
     if (op == CP_HEAD_OP_LOSS_BWD) return bwd_ws(ds).total;
     if (op == CP_HEAD_OP_FIRST_TOKEN) return first_token_ws(ds).total;
+    if (op == CP_HEAD_OP_FULL_LOSS_FWD) return full_fwd_ws(ds).total;
+    if (op == CP_HEAD_OP_FULL_LOSS_BWD) return full_bwd_ws(ds).total;
     return draft_ws(ds).total;   // both draft calls
 }
 
@@ -1148,6 +1269,91 @@ int fast_draft_sequential(const cp_head_desc &ds, const void *Hv, const void *Wv
     ProfileScope prof("seq_draw", (double)B * n * r * seg_cols * d * 2, st);
     k_draft_sequential<<<(unsigned)B, kSeqBlock, 0, st>>>(d, V, n, r, parts, seg_cols, part, Y, U, logw, uniforms, tokens,
                                                           logq);                                             // eq. 11-13
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------------------------------
+// full heads: loss forward and backward
+// ------------------------------------------------------------------------------------------
+
+size_t fast_full_ctx_bytes(const cp_head_desc &ds) { return full_ctx(ds).total; }
+
+int fast_full_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Fv, const void *Gv, const int32_t *X,
+                       float *loss, void *ctx, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *F = (const bf16_t *)Fv;
+    const FullCtx cl = full_ctx(ds);
+    const FullFwdWs f = full_fwd_ws(ds);
+    const int T = (int)ds.T, d = ds.d, V = ds.V, nr = ds.n * ds.r;
+    const size_t M = (size_t)T * nr;
+    float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    float *logw = at<float>(ws, f.logw), *C = at<float>(ws, f.C);
+    float2 *part = at<float2>(ws, f.part);
+    launch_gate(ds, Hv, Gv, logw, w, st);                                                       // eq. 7
+    for (int sa = 0; sa < nr; ++sa)                                                             // z_sa = F_sa h (eq. 6), statistics
+        launch_gemm_nt<Cfg>("full_gemm_z_stats", H, d, T, F + (size_t)sa * V * d, d, V, d,
+                            EpiRowStats{part + (size_t)sa * T * f.parts, f.parts, T, V}, st);
+    k_full_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>((size_t)T, d, V, ds.n, ds.r, f.parts, part, H, F, X,
+                                                                        lse, C);             // eq. 5, 8
+    launch_mixture(ds, logw, C, loss, gamma, -1.f, st);                                         // eq. 9
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int fast_full_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Fv, const void *Gv, const int32_t *X,
+                       const float *dloss, float scale, const void *ctx, float *dH, float *dF, float *dG, void *ws,
+                       hipStream_t st)
+{
+    const int d = ds.d, V = ds.V, r = ds.r, n = ds.n, nr = n * r;
+    if (ds.T == 0) {
+        if (dF) launch_fill_zero(dF, (size_t)nr * V * d, st);
+        if (dG) launch_fill_zero(dG, (size_t)r * d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *F = (const bf16_t *)Fv, *G = (const bf16_t *)Gv;
+    const FullCtx cl = full_ctx(ds);
+    const FullBwdWs b = full_bwd_ws(ds);
+    const size_t T = (size_t)ds.T, M = T * nr;
+    const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    float4 *rowinfo = at<float4>(ws, b.coef);
+    float *dg = at<float>(ws, b.dg);
+    bf16_t *Ft = at<bf16_t>(ws, b.Ft), *Ht = at<bf16_t>(ws, b.Ht);
+    bf16_t *dZ = at<bf16_t>(ws, b.dZ), *dZt = at<bf16_t>(ws, b.dZt);
+    const int Vp = (int)b.Vp, Tp = (int)b.Tp;
+    const long ldV = (long)b.ldV, ldT = (long)b.ldT, ldM = (long)b.ldM;
+
+    k_full_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(T, n, r, w, gamma, lse, dloss, scale, X, rowinfo, dg);
+    if (dF) transpose_bf16(H, d, (int)T, d, Ht, ldT, Tp, st);         // Ht[d, Tp]
+    int first_chunk = 1;
+    for (size_t t0 = 0; t0 < T; t0 += b.chunk) {
+        const int Tc = (int)((T - t0 < b.chunk) ? T - t0 : b.chunk);
+        const int Tcp = (int)round_up((size_t)Tc, 64);
+        const bf16_t *Hc = H + t0 * d;
+        for (int sa = 0; sa < nr; ++sa) {
+            const bf16_t *Fsa = F + (size_t)sa * V * d;
+            // recompute z_sa for these positions; the epilogue turns it into dz (bf16), also transposed
+            launch_gemm_nt<Cfg>("full_gemm_z_dz", Hc, d, Tc, Fsa, d, V, d,
+                                EpiDz{dZ, (long)Vp, dF ? dZt : nullptr, ldM, rowinfo + (size_t)sa * T + t0, Tc, Tcp, V, Vp}, st);
+            // dH += dz F_sa   (contraction over the vocabulary)
+            transpose_bf16(Fsa, d, V, d, Ft, ldV, Vp, st);            // Ft[d, Vp]
+            launch_gemm_nt<Cfg>("full_gemm_dh", dZ, Vp, Tc, Ft, ldV, d, Vp,
+                                EpiStoreF32{dH + t0 * d, (long)d, Tc, d, sa ? 1 : 0}, st);
+            // dF_sa += dz^T H   (contraction over the positions of the chunk)
+            if (dF)
+                launch_gemm_nt<Cfg>("full_gemm_df", dZt, ldM, V, Ht + t0, ldT, d, Tcp,
+                                    EpiStoreF32{dF + (size_t)sa * V * d, (long)d, V, d, first_chunk ? 0 : 1}, st);
+        }
+        first_chunk = 0;
+    }
+    k_add_gate_to_dh<<<blocks_for(T * d, kBlock), kBlock, 0, st>>>(T, d, r, G, dg, dH);       // + G^T dg
+    if (dG) {
+        float *part = at<float>(ws, b.dGpart);
+        const unsigned chunks = (unsigned)((T + kGateChunk - 1) / kGateChunk);
+        k_dgate_partial<<<dim3(blocks_for((size_t)d, kBlock), chunks), kBlock, 0, st>>>(T, d, r, H, dg, part);
+        k_dgate_reduce<<<blocks_for((size_t)r * d, kBlock), kBlock, 0, st>>>((int)chunks, d, r, part, dG);
+    }
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 

@@ -126,3 +126,45 @@ class CpHead:
         laux = torch.empty(1, dtype=torch.float32, device=self.device)
         binding.cp_head_aux_balance(ds, H, self.G, counts, laux, ws, stream)
         return counts, laux
+
+
+class CpFullHead:
+    """Full heads F[n,r,V,d] (one V x d matrix per future token and expert) plus the gate, on the device."""
+
+    def __init__(self, F: np.ndarray, G: np.ndarray, dtype: str = "bf16", flags: int = 0, device="cuda:0"):
+        self.device = torch.device(device)
+        self.dtype = dtype
+        self.flags = flags
+        self.n, self.r, self.V, self.d = F.shape
+        self.F = to_device(F, dtype, self.device)
+        self.G = to_device(G, dtype, self.device)
+        self._ctx: Optional[torch.Tensor] = None
+
+    def desc(self, T: int) -> binding.Desc:
+        return binding.make_desc(T, self.d, self.V, self.n, self.r,
+                                 binding.BF16 if self.dtype == "bf16" else binding.FP32, self.flags)
+
+    def loss_fwd(self, H: torch.Tensor, X: torch.Tensor, stream=None) -> torch.Tensor:
+        T = H.shape[0]
+        ds = self.desc(T)
+        self._ctx = _scratch(binding.cp_head_full_ctx_bytes(ds), self.device)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_FWD), self.device)
+        loss = torch.empty(T, dtype=torch.float32, device=self.device)
+        binding.cp_head_full_loss_fwd(ds, H, self.F, self.G, X, loss, self._ctx, ws, stream)
+        return loss
+
+    def loss_bwd(self, H: torch.Tensor, X: torch.Tensor, dloss: Optional[torch.Tensor] = None, scale: float = 1.0,
+                 want_dF: bool = True, stream=None) -> Dict[str, torch.Tensor]:
+        assert self._ctx is not None, "call loss_fwd first"
+        T = H.shape[0]
+        ds = self.desc(T)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_BWD), self.device)
+        f32 = dict(dtype=torch.float32, device=self.device)
+        out = {
+            "dH": torch.empty((T, self.d), **f32),
+            "dF": torch.empty((self.n, self.r, self.V, self.d), **f32) if want_dF else None,
+            "dG": torch.empty((self.r, self.d), **f32),
+        }
+        binding.cp_head_full_loss_bwd(ds, H, self.F, self.G, X, dloss, scale, self._ctx,
+                                      out["dH"], out["dF"], out["dG"], ws, stream)
+        return {k: v for k, v in out.items() if v is not None}

@@ -36,6 +36,7 @@ SEED_TARGETS = 1005
 SEED_UNIFORMS = 1006
 SEED_SUBSET = 1007
 SEED_PERM = 1008
+SEED_F = 1010
 
 
 @dataclasses.dataclass(frozen=True)
@@ -69,6 +70,9 @@ CONFIGS: Dict[str, HeadConfig] = {
     "head_7b": HeadConfig("head_7b", T=16384, d=4096, V=32000, n=4, r=8),
     "large_vocab": HeadConfig("large_vocab", T=16384, d=4096, V=128256, n=3, r=4),
     "draft": HeadConfig("draft", T=8, d=4096, V=128256, n=4, r=8),
+    # full V x d heads per (s, a) (no shared unembedding): the from-scratch parameterisation at a size
+    # whose 2.1 GB of head weights the host can still generate in seconds
+    "full_heads": HeadConfig("full_heads", T=8192, d=2048, V=32000, n=2, r=4),
 }
 
 
@@ -144,6 +148,11 @@ def head_weights(cfg: HeadConfig) -> np.ndarray:
 def unembedding(cfg: HeadConfig) -> np.ndarray:
     """U[V,d]."""
     return _normal(SEED_U, (cfg.V, cfg.d), cfg.u_scale * cfg.d ** -0.5, cfg.dtype)
+
+
+def full_head_weights(cfg: HeadConfig) -> np.ndarray:
+    """F[n,r,V,d]; z = F[s,a] @ h.  N(0, u_scale^2/d), the scale of the shared-unembedding logits."""
+    return _normal(SEED_F, (cfg.n, cfg.r, cfg.V, cfg.d), cfg.u_scale * cfg.d ** -0.5, cfg.dtype)
 
 
 def gate(cfg: HeadConfig) -> np.ndarray:

@@ -1,0 +1,168 @@
+"""GPU parity of the full-head variant (eq. 6 as printed: one V x d matrix per future token and expert,
+no shared unembedding) against the fp64 oracle: element by element at sizes that span several tiles
+with ragged tails, and on sampled positions at the `full_heads` benchmark size."""
+import numpy as np
+import pytest
+
+from paper_2410_17765_amd import synth
+from tests.helpers import GRAD_REL_FRO, LOSS_ATOL, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2410_17765_amd import binding, head
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()
+    return head
+
+
+def make(cfg):
+    return {"H": synth.hidden(cfg), "F": synth.full_head_weights(cfg), "G": synth.gate(cfg), "X": synth.targets(cfg)}
+
+
+def run(head, cfg, inp, dloss=None, flags=0, want_dF=True, scale=1.0):
+    import torch
+    h = head.CpFullHead(inp["F"], inp["G"], dtype=cfg.dtype, flags=flags)
+    H = head.to_device(inp["H"], cfg.dtype)
+    X = torch.from_numpy(inp["X"]).cuda()
+    loss = h.loss_fwd(H, X)
+    dl = None if dloss is None else torch.from_numpy(dloss).cuda()
+    grads = {k: v.cpu().numpy() for k, v in h.loss_bwd(H, X, dl, scale=scale, want_dF=want_dF).items()}
+    torch.cuda.synchronize()
+    return loss.cpu().numpy(), grads
+
+
+CASES = [
+    (synth.HeadConfig("full_small", T=300, d=128, V=1000, n=2, r=3, u_scale=2.0), 0),
+    (synth.HeadConfig("full_ragged", T=523, d=192, V=777, n=3, r=2, u_scale=3.0), 0),
+    (synth.HeadConfig("full_chunked", T=600, d=64, V=515, n=2, r=4, u_scale=2.0), 2),   # 256 positions per chunk
+    (synth.HeadConfig("full_one_position", T=1, d=64, V=300, n=1, r=1), 0),
+    (synth.HeadConfig("full_wide_rank", T=40, d=64, V=260, n=2, r=33, u_scale=2.0), 0),
+]
+
+
+@pytest.mark.parametrize("cfg,flags", CASES, ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_loss_and_gradients(gpu, oracle, cfg, flags):
+    print(f"case {cfg} flags={flags}", flush=True)
+    inp = make(cfg)
+    if cfg.T > 8:
+        inp["X"][3, 0] = -1                       # a dropped factor
+        inp["X"][5, :] = -1                       # a position with no targets at all
+    dloss = synth.upstream_grad(cfg.T).astype(np.float32)
+    loss, g = run(gpu, cfg, inp, dloss)
+    ref = oracle.full_loss_fwd(inp["H"], inp["F"], inp["G"], inp["X"])
+    err = np.abs(loss - ref).max()
+    print(f"  loss max abs err {err:.3e}", flush=True)
+    assert err <= LOSS_ATOL
+    rg = oracle.full_loss_bwd(inp["H"], inp["F"], inp["G"], inp["X"], dloss.astype(np.float64))
+    for k in ("dH", "dF", "dG"):
+        e = rel_fro(g[k], rg[k])
+        print(f"  {k} rel fro {e:.3e}", flush=True)
+        assert e <= GRAD_REL_FRO, k
+
+
+def test_frozen_heads_scale_and_determinism(gpu):
+    cfg = synth.HeadConfig("full_opts", T=130, d=64, V=300, n=2, r=2, u_scale=2.0)
+    inp = make(cfg)
+    l1, g1 = run(gpu, cfg, inp)
+    l2, g2 = run(gpu, cfg, inp)
+    np.testing.assert_array_equal(l1, l2)
+    for k in g1:
+        np.testing.assert_array_equal(g1[k], g2[k])
+    _, g3 = run(gpu, cfg, inp, want_dF=False, scale=0.5)
+    assert "dF" not in g3
+    np.testing.assert_allclose(g3["dH"], 0.5 * g1["dH"], rtol=2e-2, atol=1e-6)
+    np.testing.assert_allclose(g3["dG"], 0.5 * g1["dG"], rtol=2e-2, atol=1e-6)
+
+
+def test_empty_batch_and_plain_path(gpu):
+    import torch
+    from paper_2410_17765_amd import binding
+    cfg = synth.HeadConfig("full_empty", T=0, d=64, V=300, n=2, r=2)
+    h = gpu.CpFullHead(synth.full_head_weights(cfg), synth.gate(cfg), dtype="bf16")
+    H = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    X = torch.empty((0, 2), dtype=torch.int32, device="cuda")
+    assert h.loss_fwd(H, X).shape == (0,)
+    g = h.loss_bwd(H, X)
+    torch.cuda.synchronize()
+    assert float(g["dF"].abs().max()) == 0.0 and float(g["dG"].abs().max()) == 0.0
+    # fp32 storage is not served by this variant and says so
+    cfg32 = cfg.with_(T=4, dtype="fp32")
+    h32 = gpu.CpFullHead(synth.full_head_weights(cfg32), synth.gate(cfg32), dtype="fp32")
+    with pytest.raises(binding.CpHeadError):
+        h32.loss_fwd(torch.zeros((4, 64), device="cuda"), torch.zeros((4, 2), dtype=torch.int32, device="cuda"))
+
+
+# ---------------------------------------------------------------------------- benchmark size
+SUBSET = 8
+
+
+@pytest.fixture(scope="module")
+def full():
+    import gc
+    import torch
+    from paper_2410_17765_amd import head
+    cfg = synth.CONFIGS["full_heads"]
+    print(f"[full heads] generating {cfg}", flush=True)
+    inp = make(cfg)
+    h = head.CpFullHead(inp["F"], inp["G"], dtype=cfg.dtype)
+    H = head.to_device(inp["H"], cfg.dtype)
+    X = torch.from_numpy(inp["X"]).cuda()
+    scale = 1.0 / cfg.T
+    print("[full heads] running on the GPU", flush=True)
+    loss = h.loss_fwd(H, X)
+    grads = h.loss_bwd(H, X, None, scale=scale)
+    torch.cuda.synchronize()
+    yield dict(cfg=cfg, inp=inp, h=h, H=H, X=X, scale=scale, loss=loss, grads=grads, torch=torch, head=head)
+    del h, H, X, loss, grads
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def test_benchmark_size_sampled_positions(oracle, full):
+    cfg, inp, torch, head = full["cfg"], full["inp"], full["torch"], full["head"]
+    sel = synth.position_subset(cfg.T, SUBSET)
+    print(f"[full heads] oracle on positions {sel.tolist()}", flush=True)
+    ref = oracle.full_loss_fwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel])
+    err = np.abs(full["loss"].cpu().numpy()[sel] - ref).max()
+    print(f"  loss max abs err {err:.3e} (mean loss {ref.mean():.3f})", flush=True)
+    assert err <= LOSS_ATOL
+    rg = oracle.full_loss_bwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel], np.full(len(sel), full["scale"]))
+    e = rel_fro(full["grads"]["dH"][torch.from_numpy(sel).cuda()].cpu().numpy(), rg["dH"])
+    print(f"  dH rows rel fro {e:.3e}", flush=True)
+    assert e <= GRAD_REL_FRO
+    # weight gradients: a GPU call on exactly these positions
+    Hs = head.to_device(inp["H"][sel], cfg.dtype)
+    Xs = torch.from_numpy(inp["X"][sel]).cuda()
+    full["h"].loss_fwd(Hs, Xs)
+    g = full["h"].loss_bwd(Hs, Xs, None, scale=full["scale"])
+    torch.cuda.synchronize()
+    for k in ("dF", "dG", "dH"):
+        e = rel_fro(g[k].cpu().numpy(), rg[k])
+        print(f"  subset {k} rel fro {e:.3e}", flush=True)
+        assert e <= GRAD_REL_FRO, k
+
+
+def test_benchmark_size_batch_gradients_are_consistent(full):
+    cfg, torch, h, g = full["cfg"], full["torch"], full["h"], full["grads"]
+    half = cfg.T // 2
+    parts = []
+    for lo, hi in ((0, half), (half, cfg.T)):
+        Hh, Xh = full["H"][lo:hi].contiguous(), full["X"][lo:hi].contiguous()
+        h.loss_fwd(Hh, Xh)
+        gh = h.loss_bwd(Hh, Xh, None, scale=full["scale"])
+        torch.cuda.synchronize()
+        parts.append(gh)
+    for k in ("dF", "dG"):
+        tot = parts[0][k] + parts[1][k]
+        rel = float((tot - g[k]).double().norm() / g[k].double().norm())
+        print(f"  {k}: |full - (first half + second half)| / |full| = {rel:.3e}", flush=True)
+        assert rel <= 2e-3, k
+    rel = float((parts[1]["dH"] - g["dH"][half:]).double().norm() / g["dH"][half:].double().norm())
+    assert rel <= 2e-3
+    # sum_v dz_v = 0 for every row, so the columns of every dF_sa sum to zero over the vocabulary
+    col = g["dF"].double().sum(dim=2)
+    assert float((col.abs() / (g["dF"].double().abs().sum(dim=2) + 1e-30)).max()) < 2e-2
