@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token'")
+    ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token', 'full_heads', 'full_heads_7b'")
     ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per two threads)")
@@ -62,6 +62,99 @@ def cpu_baseline_loss(cfg, inp, positions):
     return {"value": len(sel) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"{len(sel)} seeded positions of the workload at full d, V, n, r; fp64 forward + backward "
                       f"with all gradients; {dt:.1f} s wall"}
+
+
+def bench_full(args):
+    """fwd+bwd step of the full-head variant (eq. 6: a V x d matrix per future token and expert).
+    `full_heads` takes its seeded inputs from synth; `full_heads_7b` is the headline shape, whose 8.4 GB of
+    head weights are drawn on the device (seeded torch generator): timing only, parity is shown at `full_heads`."""
+    import numpy as np
+    import torch
+    from paper_2410_17765_amd import binding, head, synth
+
+    binding.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    on_device = args.workload == "full_heads_7b"
+    cfg = synth.CONFIGS["head_7b"].with_(name="full_heads_7b") if on_device else synth.CONFIGS["full_heads"]
+    if on_device:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.SEED_F)
+        F = torch.empty((cfg.n, cfg.r, cfg.V, cfg.d), dtype=torch.bfloat16, device=dev)
+        for s in range(cfg.n):
+            for a in range(cfg.r):
+                F[s, a] = (torch.randn((cfg.V, cfg.d), generator=gen, device=dev) * cfg.d ** -0.5).to(torch.bfloat16)
+        G = head.to_device(synth.gate(cfg), cfg.dtype)
+        H = head.to_device(synth.hidden(cfg), cfg.dtype)
+        X = torch.from_numpy(synth.targets(cfg)).to(dev)
+        inp = None
+    else:
+        inp = {"H": synth.hidden(cfg), "F": synth.full_head_weights(cfg), "G": synth.gate(cfg), "X": synth.targets(cfg)}
+        F, G = head.to_device(inp["F"], cfg.dtype), head.to_device(inp["G"], cfg.dtype)
+        H = head.to_device(inp["H"], cfg.dtype)
+        X = torch.from_numpy(inp["X"]).to(dev)
+    ds = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, binding.BF16, 0)
+    ctx = torch.empty(binding.cp_head_full_ctx_bytes(ds), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_FWD),
+                         binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_BWD)), dtype=torch.uint8, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    loss = torch.empty(cfg.T, **f32)
+    dH = torch.empty((cfg.T, cfg.d), **f32)
+    dF = torch.empty((cfg.n, cfg.r, cfg.V, cfg.d), **f32)
+    dG = torch.empty((cfg.r, cfg.d), **f32)
+    scale = 1.0 / cfg.T
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        binding.cp_head_full_loss_fwd(ds, H, F, G, X, loss, ctx, ws, stream)
+        binding.cp_head_full_loss_bwd(ds, H, F, G, X, None, scale, ctx, dH, dF, dG, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.cp_head_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    binding.cp_head_profile_enable(False)
+    kernels = binding.cp_head_profile_read()
+    ms_per_step = dt * 1e3 / args.steps
+    gemms = [k for k in kernels if "gemm_" in k[0]]
+    dom = max(gemms, key=lambda k: k[2])
+    achieved = dom[3] / (dom[2] * 1e-3) / 1e12
+    model_flops = 6.0 * cfg.n * cfg.r * cfg.d * cfg.V * cfg.T
+    out = {
+        "metric": "CP-head (full heads) fwd+bwd tokens/s", "value": cfg.T * args.steps / dt, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic (head weights drawn on the device)" if on_device else "synthetic",
+        "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
+                   "token": "one position (n future tokens each)"},
+        "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
+        "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "mean_loss": float(loss.mean()),
+        "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "launches": dom[1],
+                     "avg_ms": dom[2] / dom[1]},
+        "kernels": [{"name": k[0], "launches": k[1], "ms_per_step": k[2] / args.steps,
+                     "rate": (k[3] / (k[2] * 1e-3) / 1e12) if k[2] > 0 else None,
+                     "rate_unit": "TFLOP/s" if "gemm_" in k[0] else "TB/s"} for k in kernels],
+    }
+    if inp is not None and not args.no_cpu_baseline:
+        from oracle import cp_oracle
+        cp_oracle.build()
+        cores = cp_oracle.num_threads()
+        sel = synth.position_subset(cfg.T, args.cpu_positions or max(1, cores // 2))
+        t0 = time.time()
+        cp_oracle.full_loss_fwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel])
+        cp_oracle.full_loss_bwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel], np.ones(len(sel)))
+        dtc = time.time() - t0
+        out["cpu_baseline"] = {"value": len(sel) / dtc, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                               "sample": f"{len(sel)} seeded positions of the workload at full d, V, n, r; fp64 forward "
+                                         f"+ backward with all gradients; {dtc:.1f} s wall"}
+    return out
 
 
 def bench_loss(args):
@@ -255,6 +348,8 @@ def main():
         sys.exit(2)
     if args.workload in ("draft", "draft_sequential", "first_token"):
         out = bench_draft(args, args.workload)
+    elif args.workload in ("full_heads", "full_heads_7b"):
+        out = bench_full(args)
     else:
         out = bench_loss(args)
     print(json.dumps(out))
