@@ -230,6 +230,30 @@ def bench_loss(args):
                      "rate": (k[3] / (k[2] * 1e-3) / 1e12) if k[2] > 0 else None,
                      "rate_unit": "TFLOP/s" if k[0].startswith("gemm_") else "TB/s"} for k in kernels],
     }
+    # the same workload in the two other modes the method is used in: forward only (evaluation), and
+    # backward with the shared unembedding frozen (head-only fine tuning: no dU product)
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps
+
+    fwd_flops = 2.0 * cfg.n * cfg.r * cfg.d * (cfg.d + cfg.V) * cfg.T
+    t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
+    out["forward_only"] = {"ms_per_step": t_fwd * 1e3, "tokens_per_s": cfg.T / t_fwd,
+                           "model_tflops": fwd_flops / t_fwd / 1e12}
+    if not args.frozen_u:
+        def frozen_step():
+            binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
+            binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, None, dG, ws, stream)
+        t_fr = timed(frozen_step)
+        fr_flops = 2.0 * cfg.n * cfg.r * cfg.d * (3 * cfg.d + 2 * cfg.V) * cfg.T
+        out["frozen_u"] = {"ms_per_step": t_fr * 1e3, "tokens_per_s": cfg.T / t_fr,
+                           "model_tflops": fr_flops / t_fr / 1e12,
+                           "model_flop_frac_of_bf16_peak": fr_flops / t_fr / 1e12 / PEAK_BF16_TFLOPS}
     del ws, ctx, dW, dH, dU, H, h
     torch.cuda.empty_cache()
     if not args.no_draft:
