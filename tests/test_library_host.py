@@ -102,3 +102,44 @@ def test_null_and_small_workspace_rejected_before_launch(lib):
     assert lib.cp_head_draft_sample(*argsd) == -1
     argsd[6] = p; argsd[10] = 0
     assert lib.cp_head_draft_sample(*argsd) == -3
+
+
+def test_new_calls_reject_bad_arguments_before_launch(lib):
+    p = 0x10000
+    bf = binding.make_desc(4, 64, 300, 2, 2, binding.BF16)
+    fp = binding.make_desc(4, 8, 16, 2, 2, binding.FP32)
+    # first-token marginal: both paths are served; null input, short workspace
+    for ds in (bf, fp):
+        need = binding.cp_head_workspace_bytes(ds, binding.OP_FIRST_TOKEN)
+        assert need > 4 * 2 * ds.V * 4                       # it holds the r rows of logits per row of the batch
+        args = [ctypes.byref(ds), p, p, p, p, p, p, need, None]
+        bad = list(args); bad[5] = None
+        assert lib.cp_head_first_token_logprob(*bad) == -1
+        bad = list(args); bad[7] = need - 1
+        assert lib.cp_head_first_token_logprob(*bad) == -3
+    # sequential sampler and full heads: matrix-core path only
+    args = [ctypes.byref(fp), p, p, p, p, p, p, p, p, 1 << 20, None]
+    assert lib.cp_head_draft_sample_sequential(*args) == -2
+    args[0] = ctypes.byref(bf); args[9] = 0
+    assert lib.cp_head_draft_sample_sequential(*args) == -3
+    args[5] = None                                           # uniforms
+    assert lib.cp_head_draft_sample_sequential(*args) == -1
+    out = ctypes.c_size_t()
+    assert lib.cp_head_full_ctx_bytes(ctypes.byref(bf), ctypes.byref(out)) == 0 and out.value >= 4 * 2 * 2 * 4
+    argsf = [ctypes.byref(fp), p, p, p, p, p, p, p, 1 << 20, None]
+    assert lib.cp_head_full_loss_fwd(*argsf) == -2
+    argsf[0] = ctypes.byref(bf); argsf[8] = 0
+    assert lib.cp_head_full_loss_fwd(*argsf) == -3
+    argsb = [ctypes.byref(bf), p, p, p, p, None, 1.0, p, None, p, p, p, 1 << 30, None]
+    assert lib.cp_head_full_loss_bwd(*argsb) == -1           # dH is required
+    # balancing statistic: outputs required
+    assert lib.cp_head_aux_balance(ctypes.byref(bf), p, p, None, p, p, 256, None) == -1
+
+
+def test_full_head_workspace_is_bounded_in_positions(lib):
+    a = binding.make_desc(1 << 16, 4096, 32000, 4, 8, binding.BF16)
+    b = binding.make_desc(1 << 17, 4096, 32000, 4, 8, binding.BF16)
+    wa = binding.cp_head_workspace_bytes(a, binding.OP_FULL_LOSS_BWD)
+    wb = binding.cp_head_workspace_bytes(b, binding.OP_FULL_LOSS_BWD)
+    # doubling T adds per-position bookkeeping only (row info, transposed H), never logit-sized rows
+    assert (wb - wa) / (1 << 16) < 4 * 8 * 16 + 4096 * 2 + 8 * 4 + 4096
