@@ -767,5 +767,258 @@ int CPO(full_loss_bwd)(const cpo_shape *sh, const in_t *H, const in_t *F, const 
     return fail ? -1 : 0;
 }
 
+/* ------------------------------------------------------------------------- */
+/* head-only fine-tuning loss ("Fine tuning", eq. 14 and the sum after it)    */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * The paper leaves open what the k-th token's distribution p^d is conditioned on, the direction of the
+ * KL term and the discount.  Reading taken here:
+ *   p^d_k[v] = P(x_k = v | x_<k) = sum_a qhat^(k)_a P^(k)(v | a),  qhat^(k) = softmax_a(log w_a + sum_{j<k} C_ja)
+ *              (the conditional of eq. 13 under the true prefix x_<k);
+ *   p^c_k    = softmax(TZ[t,k,:]), the distribution of the original head, supplied by the caller;
+ *   L_k      = beta * KL(p^c_k || p^d_k) + (1 - beta) * (-log p^d_k[x_k])
+ *              (arguments read as (prediction, target) in both terms of eq. 14);
+ *   loss[t]  = sum_{k=1..n} disc^(k-1) L_k.
+ * With beta = 0 and disc = 1 the chain of conditionals multiplies to the joint, so the loss is that of
+ * loss_fwd.  A negative target drops token k's term; its factor then leaves the expert weights unchanged.
+ *
+ * TZ[T,n,V] teacher logits.  loss[T]; optional kl[T,n], ce[T,n] (zero for dropped tokens).
+ */
+int CPO(distill_loss_fwd)(const cpo_shape *sh, const in_t *H, const in_t *W, const in_t *U, const in_t *G,
+                          const int32_t *X, const in_t *TZ, double beta, double disc,
+                          double *loss, double *kl_out, double *ce_out)
+{
+    const int d = sh->d, V = sh->V, n = sh->n, r = sh->r;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *y = malloc(sizeof(double) * d), *lp = malloc(sizeof(double) * (size_t)r * V);
+        double *lpc = malloc(sizeof(double) * V), *q = malloc(sizeof(double) * r);
+        if (!y || !lp || !lpc || !q) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t t = 0; t < sh->T; ++t) {
+                const in_t *h = H + (size_t)t * d;
+                gate_logw(sh, h, G, q);
+                double total = 0.0, weight = 1.0;
+                for (int k = 0; k < n; ++k, weight *= disc) {
+                    const int32_t x = X[(size_t)t * n + k];
+                    double kl = 0.0, ce = 0.0;
+                    if (x >= 0) {
+                        for (int al = 0; al < r; ++al) {
+                            double *za = lp + (size_t)al * V;
+                            head_y(sh, h, W, k, al, y);
+                            head_z(sh, U, y, za);
+                            double l = logsumexp(za, V);
+                            for (int v = 0; v < V; ++v) za[v] -= l;                  /* log P^(k)(v | al) */
+                        }
+                        const in_t *tz = TZ + ((size_t)t * n + k) * V;
+                        for (int v = 0; v < V; ++v) lpc[v] = (double)tz[v];
+                        double lt = logsumexp(lpc, V);
+                        for (int v = 0; v < V; ++v) lpc[v] -= lt;                    /* log p^c_k[v] */
+                        double qn = logsumexp(q, r);
+                        for (int v = 0; v < V; ++v) {
+                            double m = 0.0;
+                            for (int al = 0; al < r; ++al) m += exp(q[al] - qn + lp[(size_t)al * V + v]);
+                            kl += exp(lpc[v]) * (lpc[v] - log(m));
+                            if (v == x) ce = -log(m);
+                        }
+                        total += weight * (beta * kl + (1.0 - beta) * ce);
+                        for (int al = 0; al < r; ++al) q[al] += lp[(size_t)al * V + x];
+                    }
+                    if (kl_out) kl_out[(size_t)t * n + k] = kl;
+                    if (ce_out) ce_out[(size_t)t * n + k] = ce;
+                }
+                loss[t] = total;
+            }
+        }
+        free(y); free(lp); free(lpc); free(q);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Gradients of sum_t dloss[t] * loss[t] for distill_loss_fwd (the teacher logits are constants).
+ * With g_k = disc^(k-1) (zero for a dropped token), rho_a[v] = qhat_a P_a[v] / p^d[v] (expert posterior
+ * given token v), S_a = sum_v p^c[v] rho_a[v] and R_a = beta S_a + (1 - beta) rho_a[x_k], all for token k:
+ *   dL/dq^(k)_a = g_k (qhat_a - R_a)                 q^(k)_a = log w_a + sum_{j<k} C_ja
+ *   dL/dz_ka[v] = g_k ( R_a P_a[v] - beta p^c[v] rho_a[v] - (1 - beta) rho_a[x_k] 1[v = x_k] )
+ *                 + D_ka (1[v = x_k] - P_a[v]),      D_ka = sum_{k' > k} dL/dq^(k')_a   (through C_ka)
+ *   dL/dg_a     = sum_k dL/dq^(k)_a                  (these sum to zero over a, so the log-softmax of the
+ *                                                     gate passes them through unchanged)
+ * and below z, g everything is linear as in loss_bwd.  dH, dW, dU, dG overwritten; any may be NULL.
+ */
+int CPO(distill_loss_bwd)(const cpo_shape *sh, const in_t *H, const in_t *W, const in_t *U, const in_t *G,
+                          const int32_t *X, const in_t *TZ, double beta, double disc, const double *dloss,
+                          double *dH, double *dW, double *dU, double *dG)
+{
+    if (sh->round_y) return -1;
+    const int d = sh->d, V = sh->V, n = sh->n, r = sh->r;
+    const int64_t T = sh->T;
+    const size_t nr = (size_t)n * r;
+    double *dz_all = malloc(sizeof(double) * ((size_t)T * nr * V + 1));
+    double *y_all = malloc(sizeof(double) * ((size_t)T * nr * d + 1));
+    double *dy_all = malloc(sizeof(double) * ((size_t)T * nr * d + 1));
+    double *dg_all = malloc(sizeof(double) * ((size_t)T * r + 1));
+    if (!dz_all || !y_all || !dy_all || !dg_all) { free(dz_all); free(y_all); free(dy_all); free(dg_all); return -1; }
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *lpc = malloc(sizeof(double) * V), *q = malloc(sizeof(double) * r), *qh = malloc(sizeof(double) * r);
+        double *m = malloc(sizeof(double) * V);
+        double *dq = malloc(sizeof(double) * nr);      /* dL/dq^(k)_a */
+        double *Rk = malloc(sizeof(double) * nr), *rhox = malloc(sizeof(double) * nr);
+        if (!lpc || !q || !qh || !m || !dq || !Rk || !rhox) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t t = 0; t < T; ++t) {
+                const in_t *h = H + (size_t)t * d;
+                const double up = dloss ? dloss[t] : 1.0;
+                gate_logw(sh, h, G, q);
+                double weight = 1.0;
+                /* forward sweep over the tokens: dz_all holds log P, then the first part of dz */
+                for (int k = 0; k < n; ++k, weight *= disc) {
+                    const int32_t x = X[(size_t)t * n + k];
+                    for (int al = 0; al < r; ++al) {
+                        size_t row = ((size_t)t * n + k) * r + al;
+                        double *y = y_all + row * d, *lp = dz_all + row * V;
+                        head_y(sh, h, W, k, al, y);
+                        head_z(sh, U, y, lp);
+                        double l = logsumexp(lp, V);
+                        for (int v = 0; v < V; ++v) lp[v] -= l;
+                    }
+                    if (x < 0) {
+                        for (int al = 0; al < r; ++al) {
+                            dq[(size_t)k * r + al] = 0.0; Rk[(size_t)k * r + al] = 0.0; rhox[(size_t)k * r + al] = 0.0;
+                            double *lp = dz_all + (((size_t)t * n + k) * r + al) * V;
+                            for (int v = 0; v < V; ++v) lp[v] = 0.0;                 /* dropped: no gradient */
+                        }
+                        continue;
+                    }
+                    const in_t *tz = TZ + ((size_t)t * n + k) * V;
+                    for (int v = 0; v < V; ++v) lpc[v] = (double)tz[v];
+                    double lt = logsumexp(lpc, V);
+                    for (int v = 0; v < V; ++v) lpc[v] -= lt;
+                    double qn = logsumexp(q, r);
+                    for (int al = 0; al < r; ++al) qh[al] = exp(q[al] - qn);
+                    for (int v = 0; v < V; ++v) {
+                        double acc = 0.0;
+                        for (int al = 0; al < r; ++al)
+                            acc += qh[al] * exp(dz_all[(((size_t)t * n + k) * r + al) * V + v]);
+                        m[v] = acc;                                                  /* p^d_k[v] */
+                    }
+                    for (int al = 0; al < r; ++al) {
+                        double *lp = dz_all + (((size_t)t * n + k) * r + al) * V;
+                        double S = 0.0;
+                        for (int v = 0; v < V; ++v) S += exp(lpc[v]) * qh[al] * exp(lp[v]) / m[v];
+                        double rx = qh[al] * exp(lp[x]) / m[x];
+                        double R = beta * S + (1.0 - beta) * rx;
+                        Rk[(size_t)k * r + al] = R;
+                        rhox[(size_t)k * r + al] = rx;
+                        dq[(size_t)k * r + al] = weight * (qh[al] - R);
+                        q[al] += lp[x];                                              /* C_ka enters later tokens */
+                        /* first part of dz, g_k ( R P - beta p^c rho - (1-beta) rho[x] 1[v=x] ), replaces log P in the slot */
+                        for (int v = 0; v < V; ++v) {
+                            double P = exp(lp[v]);
+                            double rho = qh[al] * P / m[v];
+                            double val = weight * (R * P - beta * exp(lpc[v]) * rho);
+                            if (v == x) val -= weight * (1.0 - beta) * rx;
+                            lp[v] = val;
+                        }
+                    }
+                }
+                /* second part: D_ka (1[v = x_k] - P_ka[v]), known once every later token has been seen;
+                 * P is formed again from y (the slot no longer holds log P) */
+                for (int k = 0; k < n; ++k) {
+                    const int32_t x = X[(size_t)t * n + k];
+                    if (x < 0) continue;
+                    for (int al = 0; al < r; ++al) {
+                        double D = 0.0;
+                        for (int k2 = k + 1; k2 < n; ++k2) D += dq[(size_t)k2 * r + al];
+                        size_t row = ((size_t)t * n + k) * r + al;
+                        double *dz = dz_all + row * V;
+                        head_z(sh, U, y_all + row * d, m);                           /* m is free by now: z_ka */
+                        double l = logsumexp(m, V);
+                        for (int v = 0; v < V; ++v) dz[v] -= D * exp(m[v] - l);
+                        dz[x] += D;
+                    }
+                }
+                for (int al = 0; al < r; ++al) {
+                    double acc = 0.0;
+                    for (int k = 0; k < n; ++k) acc += dq[(size_t)k * r + al];
+                    dg_all[(size_t)t * r + al] = up * acc;
+                }
+                for (int k = 0; k < n; ++k)
+                    for (int al = 0; al < r; ++al) {
+                        size_t row = ((size_t)t * n + k) * r + al;
+                        double *dz = dz_all + row * V, *dy = dy_all + row * d;
+                        for (int v = 0; v < V; ++v) dz[v] *= up;
+                        for (int j = 0; j < d; ++j) {
+                            double acc = 0.0;
+                            for (int v = 0; v < V; ++v) acc += (double)U[(size_t)v * d + j] * dz[v];
+                            dy[j] = acc;
+                        }
+                    }
+                if (dH) {
+                    double *dh = dH + (size_t)t * d;
+                    for (int j = 0; j < d; ++j) {
+                        double acc = 0.0;
+                        for (size_t sa = 0; sa < nr; ++sa) {
+                            const in_t *Wsa = W + sa * d * d;
+                            const double *dy = dy_all + ((size_t)t * nr + sa) * d;
+                            for (int kk = 0; kk < d; ++kk) acc += (double)Wsa[(size_t)kk * d + j] * dy[kk];
+                        }
+                        for (int al = 0; al < r; ++al)
+                            acc += (double)G[(size_t)al * d + j] * dg_all[(size_t)t * r + al];
+                        dh[j] = acc;
+                    }
+                }
+            }
+        }
+        free(lpc); free(q); free(qh); free(m); free(dq); free(Rk); free(rhox);
+    }
+    if (!fail && dW) {
+#pragma omp parallel for schedule(static)
+        for (int64_t sak = 0; sak < (int64_t)nr * d; ++sak) {
+            size_t sa = (size_t)sak / d;
+            int kk = (int)(sak % d);
+            double *out = dW + (size_t)sak * d;
+            for (int j = 0; j < d; ++j) out[j] = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double dyk = dy_all[((size_t)t * nr + sa) * d + kk];
+                const in_t *h = H + (size_t)t * d;
+                for (int j = 0; j < d; ++j) out[j] += dyk * (double)h[j];
+            }
+        }
+    }
+    if (!fail && dU) {
+#pragma omp parallel for schedule(static)
+        for (int v = 0; v < V; ++v) {
+            double *out = dU + (size_t)v * d;
+            for (int j = 0; j < d; ++j) out[j] = 0.0;
+            for (size_t row = 0; row < (size_t)T * nr; ++row) {
+                double dzv = dz_all[row * V + v];
+                const double *y = y_all + row * d;
+                for (int j = 0; j < d; ++j) out[j] += dzv * y[j];
+            }
+        }
+    }
+    if (!fail && dG) {
+        for (int al = 0; al < r; ++al)
+            for (int j = 0; j < d; ++j) {
+                double acc = 0.0;
+                for (int64_t t = 0; t < T; ++t) acc += dg_all[(size_t)t * r + al] * (double)H[(size_t)t * d + j];
+                dG[(size_t)al * d + j] = acc;
+            }
+    }
+    free(dz_all); free(y_all); free(dy_all); free(dg_all);
+    return fail ? -1 : 0;
+}
+
 /* For tests of the rounding helper. */
 double CPO(round_to_bf16)(double v) { return round_to_bf16(v); }

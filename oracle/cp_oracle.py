@@ -277,6 +277,58 @@ def full_loss_bwd(H, F, G, X, dloss=None, want=("dH", "dF", "dG")):
     return {k: v for k, v in out.items() if v is not None}
 
 
+def _teacher(TZ, kind, sh):
+    TZ = np.ascontiguousarray(TZ, dtype=np.float32 if kind == "f32" else np.float64)
+    assert TZ.shape == (sh.T, sh.n, sh.V), TZ.shape
+    return TZ
+
+
+def distill_loss_fwd(H, W, U, G, X, TZ, beta: float = 0.9, disc: float = 1.0, details: bool = False):
+    """Head-only fine-tuning loss (eq. 14 and the discounted sum after it) against teacher logits TZ[T,n,V]:
+    loss[T] (and kl[T,n], ce[T,n] with details)."""
+    kinds = {np.asarray(a).dtype for a in (H, W, U, G, TZ)}
+    if kinds != {np.dtype(np.float32)}:
+        H, W, U, G = (np.asarray(a, dtype=np.float64) for a in (H, W, U, G))
+    kind, (H, W, U, G) = _prep(H, W, U, G)
+    sh = _shape(H, W, U, False)
+    X = np.ascontiguousarray(X, dtype=np.int32)
+    TZ = _teacher(TZ, kind, sh)
+    loss = np.empty(sh.T)
+    kl = np.empty((sh.T, sh.n)) if details else None
+    ce = np.empty((sh.T, sh.n)) if details else None
+    fn = getattr(_lib(kind), f"cpo_{kind}_distill_loss_fwd")
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_double, ctypes.c_double] + [ctypes.c_void_p] * 3
+    rc = fn(ctypes.cast(ctypes.byref(sh), ctypes.c_void_p), _p(H), _p(W), _p(U), _p(G), _p(X), _p(TZ),
+            float(beta), float(disc), _p(loss), _p(kl), _p(ce))
+    if rc != 0:
+        raise RuntimeError("oracle distill_loss_fwd failed")
+    return (loss, kl, ce) if details else loss
+
+
+def distill_loss_bwd(H, W, U, G, X, TZ, beta: float = 0.9, disc: float = 1.0, dloss=None,
+                     want=("dH", "dW", "dU", "dG")):
+    """Gradients of sum_t dloss[t] * distill_loss[t] (teacher logits are constants)."""
+    kinds = {np.asarray(a).dtype for a in (H, W, U, G, TZ)}
+    if kinds != {np.dtype(np.float32)}:
+        H, W, U, G = (np.asarray(a, dtype=np.float64) for a in (H, W, U, G))
+    kind, (H, W, U, G) = _prep(H, W, U, G)
+    sh = _shape(H, W, U, False)
+    X = np.ascontiguousarray(X, dtype=np.int32)
+    TZ = _teacher(TZ, kind, sh)
+    dl = None if dloss is None else np.ascontiguousarray(dloss, dtype=np.float64)
+    out = {"dH": np.empty(H.shape) if "dH" in want else None, "dW": np.empty(W.shape) if "dW" in want else None,
+           "dU": np.empty(U.shape) if "dU" in want else None, "dG": np.empty(G.shape) if "dG" in want else None}
+    fn = getattr(_lib(kind), f"cpo_{kind}_distill_loss_bwd")
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_double, ctypes.c_double] + [ctypes.c_void_p] * 5
+    rc = fn(ctypes.cast(ctypes.byref(sh), ctypes.c_void_p), _p(H), _p(W), _p(U), _p(G), _p(X), _p(TZ),
+            float(beta), float(disc), _p(dl), _p(out["dH"]), _p(out["dW"]), _p(out["dU"]), _p(out["dG"]))
+    if rc != 0:
+        raise RuntimeError("oracle distill_loss_bwd failed")
+    return {k: v for k, v in out.items() if v is not None}
+
+
 def round_to_bf16(v: float) -> float:
     fn = _lib("f64").cpo_f64_round_to_bf16
     fn.restype = ctypes.c_double

@@ -503,3 +503,101 @@ def test_full_heads_invariants(oracle):
     assert np.abs(g["dF"][1]).max() == 0.0
     np.testing.assert_allclose(g["dF"][0].sum(axis=1), 0.0, atol=1e-13)      # sum_v dz_v = 0
     np.testing.assert_allclose(g["dG"].sum(axis=0), 0.0, atol=1e-13)         # sum_a dg_a = 0
+
+
+# ---------------------------------------------------------------------------
+# head-only fine-tuning loss ("Fine tuning", eq. 14): beta * KL + (1 - beta) * CE per token, discounted
+# ---------------------------------------------------------------------------
+
+def distill_problem(T=4, d=6, V=7, n=3, r=3, seed=21):
+    H, W, U, G, X = small_problem(T=T, d=d, V=V, n=n, r=r, seed=seed)
+    TZ = np.random.default_rng(seed + 1).standard_normal((T, n, V)) * 1.5
+    return H, W, U, G, X, TZ
+
+
+def test_distill_without_teacher_term_is_the_joint_likelihood(oracle):
+    # beta = 0, no discount: the per-token cross-entropies are the chain of conditionals of the joint
+    H, W, U, G, X, TZ = distill_problem()
+    np.testing.assert_allclose(oracle.distill_loss_fwd(H, W, U, G, X, TZ, beta=0.0, disc=1.0),
+                               oracle.loss_fwd(H, W, U, G, X), rtol=1e-12)
+    dl = np.random.default_rng(5).standard_normal(H.shape[0])
+    gd = oracle.distill_loss_bwd(H, W, U, G, X, TZ, beta=0.0, disc=1.0, dloss=dl)
+    gr = oracle.loss_bwd(H, W, U, G, X, dl)
+    for k in gr:
+        np.testing.assert_allclose(gd[k], gr[k], rtol=1e-9, atol=1e-12, err_msg=k)
+
+
+def test_distill_terms_against_library_routines(oracle):
+    # each token's terms from the pinned conditional P(x_k | x_<k) and scipy's relative entropy
+    H, W, U, G, X, TZ = distill_problem()
+    beta, disc = 0.9, 0.7
+    loss, kl, ce = oracle.distill_loss_fwd(H, W, U, G, X, TZ, beta=beta, disc=disc, details=True)
+    for t in range(H.shape[0]):
+        tot = 0.0
+        for k in range(X.shape[1]):
+            cond = oracle.sequential_conditional(H, W, U, G, t, list(X[t, :k]))
+            pc = sps.softmax(TZ[t, k])
+            np.testing.assert_allclose(kl[t, k], sps.rel_entr(pc, cond).sum(), rtol=1e-10)
+            np.testing.assert_allclose(ce[t, k], -np.log(cond[X[t, k]]), rtol=1e-10)
+            tot += disc ** k * (beta * kl[t, k] + (1 - beta) * ce[t, k])
+        np.testing.assert_allclose(loss[t], tot, rtol=1e-12)
+    assert (kl >= -1e-14).all()                                  # Gibbs
+
+
+def test_distill_teacher_equal_to_student_has_zero_divergence(oracle):
+    H, W, U, G, X, TZ = distill_problem(T=2)
+    for t in range(2):
+        for k in range(X.shape[1]):
+            TZ[t, k] = np.log(oracle.sequential_conditional(H, W, U, G, t, list(X[t, :k]))) + 3.0   # any shift
+    _, kl, _ = oracle.distill_loss_fwd(H, W, U, G, X, TZ, details=True)
+    assert np.abs(kl).max() < 1e-13
+    # ... and there the divergence is stationary: the gradient is that of the cross-entropy part alone
+    g1 = oracle.distill_loss_bwd(H, W, U, G, X, TZ, beta=0.9, disc=1.0)
+    g0 = oracle.distill_loss_bwd(H, W, U, G, X, TZ, beta=0.0, disc=1.0)
+    for k in g0:
+        np.testing.assert_allclose(g1[k], 0.1 * g0[k], rtol=1e-8, atol=1e-12, err_msg=k)
+
+
+def test_distill_rank_one_single_token_is_textbook_distillation(oracle):
+    H, W, U, G, X, TZ = distill_problem(n=1, r=1)
+    beta = 0.6
+    ref = []
+    for t in range(H.shape[0]):
+        logp = sps.log_softmax(U @ (W[0, 0] @ H[t]))
+        pc = sps.softmax(TZ[t, 0])
+        ref.append(beta * sps.rel_entr(pc, np.exp(logp)).sum() - (1 - beta) * logp[X[t, 0]])
+    np.testing.assert_allclose(oracle.distill_loss_fwd(H, W, U, G, X, TZ, beta=beta), ref, rtol=1e-12)
+
+
+@pytest.mark.parametrize("which", ["H", "W", "U", "G"])
+def test_distill_gradients_match_central_differences(oracle, which):
+    H, W, U, G, X, TZ = distill_problem()
+    X[1, 1] = -1                                                 # a dropped token in the middle of a row
+    beta, disc = 0.9, 0.8
+    dl = np.random.default_rng(8).standard_normal(H.shape[0])
+    grads = oracle.distill_loss_bwd(H, W, U, G, X, TZ, beta=beta, disc=disc, dloss=dl)
+    args = {"H": H, "W": W, "U": U, "G": G}
+    rng = np.random.default_rng(9)
+    eps = 1e-6
+    for _ in range(14):
+        idx = tuple(rng.integers(0, s) for s in args[which].shape)
+        vals = []
+        for sign in (+1, -1):
+            pert = {k: v.copy() for k, v in args.items()}
+            pert[which][idx] += sign * eps
+            vals.append(float(dl @ oracle.distill_loss_fwd(pert["H"], pert["W"], pert["U"], pert["G"], X, TZ,
+                                                           beta=beta, disc=disc)))
+        fd = (vals[0] - vals[1]) / (2 * eps)
+        np.testing.assert_allclose(grads["d" + which][idx], fd, rtol=5e-6, atol=5e-9)
+
+
+def test_distill_dropped_token(oracle):
+    H, W, U, G, X, TZ = distill_problem()
+    X[:, 2] = -1
+    loss, kl, ce = oracle.distill_loss_fwd(H, W, U, G, X, TZ, details=True)
+    assert np.abs(kl[:, 2]).max() == 0.0 and np.abs(ce[:, 2]).max() == 0.0
+    g = oracle.distill_loss_bwd(H, W, U, G, X, TZ)
+    assert np.abs(g["dW"][2]).max() == 0.0                        # the third head never enters
+    # same as a two-token head
+    np.testing.assert_allclose(loss, oracle.distill_loss_fwd(H, W[:2].copy(), U, G, X[:, :2].copy(), TZ[:, :2].copy()),
+                               rtol=1e-12)
