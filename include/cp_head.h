@@ -69,7 +69,8 @@ enum {
 enum {
     CP_HEAD_OP_LOSS_FWD = 0, CP_HEAD_OP_LOSS_BWD = 1, CP_HEAD_OP_DRAFT = 2,
     CP_HEAD_OP_FIRST_TOKEN = 3, CP_HEAD_OP_DRAFT_SEQUENTIAL = 4, CP_HEAD_OP_AUX_BALANCE = 5,
-    CP_HEAD_OP_FULL_LOSS_FWD = 6, CP_HEAD_OP_FULL_LOSS_BWD = 7
+    CP_HEAD_OP_FULL_LOSS_FWD = 6, CP_HEAD_OP_FULL_LOSS_BWD = 7,
+    CP_HEAD_OP_DISTILL_FWD = 8, CP_HEAD_OP_DISTILL_BWD = 9
 };
 
 typedef struct cp_head_desc {
@@ -216,6 +217,38 @@ int cp_head_full_loss_bwd(const cp_head_desc *desc,
                           const void *ctx,
                           float *dH, float *dF, float *dG,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Head-only fine-tuning loss (section "Fine tuning", eq. 14 and the discounted sum after it) for the
+ * shared-unembedding heads, against the logits of the original head.  The paper leaves open what the
+ * k-th token's distribution is conditioned on, the direction of the KL term and the discount; the
+ * reading implemented is
+ *     p^d_k[v] = P(x_k = v | x_<k) = sum_a qhat^(k)_a P^(k)(v | a)    (eq. 13 under the true prefix X[t, <k])
+ *     p^c_k    = softmax(TZ[t, k, :])                                 (TZ[T,n,V]: teacher logits, storage type)
+ *     L_k      = beta * KL(p^c_k || p^d_k) - (1 - beta) * log p^d_k[X[t,k]]
+ *     loss[t]  = sum_{k=0..n-1} discount^k L_k
+ * (the paper sets beta = 0.9; with beta = 0 and discount = 1 the loss equals cp_head_loss_fwd's).
+ * A negative target drops token k's term and leaves the expert weights of later tokens unchanged.
+ * cp_head_distill_ctx_bytes sizes the `ctx` shared by the two calls; workspaces are sized by
+ * cp_head_workspace_bytes with CP_HEAD_OP_DISTILL_FWD / _BWD.  Backward: gradients of
+ * sum_t dloss[t] * loss[t] with TZ constant; dloss/scale and the outputs as in cp_head_loss_bwd
+ * (dU = NULL for the frozen unembedding of fine tuning).  No logits are stored: the mixture over the
+ * experts is formed inside the tiles of two further vocabulary-sized products.
+ * Served for bf16 storage, d a multiple of 64 and r in {1, 2, 4, 8}; otherwise CP_HEAD_ERR_UNSUPPORTED.
+ */
+int cp_head_distill_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
+int cp_head_distill_loss_fwd(const cp_head_desc *desc,
+                             const void *H, const void *W, const void *U, const void *G,
+                             const int32_t *X, const void *TZ, float beta, float discount,
+                             float *loss,
+                             void *ctx, void *workspace, size_t workspace_bytes, void *stream);
+int cp_head_distill_loss_bwd(const cp_head_desc *desc,
+                             const void *H, const void *W, const void *U, const void *G,
+                             const int32_t *X, const void *TZ,
+                             const float *dloss, float scale,
+                             const void *ctx,
+                             float *dH, float *dW, float *dU, float *dG,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Optional per-kernel timing for benchmarks (not part of the method).  While

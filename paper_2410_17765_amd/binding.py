@@ -18,6 +18,7 @@ MIN_WORKSPACE = 2
 OP_LOSS_FWD, OP_LOSS_BWD, OP_DRAFT = 0, 1, 2
 OP_FIRST_TOKEN, OP_DRAFT_SEQUENTIAL, OP_AUX_BALANCE = 3, 4, 5
 OP_FULL_LOSS_FWD, OP_FULL_LOSS_BWD = 6, 7
+OP_DISTILL_FWD, OP_DISTILL_BWD = 8, 9
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcphead.so")
@@ -27,6 +28,7 @@ EXPORTS = ("cp_head_strerror", "cp_head_ctx_bytes", "cp_head_workspace_bytes",
            "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample",
            "cp_head_first_token_logprob", "cp_head_draft_sample_sequential", "cp_head_aux_balance",
            "cp_head_full_ctx_bytes", "cp_head_full_loss_fwd", "cp_head_full_loss_bwd",
+           "cp_head_distill_ctx_bytes", "cp_head_distill_loss_fwd", "cp_head_distill_loss_bwd",
            "cp_head_profile_enable", "cp_head_profile_read")
 
 
@@ -70,6 +72,11 @@ def lib() -> ctypes.CDLL:
         L.cp_head_full_loss_fwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_full_loss_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, ctypes.c_float, vp,
                                             vp, vp, vp, vp, sz, vp]
+        L.cp_head_distill_ctx_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(sz)]
+        L.cp_head_distill_loss_fwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, ctypes.c_float,
+                                               ctypes.c_float, vp, vp, vp, sz, vp]
+        L.cp_head_distill_loss_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp,
+                                               vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_profile_enable.argtypes = [ctypes.c_int]
         L.cp_head_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         for name in EXPORTS[1:]:
@@ -190,6 +197,31 @@ def cp_head_full_loss_bwd(desc: Desc, H, F, G, X, dloss, scale, ctx, dH, dF, dG,
                                      _ptr(workspace), _nbytes(workspace), _stream(stream))
     if rc != 0:
         raise CpHeadError(rc, "cp_head_full_loss_bwd")
+
+
+def cp_head_distill_ctx_bytes(desc: Desc) -> int:
+    out = ctypes.c_size_t(0)
+    rc = lib().cp_head_distill_ctx_bytes(ctypes.byref(desc), ctypes.byref(out))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_distill_ctx_bytes")
+    return out.value
+
+
+def cp_head_distill_loss_fwd(desc: Desc, H, W, U, G, X, TZ, beta, discount, loss, ctx, workspace, stream=None) -> None:
+    rc = lib().cp_head_distill_loss_fwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(X), _ptr(TZ),
+                                        ctypes.c_float(beta), ctypes.c_float(discount), _ptr(loss), _ptr(ctx),
+                                        _ptr(workspace), _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_distill_loss_fwd")
+
+
+def cp_head_distill_loss_bwd(desc: Desc, H, W, U, G, X, TZ, dloss, scale, ctx, dH, dW, dU, dG, workspace,
+                             stream=None) -> None:
+    rc = lib().cp_head_distill_loss_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(X), _ptr(TZ),
+                                        _ptr(dloss), ctypes.c_float(scale), _ptr(ctx), _ptr(dH), _ptr(dW), _ptr(dU),
+                                        _ptr(dG), _ptr(workspace), _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_distill_loss_bwd")
 
 
 def cp_head_profile_enable(on: bool) -> None:

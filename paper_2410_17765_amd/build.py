@@ -12,7 +12,7 @@ _INCLUDE = os.path.join(os.path.dirname(_PKG), "include")
 _OBJ = os.path.join(_CSRC, "_build")
 LIB_PATH = os.path.join(_PKG, "libcphead.so")
 
-SOURCES = ["api.hip", "generic.hip", "fast.hip"]
+SOURCES = ["api.hip", "generic.hip", "fast.hip", "distill.hip"]
 
 # packed-fp32 code generation is switched off on purpose: some forms of those instructions have been seen to
 # give wrong results on this hardware generation, so the compiler is told not to emit them

@@ -62,6 +62,8 @@ size_t workspace_need(const cp_head_desc &ds, int op)
     if (op == CP_HEAD_OP_AUX_BALANCE) return 256;   // none needed; a token size keeps the calling pattern uniform
     if (op == CP_HEAD_OP_FULL_LOSS_FWD || op == CP_HEAD_OP_FULL_LOSS_BWD)   // not served on the plain path
         return use_fast_path(ds) ? fast_workspace_bytes(ds, op) : 256;
+    if (op == CP_HEAD_OP_DISTILL_FWD || op == CP_HEAD_OP_DISTILL_BWD)
+        return distill_supported(ds) ? distill_workspace_bytes(ds, op) : 256;
     if (use_fast_path(ds)) return fast_workspace_bytes(ds, op);
     if (op == CP_HEAD_OP_FIRST_TOKEN) return generic_first_token_workspace_bytes(ds);
     if (op == CP_HEAD_OP_DRAFT_SEQUENTIAL) return 256;   // not served on the plain path
@@ -133,7 +135,7 @@ int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes)
     if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
     const int rc = check_desc(desc);
     if (rc != CP_HEAD_OK) return rc;
-    if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_FULL_LOSS_BWD) return CP_HEAD_ERR_INVALID_ARG;
+    if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_DISTILL_BWD) return CP_HEAD_ERR_INVALID_ARG;
     *bytes = workspace_need(*desc, op);
     return CP_HEAD_OK;
 }
@@ -267,6 +269,48 @@ int cp_head_full_loss_bwd(const cp_head_desc *desc, const void *H, const void *F
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_FULL_LOSS_BWD)) return CP_HEAD_ERR_WORKSPACE;
     return fast_full_loss_bwd(*desc, H, F, G, X, dloss, scale, ctx, dH, dF, dG, workspace,
                               static_cast<hipStream_t>(stream));
+}
+
+int cp_head_distill_ctx_bytes(const cp_head_desc *desc, size_t *bytes)
+{
+    if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
+    const int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!distill_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
+    *bytes = distill_ctx_bytes(*desc);
+    return CP_HEAD_OK;
+}
+
+int cp_head_distill_loss_fwd(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                             const int32_t *X, const void *TZ, float beta, float discount, float *loss, void *ctx,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !X || !TZ || !loss)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!(beta >= 0.f && beta <= 1.f) || !(discount >= 0.f)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!distill_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
+    if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DISTILL_FWD)) return CP_HEAD_ERR_WORKSPACE;
+    return distill_loss_fwd(*desc, H, W, U, G, X, TZ, beta, discount, loss, ctx, workspace,
+                            static_cast<hipStream_t>(stream));
+}
+
+int cp_head_distill_loss_bwd(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                             const int32_t *X, const void *TZ, const float *dloss, float scale, const void *ctx,
+                             float *dH, float *dW, float *dU, float *dG, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !X || !TZ || !dH)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!distill_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
+    if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DISTILL_BWD)) return CP_HEAD_ERR_WORKSPACE;
+    return distill_loss_bwd(*desc, H, W, U, G, X, TZ, dloss, scale, ctx, dH, dW, dU, dG, workspace,
+                            static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

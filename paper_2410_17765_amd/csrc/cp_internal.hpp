@@ -43,6 +43,13 @@ __device__ __forceinline__ float wave_max(float v)
 // ---------------------------------------------------------------- host-side layout
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + per - 1) / per); }
+template <typename T>
+inline T *at(void *base, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(base) + off); }
+template <typename T>
+inline const T *at(const void *base, size_t off) { return reinterpret_cast<const T *>(static_cast<const char *>(base) + off); }
+
 // Saved-for-backward buffer: [lse M f32][w T*r f32][gamma T*r f32][Y M*d].
 struct CtxLayout {
     size_t lse, w, gamma, Y, total;
@@ -119,11 +126,38 @@ int fast_first_token(const cp_head_desc &ds, const void *H, const void *W, const
 int fast_draft_sequential(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                           const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 
+// Pieces of the matrix-core loss path that other losses over the same heads build on.
+struct FastFwdBuffers {
+    float *lse, *w, *gamma;   // in ctx: log-normalisers [M], gate weights and posterior [T, r]
+    float *logw, *C;          // in the forward workspace: log w [T, r], C [M] (eq. 8)
+    bf16_t *Y;                // in ctx: y [M, d]
+};
+int fast_fwd_rows(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                  const int32_t *X, void *ctx, void *ws, FastFwdBuffers *out, hipStream_t st);
+// writes dz for rows m0 .. m0+Mc-1 of the chunk whose y is Yc: dZ[Mc, ldz] and, unless null, dZt[V, ldzt]
+typedef void (*FastDzLaunch)(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz,
+                             bf16_t *dZt, long ldzt, hipStream_t st);
+int fast_bwd_from_dz(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const void *Y, const float *dg, float *dH, float *dW, float *dU, float *dG, void *ws,
+                     FastDzLaunch dz_launch, void *user, hipStream_t st);
+bool fast_dims_fit(const cp_head_desc &ds);
+
 size_t fast_full_ctx_bytes(const cp_head_desc &ds);
 int fast_full_loss_fwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
                        float *loss, void *ctx, void *ws, hipStream_t st);
 int fast_full_loss_bwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
                        const float *dloss, float scale, const void *ctx, float *dH, float *dF, float *dG, void *ws,
                        hipStream_t st);
+
+// ---------------------------------------------------------------- fine-tuning (distillation) loss
+bool distill_supported(const cp_head_desc &ds);
+size_t distill_ctx_bytes(const cp_head_desc &ds);
+size_t distill_workspace_bytes(const cp_head_desc &ds, int op);
+int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, const void *TZ, float beta, float disc, float *loss, void *ctx, void *ws,
+                     hipStream_t st);
+int distill_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, const void *TZ, const float *dloss, float scale, const void *ctx, float *dH,
+                     float *dW, float *dU, float *dG, void *ws, hipStream_t st);
 
 }  // namespace cph

@@ -1,0 +1,499 @@
+// Head-only fine-tuning loss ("Fine tuning", eq. 14 and the discounted sum after it) on the matrix-core path.
+//
+// Reading of the paper's open points (the same as the CPU checker's):
+//   p^d_k[v] = sum_a qhat^(k)_a P^(k)(v | a),  qhat^(k) = softmax_a(log w_a + sum_{j<k} C_ja)   (eq. 13, true prefix)
+//   p^c_k    = softmax(TZ[t,k,:])                                                              (teacher, an input)
+//   L_k      = beta KL(p^c_k || p^d_k) - (1 - beta) log p^d_k[x_k],   loss[t] = sum_k disc^(k-1) L_k
+//
+// The per-token distribution p^d_k is a mixture over the r experts, so its logarithm couples the r head rows
+// of one (t, k).  Those rows are adjacent (m = (t n + k) r + a) and, for r in {1, 2, 4, 8}, sit in the four
+// accumulator registers of one 8-row group of the MFMA result layout (and, for r = 8, in both lane halves):
+// the epilogues below form log p^d_k[v] inside the tile, with no logits stored.
+//
+// Forward:  the per-row part of the training loss (gate, y, statistics of z, lse, C) -> teacher log-normalisers
+//           -> expert weights qhat per token -> a second product z = Y U^T whose epilogue accumulates, per row,
+//           S_a = sum_v p^c[v] rho_a[v] and, per token, KL(p^c || p^d) -> per-position loss and the row
+//           coefficients of the backward pass.
+// Backward: a third product whose epilogue writes dz = c1 P - c3 p^c rho + c2 1[v = x] in bf16; everything
+//           below dz is the training loss's backward pass.
+#include "gemm_nt.hpp"
+
+#include <math.h>
+
+namespace cph {
+
+namespace {
+
+typedef TileCfg<256, 256, 2, 2> Cfg;
+constexpr int kBlock = 256;
+
+// ------------------------------------------------------------------------------------------
+// small kernels
+// ------------------------------------------------------------------------------------------
+
+// log-normaliser of every teacher row TZ[g, :] (bf16), one block per row
+__global__ void __launch_bounds__(kBlock) k_teacher_lse(int V, const bf16_t *__restrict__ TZ, float *__restrict__ tlse)
+{
+    __shared__ float red[kBlock / kWave];
+    const size_t g = blockIdx.x;
+    const bf16_t *row = TZ + g * V;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float mx = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += kBlock) mx = fmaxf(mx, bf16_to_f32(row[v]));
+    mx = wave_max(mx);
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    float Mx = red[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / kWave; ++w) Mx = fmaxf(Mx, red[w]);
+    __syncthreads();
+    float l = 0.f;
+    for (int v = threadIdx.x; v < V; v += kBlock) l += expf(bf16_to_f32(row[v]) - Mx);
+    l = wave_sum(l);
+    if (lane == 0) red[wave] = l;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < kBlock / kWave; ++w) L += red[w];
+        tlse[g] = Mx + logf(L);
+    }
+}
+
+// Per position: the expert weights of every token's conditional (eq. 13 under the true prefix) and what
+// follows from the target column alone.  rowa[m] = {lse, log qhat}; rhox[m] = qhat_a P_a[x] / p^d[x];
+// ce[t, k] = -log p^d_k[x_k].  A dropped token (x < 0) gets log qhat = 0, rhox = 0, ce = 0.
+__global__ void k_distill_weights(size_t T, int n, int r, const float *__restrict__ logw, const float *__restrict__ C,
+                                  const float *__restrict__ lse, const int32_t *__restrict__ X,
+                                  float2 *__restrict__ rowa, float *__restrict__ rhox, float *__restrict__ ce)
+{
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    float q[8];
+    for (int a = 0; a < r; ++a) q[a] = logw[t * r + a];
+    for (int k = 0; k < n; ++k) {
+        const size_t m0 = (t * n + k) * r;
+        const int x = X[t * n + k];
+        if (x < 0) {
+            for (int a = 0; a < r; ++a) { rowa[m0 + a] = make_float2(lse[m0 + a], 0.f); rhox[m0 + a] = 0.f; }
+            ce[t * n + k] = 0.f;
+            continue;
+        }
+        float mx = q[0];
+        for (int a = 1; a < r; ++a) mx = fmaxf(mx, q[a]);
+        float s = 0.f;
+        for (int a = 0; a < r; ++a) s += expf(q[a] - mx);
+        const float qn = mx + logf(s);
+        float px = 0.f;
+        for (int a = 0; a < r; ++a) px += expf(q[a] - qn + C[m0 + a]);
+        for (int a = 0; a < r; ++a) {
+            rowa[m0 + a] = make_float2(lse[m0 + a], q[a] - qn);
+            rhox[m0 + a] = expf(q[a] - qn + C[m0 + a]) / px;
+            q[a] += C[m0 + a];
+        }
+        ce[t * n + k] = -logf(px);
+    }
+}
+
+// sums of the per-tile partial pairs of one row, one wavefront per row
+__global__ void __launch_bounds__(kBlock) k_sum_parts(size_t M, int parts, const float2 *__restrict__ part,
+                                                      float2 *__restrict__ out)
+{
+    const size_t m = (size_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const int lane = threadIdx.x & 63;
+    float a = 0.f, b = 0.f;
+    for (int p = lane; p < parts; p += kWave) {
+        const float2 v = part[m * parts + p];
+        a += v.x;
+        b += v.y;
+    }
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if (lane == 0) out[m] = make_float2(a, b);
+}
+
+// Per position: the loss and the row coefficients of the backward pass (for an upstream gradient of one):
+//   R_a = beta S_a + (1 - beta) rhox_a,  dq_ka = g_k (qhat_a - R_a),  D_ka = sum_{k' > k} dq_k'a
+//   c1[m] = g_k R_a - D_ka,  c2[m] = D_ka - (1 - beta) g_k rhox_a,  c3[t, k] = beta g_k,  dgsum[t, a] = sum_k dq_ka
+// with g_k = disc^k for a kept token and 0 for a dropped one.
+__global__ void k_distill_finish(size_t T, int n, int r, float beta, float disc, const int32_t *__restrict__ X,
+                                 const float2 *__restrict__ rowa, const float *__restrict__ rhox,
+                                 const float *__restrict__ ce, const float2 *__restrict__ SK,
+                                 float *__restrict__ loss, float *__restrict__ c1, float *__restrict__ c2,
+                                 float *__restrict__ c3, float *__restrict__ dgsum)
+{
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    float D[8];
+    for (int a = 0; a < r; ++a) D[a] = 0.f;
+    // last token to first, so that D accumulates the tokens after k
+    float total = 0.f;
+    for (int k = n - 1; k >= 0; --k) {
+        const size_t m0 = (t * n + k) * r;
+        const bool kept = X[t * n + k] >= 0;
+        const float g = !kept ? 0.f : (k == 0 ? 1.f : powf(disc, (float)k));
+        if (kept) total += g * (beta * SK[m0].y + (1.f - beta) * ce[t * n + k]);
+        for (int a = 0; a < r; ++a) {
+            const float R = beta * SK[m0 + a].x + (1.f - beta) * rhox[m0 + a];
+            c1[m0 + a] = kept ? g * R - D[a] : 0.f;
+            c2[m0 + a] = kept ? D[a] - (1.f - beta) * g * rhox[m0 + a] : 0.f;
+            if (kept) D[a] += g * (expf(rowa[m0 + a].y) - R);
+        }
+        c3[t * n + k] = beta * g;
+    }
+    for (int a = 0; a < r; ++a) dgsum[t * r + a] = D[a];
+    loss[t] = total;
+}
+
+// Backward row information: rowinfo[m] = {lse, log qhat, up c1, up c2}, grp[t n + k] = {tlse, up c3, x, -},
+// dg[t, a] = up dgsum[t, a];  up = dloss[t] * scale (or scale)
+__global__ void k_distill_bwd_rows(size_t M, int n, int r, const float2 *__restrict__ rowa, const float *__restrict__ c1,
+                                   const float *__restrict__ c2, const float *__restrict__ c3,
+                                   const float *__restrict__ tlse, const float *__restrict__ dgsum,
+                                   const float *__restrict__ dloss, float scale, const int32_t *__restrict__ X,
+                                   float4 *__restrict__ rowinfo, float4 *__restrict__ grp, float *__restrict__ dg)
+{
+    const size_t m = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= M) return;
+    const size_t g = m / r, t = g / n;
+    const int a = (int)(m % r);
+    const float up = dloss ? dloss[t] * scale : scale;
+    const float2 ra = rowa[m];
+    rowinfo[m] = make_float4(ra.x, ra.y, up * c1[m], up * c2[m]);
+    if (a == 0) grp[g] = make_float4(tlse[g], up * c3[g], __int_as_float(X[g]), 0.f);
+    if (g % n == 0) dg[t * r + a] = up * dgsum[t * r + a];
+}
+
+// ------------------------------------------------------------------------------------------
+// epilogues
+// ------------------------------------------------------------------------------------------
+
+// log of the mixture over the R experts of a token, for the four registers jj of one 8-row group:
+// l[jj] = log(qhat_a P_a[v]) of this lane's column; on return lm[jj] = log sum_a exp(l_a) of jj's group.
+template <int R>
+__device__ __forceinline__ void group_log_mixture(const float (&l)[4], float (&lm)[4])
+{
+    if (R == 1) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) lm[jj] = l[jj];
+    } else if (R == 2) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const float mx = fmaxf(l[2 * p], l[2 * p + 1]);
+            const float v = mx + __logf(__expf(l[2 * p] - mx) + __expf(l[2 * p + 1] - mx));
+            lm[2 * p] = v;
+            lm[2 * p + 1] = v;
+        }
+    } else {
+        float mx = fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3]));
+        if (R == 8) mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));            // the other four rows: other lane half
+        float s = __expf(l[0] - mx) + __expf(l[1] - mx) + __expf(l[2] - mx) + __expf(l[3] - mx);
+        if (R == 8) s += __shfl_xor(s, 32, kWave);
+        const float v = mx + __logf(s);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) lm[jj] = v;
+    }
+}
+
+// Second forward product: per row S_a = sum_v p^c[v] rho_a[v] and per token KL(p^c || p^d), as per-tile
+// partial sums {S, KL} in part[M, parts] (every row of a token carries the token's KL).
+template <int R>
+struct EpiDistillStats {
+    float2 *part;
+    int parts;
+    const float2 *rowa;      // [M] {lse, log qhat}
+    const bf16_t *TZ;        // [M / R, V]
+    const float *tlse;       // [M / R]
+    int M, V;
+    template <class C>
+    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int tn, char *) const
+    {
+        const int slot = tn * C::WN + (wave % C::WN);
+        const int half = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int rbase = row0 + 32 * i + 8 * q + 4 * half;
+                float lse_[4], lq_[4], tl_[4];
+                size_t trow_[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int rc = min(rbase + jj, M - 1);
+                    const float2 ra = rowa[rc];
+                    lse_[jj] = ra.x;
+                    lq_[jj] = ra.y;
+                    const int g = rc / R;
+                    tl_[jj] = tlse[g];
+                    trow_[jj] = (size_t)g * V;
+                }
+                float S[4] = {0.f, 0.f, 0.f, 0.f}, KL[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j) {
+                    const int col = col0 + acc_col(j, lane);
+                    const bool cv = col < V;
+                    const int cc = cv ? col : V - 1;
+                    float l[4], lm[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) l[jj] = acc[i][j][4 * q + jj] - lse_[jj] + lq_[jj];
+                    group_log_mixture<R>(l, lm);
+                    float lpc[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        if (R >= 4 && jj > 0) lpc[jj] = lpc[0];                      // one token per four rows
+                        else if (R == 2 && (jj & 1)) lpc[jj] = lpc[jj - 1];
+                        else lpc[jj] = bf16_to_f32(TZ[trow_[jj] + cc]) - tl_[jj];
+                    }
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const float pc = cv ? __expf(lpc[jj]) : 0.f;
+                        S[jj] += pc * __expf(l[jj] - lm[jj]);
+                        KL[jj] += pc * (lpc[jj] - lm[jj]);
+                    }
+                }
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const float s = row16_sum(S[jj]), kl = row16_sum(KL[jj]);
+                    const float so = dpp_move<0x142, 0xA>(0.f, s), ko = dpp_move<0x142, 0xA>(0.f, kl);
+                    const int row = rbase + jj;
+                    if ((lane & 31) == 16 && row < M) part[(size_t)row * parts + slot] = make_float2(s + so, kl + ko);
+                }
+            }
+        }
+    }
+};
+
+// Third product (backward): dz = c1 P - c3 p^c rho + c2 1[v = x] in bf16, row-major and transposed.
+template <int R>
+struct EpiDzDistill {
+    bf16_t *dZ;
+    long ldz;
+    bf16_t *dZt;             // or null
+    long ldzt;
+    const float4 *rowinfo;   // chunk-relative [Mc] {lse, log qhat, c1, c2} (upstream gradient folded in)
+    const float4 *grp;       // chunk-relative [Mc / R] {tlse, c3, target as int bits, -}
+    const bf16_t *TZ;        // chunk-relative [Mc / R, V]
+    int Mc, Mcp, V, Vp;
+    template <class C>
+    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    {
+        const int half = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int rbase = row0 + 32 * i + 8 * q + 4 * half;
+                float lse_[4], lq_[4], c1_[4], c2_[4], c3_[4], tl_[4];
+                int x_[4];
+                size_t trow_[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int row = rbase + jj;
+                    const int rc = min(row, Mc - 1);
+                    const float4 ri = rowinfo[rc];
+                    const float4 gi = grp[rc / R];
+                    const bool rv = row < Mc;
+                    lse_[jj] = ri.x;
+                    lq_[jj] = ri.y;
+                    c1_[jj] = rv ? ri.z : 0.f;
+                    c2_[jj] = rv ? ri.w : 0.f;
+                    tl_[jj] = gi.x;
+                    c3_[jj] = rv ? gi.y : 0.f;
+                    x_[jj] = __float_as_int(gi.z);
+                    trow_[jj] = (size_t)(rc / R) * V;
+                }
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j) {
+                    const int col = col0 + acc_col(j, lane);
+                    const bool cv = col < V;
+                    const int cc = cv ? col : V - 1;
+                    float l[4], lm[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) l[jj] = acc[i][j][4 * q + jj] - lse_[jj] + lq_[jj];
+                    group_log_mixture<R>(l, lm);
+                    float lpc[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        if (R >= 4 && jj > 0) lpc[jj] = lpc[0];
+                        else if (R == 2 && (jj & 1)) lpc[jj] = lpc[jj - 1];
+                        else lpc[jj] = bf16_to_f32(TZ[trow_[jj] + cc]) - tl_[jj];
+                    }
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const float P = __expf(l[jj] - lq_[jj]);
+                        const float g = c1_[jj] * P - c3_[jj] * __expf(lpc[jj] + l[jj] - lm[jj]) + (col == x_[jj] ? c2_[jj] : 0.f);
+                        acc[i][j][4 * q + jj] = cv ? g : 0.f;
+                    }
+                }
+                // keeps the row loads of later groups from being hoisted (they would spill registers)
+                asm volatile("" ::: "memory");
+            }
+        }
+        auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
+        store_tile_bf16<C>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+        if (dZt) store_tile_bf16_transposed<C>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// buffers
+// ------------------------------------------------------------------------------------------
+
+// ctx: the training loss's ctx, then {rowa [M] float2, c1 [M], c2 [M], c3 [T n], tlse [T n], dgsum [T r]}
+struct DistillCtx {
+    size_t base, rowa, c1, c2, c3, tlse, dgsum, total;
+};
+DistillCtx distill_ctx(const cp_head_desc &ds)
+{
+    DistillCtx c;
+    const size_t M = (size_t)ds.T * ds.n * ds.r, Tn = (size_t)ds.T * ds.n, Tr = (size_t)ds.T * ds.r;
+    size_t off = ctx_layout(ds, true).total;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    c.base = 0;
+    c.rowa = take(M * 8);
+    c.c1 = take(M * 4);
+    c.c2 = take(M * 4);
+    c.c3 = take(Tn * 4);
+    c.tlse = take(Tn * 4);
+    c.dgsum = take(Tr * 4);
+    c.total = off;
+    return c;
+}
+
+// forward workspace: the training loss's, then {rhox [M], ce [T n], SK [M] float2, part [M, parts] float2}
+struct DistillFwdWs {
+    size_t rhox, ce, SK, part, total;
+    int parts;
+};
+DistillFwdWs distill_fwd_ws(const cp_head_desc &ds)
+{
+    DistillFwdWs f;
+    const size_t M = (size_t)ds.T * ds.n * ds.r, Tn = (size_t)ds.T * ds.n;
+    f.parts = ((ds.V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+    size_t off = align_up(fast_workspace_bytes(ds, CP_HEAD_OP_LOSS_FWD));
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    f.rhox = take(M * 4);
+    f.ce = take(Tn * 4);
+    f.SK = take(M * 8);
+    f.part = take(M * f.parts * sizeof(float2));
+    f.total = off;
+    return f;
+}
+
+// backward workspace: the training loss's, then {rowinfo [M] float4, grp [T n] float4, dg [T r]}
+struct DistillBwdWs {
+    size_t rowinfo, grp, dg, total;
+};
+DistillBwdWs distill_bwd_ws(const cp_head_desc &ds)
+{
+    DistillBwdWs b;
+    const size_t M = (size_t)ds.T * ds.n * ds.r, Tn = (size_t)ds.T * ds.n, Tr = (size_t)ds.T * ds.r;
+    size_t off = align_up(fast_workspace_bytes(ds, CP_HEAD_OP_LOSS_BWD));
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    b.rowinfo = take(M * 16);
+    b.grp = take(Tn * 16);
+    b.dg = take(Tr * 4);
+    b.total = off;
+    return b;
+}
+
+template <int R>
+void launch_stats(const cp_head_desc &ds, const bf16_t *Y, const bf16_t *U, float2 *part, int parts,
+                  const float2 *rowa, const bf16_t *TZ, const float *tlse, hipStream_t st)
+{
+    const int M = (int)((size_t)ds.T * ds.n * ds.r);
+    launch_gemm_nt<Cfg>("distill_gemm_z_kl", Y, ds.d, M, U, ds.d, ds.V, ds.d,
+                        EpiDistillStats<R>{part, parts, rowa, TZ, tlse, M, ds.V}, st);
+}
+
+struct DistillDzArgs {
+    const bf16_t *U, *TZ;
+    const float4 *rowinfo, *grp;
+    int d, V, r;
+};
+template <int R>
+void distill_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt,
+                       long ldzt, hipStream_t st)
+{
+    const DistillDzArgs *a = static_cast<const DistillDzArgs *>(user);
+    launch_gemm_nt<Cfg>("distill_gemm_z_dz", Yc, a->d, Mc, a->U, a->d, a->V, a->d,
+                        EpiDzDistill<R>{dZ, ldz, dZt, ldzt, a->rowinfo + m0, a->grp + m0 / R, a->TZ + (m0 / R) * a->V, Mc, Mcp,
+                                        a->V, (int)ldz},
+                        st);
+}
+
+}  // namespace
+
+bool distill_supported(const cp_head_desc &ds)
+{
+    return use_fast_path(ds) && (ds.r == 1 || ds.r == 2 || ds.r == 4 || ds.r == 8);
+}
+size_t distill_ctx_bytes(const cp_head_desc &ds) { return distill_ctx(ds).total; }
+size_t distill_workspace_bytes(const cp_head_desc &ds, int op)
+{
+    return op == CP_HEAD_OP_DISTILL_FWD ? distill_fwd_ws(ds).total : distill_bwd_ws(ds).total;
+}
+
+int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,
+                     const int32_t *X, const void *TZv, float beta, float disc, float *loss, void *ctx, void *ws,
+                     hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    FastFwdBuffers fb;
+    const int rc = fast_fwd_rows(ds, H, W, Uv, G, X, ctx, ws, &fb, st);      // gate, y, statistics, lse, C (eq. 5-8)
+    if (rc != CP_HEAD_OK) return rc;
+    const bf16_t *U = (const bf16_t *)Uv, *TZ = (const bf16_t *)TZv;
+    const DistillCtx dc = distill_ctx(ds);
+    const DistillFwdWs f = distill_fwd_ws(ds);
+    const size_t T = (size_t)ds.T, M = T * ds.n * ds.r, Tn = T * ds.n;
+    float2 *rowa = at<float2>(ctx, dc.rowa);
+    float *c1 = at<float>(ctx, dc.c1), *c2 = at<float>(ctx, dc.c2), *c3 = at<float>(ctx, dc.c3);
+    float *tlse = at<float>(ctx, dc.tlse), *dgsum = at<float>(ctx, dc.dgsum);
+    float *rhox = at<float>(ws, f.rhox), *ce = at<float>(ws, f.ce);
+    float2 *SK = at<float2>(ws, f.SK), *part = at<float2>(ws, f.part);
+
+    k_teacher_lse<<<(unsigned)Tn, kBlock, 0, st>>>(ds.V, TZ, tlse);
+    k_distill_weights<<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, fb.logw, fb.C, fb.lse, X, rowa, rhox, ce);
+    switch (ds.r) {
+    case 1: launch_stats<1>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+    case 2: launch_stats<2>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+    case 4: launch_stats<4>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+    default: launch_stats<8>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+    }
+    k_sum_parts<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, f.parts, part, SK);
+    k_distill_finish<<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, beta, disc, X, rowa, rhox, ce, SK, loss, c1, c2,
+                                                               c3, dgsum);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int distill_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,
+                     const int32_t *X, const void *TZv, const float *dloss, float scale, const void *ctx, float *dH,
+                     float *dW, float *dU, float *dG, void *ws, hipStream_t st)
+{
+    const size_t nrd = (size_t)ds.n * ds.r * ds.d;
+    if (ds.T == 0) {
+        launch_fill_zero(dW, nrd * ds.d, st);
+        launch_fill_zero(dU, (size_t)ds.V * ds.d, st);
+        launch_fill_zero(dG, (size_t)ds.r * ds.d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (!fast_dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const DistillCtx dc = distill_ctx(ds);
+    const DistillBwdWs b = distill_bwd_ws(ds);
+    const CtxLayout cl = ctx_layout(ds, true);
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    const float2 *rowa = at<float2>(ctx, dc.rowa);
+    const float *c1 = at<float>(ctx, dc.c1), *c2 = at<float>(ctx, dc.c2), *c3 = at<float>(ctx, dc.c3);
+    const float *tlse = at<float>(ctx, dc.tlse), *dgsum = at<float>(ctx, dc.dgsum);
+    float4 *rowinfo = at<float4>(ws, b.rowinfo), *grp = at<float4>(ws, b.grp);
+    float *dg = at<float>(ws, b.dg);
+    k_distill_bwd_rows<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, ds.n, ds.r, rowa, c1, c2, c3, tlse, dgsum, dloss, scale, X,
+                                                                 rowinfo, grp, dg);
+    DistillDzArgs args{(const bf16_t *)Uv, (const bf16_t *)TZv, rowinfo, grp, ds.d, ds.V, ds.r};
+    FastDzLaunch fn = ds.r == 1 ? distill_dz_launch<1> : ds.r == 2 ? distill_dz_launch<2>
+                    : ds.r == 4 ? distill_dz_launch<4> : distill_dz_launch<8>;
+    return fast_bwd_from_dz(ds, H, W, Uv, G, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, fn, &args, st);
+}
+
+}  // namespace cph

@@ -17,13 +17,6 @@ namespace {
 typedef TileCfg<256, 256, 2, 2> Cfg;
 constexpr int kBlock = 256;
 
-inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + per - 1) / per); }
-
-template <typename T>
-inline T *at(void *base, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(base) + off); }
-template <typename T>
-inline const T *at(const void *base, size_t off) { return reinterpret_cast<const T *>(static_cast<const char *>(base) + off); }
 
 // ------------------------------------------------------------------------------------------
 // epilogues
@@ -62,31 +55,6 @@ struct EpiStoreF32 {
                            [&](int i, int j, int v, int, int) { return acc[i][j][v]; });
     }
 };
-
-// Cross-lane steps of the row statistics, as data-parallel-primitive moves (no LDS traffic):
-// quad swaps, mirror inside 8 and inside 16 lanes give every lane of a 16-lane row the row's value;
-// the last lane of rows 0 and 2 is then broadcast into rows 1 and 3.
-template <int CTRL, int ROW_MASK = 0xF>
-__device__ __forceinline__ float dpp_move(float old, float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
-}
-__device__ __forceinline__ float row16_max(float v)
-{
-    v = fmaxf(v, dpp_move<0xB1>(v, v));    // lane ^ 1
-    v = fmaxf(v, dpp_move<0x4E>(v, v));    // lane ^ 2
-    v = fmaxf(v, dpp_move<0x141>(v, v));   // mirror within 8
-    v = fmaxf(v, dpp_move<0x140>(v, v));   // mirror within 16
-    return v;
-}
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += dpp_move<0xB1>(v, v);
-    v += dpp_move<0x4E>(v, v);
-    v += dpp_move<0x141>(v, v);
-    v += dpp_move<0x140>(v, v);
-    return v;
-}
 
 // Running statistics of the logits (eq. 5 in log space): for every row of the wavefront's
 // sub-tile the maximum and the sum of exp(z - max) over its columns.  One (max, sum) pair per
@@ -1062,10 +1030,11 @@ size_t fast_workspace_bytes(const cp_head_desc &ds, int op)
     return draft_ws(ds).total;   // both draft calls
 }
 
-int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
-                  const int32_t *X, float *loss, void *ctx, void *ws, size_t, hipStream_t st)
+// Everything of the forward pass that is per head row: gate (eq. 7), y, the statistics of z, the
+// log-normalisers (eq. 5) and C (eq. 8).  `out` receives where the results live in ctx and ws.
+int fast_fwd_rows(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                  const int32_t *X, void *ctx, void *ws, FastFwdBuffers *out, hipStream_t st)
 {
-    if (ds.T == 0) return CP_HEAD_OK;
     if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
     const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv;
     const CtxLayout cl = ctx_layout(ds, true);
@@ -1083,40 +1052,41 @@ int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     launch_gemm_nt<Cfg>("gemm_y", H, d, T, W, d, nrd, d, EpiStoreBf16{Y, Ylo, (long)nrd, T, nrd}, st);   // y = W_sa h
     launch_gemm_nt<Cfg>("gemm_z_stats", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);  // z = U y, statistics
     k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, ds.r, f.parts, part, Y, Ylo, U, X, lse, C);
-    launch_mixture(ds, logw, C, loss, gamma, -1.f, st);                                              // eq. 9
+    out->lse = lse; out->w = w; out->gamma = gamma; out->logw = logw; out->C = C; out->Y = Y;
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
-int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
-                  const int32_t *X, const float *dloss, float scale, const void *ctx, float *dH, float *dW,
-                  float *dU, float *dG, void *ws, size_t, hipStream_t st)
+int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                  const int32_t *X, float *loss, void *ctx, void *ws, size_t, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    FastFwdBuffers b;
+    const int rc = fast_fwd_rows(ds, Hv, Wv, Uv, Gv, X, ctx, ws, &b, st);
+    if (rc != CP_HEAD_OK) return rc;
+    launch_mixture(ds, b.logw, b.C, loss, b.gamma, -1.f, st);                                        // eq. 9
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+// The backward pass below the logit gradients: per bounded chunk of head rows `dz_launch` writes dz
+// (bf16, row-major and, if asked, transposed), then dY = dz U and dU += dz^T Y; afterwards
+// dW = dY^T H, dH = dY W + G^T dg and dG = dg^T H.  dg[T,r] must already hold the gate gradients.
+int fast_bwd_from_dz(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                     const void *Yv, const float *dg, float *dH, float *dW, float *dU, float *dG, void *ws,
+                     FastDzLaunch dz_launch, void *user, hipStream_t st)
 {
     const int d = ds.d, V = ds.V, r = ds.r, n = ds.n;
     const size_t nrd = (size_t)n * r * d;
-    if (ds.T == 0) {
-        launch_fill_zero(dW, nrd * d, st);
-        launch_fill_zero(dU, (size_t)V * d, st);
-        launch_fill_zero(dG, (size_t)r * d, st);
-        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
-    }
-    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
     const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
-    const CtxLayout cl = ctx_layout(ds, true);
+    const bf16_t *Y = (const bf16_t *)Yv;
     const BwdWs b = bwd_ws(ds);
     const size_t T = (size_t)ds.T, M = T * n * r;
-    const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
-    const bf16_t *Y = at<bf16_t>(ctx, cl.Y);
-    float4 *rowinfo = at<float4>(ws, b.coef);
-    float *dg = at<float>(ws, b.dg);
     bf16_t *Ut = at<bf16_t>(ws, b.Ut), *Wt = at<bf16_t>(ws, b.Wt), *Ht = at<bf16_t>(ws, b.Ht);
     bf16_t *dY = at<bf16_t>(ws, b.dY), *dYt = at<bf16_t>(ws, b.dYt);
     bf16_t *dZ = at<bf16_t>(ws, b.dZ), *dZt = at<bf16_t>(ws, b.dZt), *Yt = at<bf16_t>(ws, b.Yt);
     const int Vp = (int)b.Vp, Tp = (int)b.Tp;
     const long ldV = (long)b.ldV, ldT = (long)b.ldT, ldM = (long)b.ldM, ldN = (long)b.ldN;
 
-    k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, lse, dloss, scale, X, rowinfo, dg);
     transpose_bf16(U, d, V, d, Ut, ldV, Vp, st);                      // Ut[d, Vp]
-
     int first = 1;
     for (size_t m0 = 0; m0 < M; m0 += b.chunk) {
         const int Mc = (int)((M - m0 < b.chunk) ? M - m0 : b.chunk);
@@ -1124,8 +1094,7 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
         const bf16_t *Yc = Y + m0 * d;
         // recompute z for the chunk; the epilogue turns it into dz (bf16); the tiles over V also
         // cover the padding columns V..Vp-1, which the epilogue zero-fills
-        launch_gemm_nt<Cfg>("gemm_z_dz", Yc, d, Mc, U, d, V, d,
-                            EpiDz{dZ, (long)Vp, dU ? dZt : nullptr, ldM, rowinfo + m0, Mc, Mcp, V, Vp}, st);
+        dz_launch(user, Yc, Mc, Mcp, m0, dZ, (long)Vp, dU ? dZt : nullptr, ldM, st);
         // dY = dz U   (contraction over the vocabulary)
         launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st);
         if (dU) {
@@ -1152,6 +1121,48 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
         k_dgate_reduce<<<blocks_for((size_t)r * d, kBlock), kBlock, 0, st>>>((int)chunks, d, r, part, dG);
     }
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+bool fast_dims_fit(const cp_head_desc &ds) { return dims_fit(ds); }
+
+namespace {
+struct LossDzArgs {
+    const bf16_t *U;
+    const float4 *rowinfo;
+    int d, V;
+};
+// dz of the training loss: dz[m, v] = coef[m] (exp(z - lse[m]) - 1[v = x_m])
+void loss_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt, long ldzt,
+                    hipStream_t st)
+{
+    const LossDzArgs *a = static_cast<const LossDzArgs *>(user);
+    launch_gemm_nt<Cfg>("gemm_z_dz", Yc, a->d, Mc, a->U, a->d, a->V, a->d,
+                        EpiDz{dZ, ldz, dZt, ldzt, a->rowinfo + m0, Mc, Mcp, a->V, (int)ldz}, st);
+}
+}  // namespace
+
+int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                  const int32_t *X, const float *dloss, float scale, const void *ctx, float *dH, float *dW,
+                  float *dU, float *dG, void *ws, size_t, hipStream_t st)
+{
+    const int d = ds.d, V = ds.V, r = ds.r, n = ds.n;
+    const size_t nrd = (size_t)n * r * d;
+    if (ds.T == 0) {
+        launch_fill_zero(dW, nrd * d, st);
+        launch_fill_zero(dU, (size_t)V * d, st);
+        launch_fill_zero(dG, (size_t)r * d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (!dims_fit(ds)) return CP_HEAD_ERR_UNSUPPORTED;
+    const CtxLayout cl = ctx_layout(ds, true);
+    const BwdWs b = bwd_ws(ds);
+    const size_t M = (size_t)ds.T * n * r;
+    const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    float4 *rowinfo = at<float4>(ws, b.coef);
+    float *dg = at<float>(ws, b.dg);
+    k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, lse, dloss, scale, X, rowinfo, dg);
+    LossDzArgs args{(const bf16_t *)Uv, rowinfo, d, V};
+    return fast_bwd_from_dz(ds, Hv, Wv, Uv, Gv, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, loss_dz_launch, &args, st);
 }
 
 int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,

@@ -509,6 +509,31 @@ inline void launch_gemm_nt(const char *name, const bf16_t *A, long lda, int M, c
     k_gemm_nt<Cfg, Epi><<<gemm_grid(g.tiles_m, g.tiles_n), Cfg::THREADS, 0, st>>>(g, epi);
 }
 
+// Cross-lane steps of the row statistics, as data-parallel-primitive moves (no LDS traffic):
+// quad swaps, mirror inside 8 and inside 16 lanes give every lane of a 16-lane row the row's value;
+// the last lane of rows 0 and 2 is then broadcast into rows 1 and 3.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_move(float old, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = fmaxf(v, dpp_move<0xB1>(v, v));    // lane ^ 1
+    v = fmaxf(v, dpp_move<0x4E>(v, v));    // lane ^ 2
+    v = fmaxf(v, dpp_move<0x141>(v, v));   // mirror within 8
+    v = fmaxf(v, dpp_move<0x140>(v, v));   // mirror within 16
+    return v;
+}
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_move<0xB1>(v, v);
+    v += dpp_move<0x4E>(v, v);
+    v += dpp_move<0x141>(v, v);
+    v += dpp_move<0x140>(v, v);
+    return v;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Coalesced output of a wavefront's sub-tile.  The MFMA result layout gives each lane single
 // elements of 32 different columns, so values are first laid out row-major in a wave-private

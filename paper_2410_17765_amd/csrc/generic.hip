@@ -19,7 +19,6 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 
-inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
 // ------------------------------------------------------------------------------------------
 // gate: logw = log_softmax(G h), w = exp(logw)      (eq. 7)
@@ -448,10 +447,6 @@ inline GenericWs generic_ws(const cp_head_desc &ds, int op)
     return g;
 }
 
-template <typename T>
-inline T *at(void *base, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(base) + off); }
-template <typename T>
-inline const T *at(const void *base, size_t off) { return reinterpret_cast<const T *>(static_cast<const char *>(base) + off); }
 
 template <typename TIn>
 int loss_fwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const int32_t *X,

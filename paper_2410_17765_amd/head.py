@@ -89,6 +89,36 @@ class CpHead:
                                  out["dH"], out["dW"], out["dU"], out["dG"], ws, stream)
         return {k: v for k, v in out.items() if v is not None}
 
+    # ------------------------------------------------------------------ fine-tuning (distillation) loss
+    def distill_loss_fwd(self, H: torch.Tensor, X: torch.Tensor, TZ: torch.Tensor, beta: float = 0.9,
+                         discount: float = 1.0, stream=None) -> torch.Tensor:
+        """TZ[T,n,V] teacher logits (storage dtype) -> loss[T] fp32.  Keeps ctx for distill_loss_bwd."""
+        T = H.shape[0]
+        ds = self.desc(T)
+        self._dctx = _scratch(binding.cp_head_distill_ctx_bytes(ds), self.device)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DISTILL_FWD), self.device)
+        loss = torch.empty(T, dtype=torch.float32, device=self.device)
+        binding.cp_head_distill_loss_fwd(ds, H, self.W, self.U, self.G, X, TZ, beta, discount, loss, self._dctx, ws,
+                                         stream)
+        return loss
+
+    def distill_loss_bwd(self, H: torch.Tensor, X: torch.Tensor, TZ: torch.Tensor,
+                         dloss: Optional[torch.Tensor] = None, scale: float = 1.0, want_dU: bool = False,
+                         stream=None) -> Dict[str, torch.Tensor]:
+        T = H.shape[0]
+        ds = self.desc(T)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DISTILL_BWD), self.device)
+        f32 = dict(dtype=torch.float32, device=self.device)
+        out = {
+            "dH": torch.empty((T, self.d), **f32),
+            "dW": torch.empty((self.n, self.r, self.d, self.d), **f32),
+            "dU": torch.empty((self.V, self.d), **f32) if want_dU else None,
+            "dG": torch.empty((self.r, self.d), **f32),
+        }
+        binding.cp_head_distill_loss_bwd(ds, H, self.W, self.U, self.G, X, TZ, dloss, scale, self._dctx,
+                                         out["dH"], out["dW"], out["dU"], out["dG"], ws, stream)
+        return {k: v for k, v in out.items() if v is not None}
+
     # ------------------------------------------------------------------ draft
     def draft_sample(self, H: torch.Tensor, uniforms: torch.Tensor, stream=None):
         B = H.shape[0]

@@ -37,6 +37,7 @@ SEED_UNIFORMS = 1006
 SEED_SUBSET = 1007
 SEED_PERM = 1008
 SEED_F = 1010
+SEED_TEACHER = 1011
 
 
 @dataclasses.dataclass(frozen=True)
@@ -153,6 +154,12 @@ def unembedding(cfg: HeadConfig) -> np.ndarray:
 def full_head_weights(cfg: HeadConfig) -> np.ndarray:
     """F[n,r,V,d]; z = F[s,a] @ h.  N(0, u_scale^2/d), the scale of the shared-unembedding logits."""
     return _normal(SEED_F, (cfg.n, cfg.r, cfg.V, cfg.d), cfg.u_scale * cfg.d ** -0.5, cfg.dtype)
+
+
+def teacher_logits(cfg: HeadConfig, scale: float = 1.5) -> np.ndarray:
+    """TZ[T,n,V]: logits of the original head for the fine-tuning loss, N(0, scale^2) (a moderately peaked
+    distribution over the vocabulary), rounded to the storage type like the other tensors."""
+    return _normal(SEED_TEACHER, (cfg.T, cfg.n, cfg.V), scale, cfg.dtype)
 
 
 def gate(cfg: HeadConfig) -> np.ndarray:

@@ -76,7 +76,7 @@ def test_unsupported(lib):
                                  ctypes.byref(out)) == -2
     assert lib.cp_head_ctx_bytes(ctypes.byref(binding.make_desc(4, 8, 16, 2, 2, 7)), ctypes.byref(out)) == -2
     assert lib.cp_head_ctx_bytes(None, ctypes.byref(out)) == -1
-    assert lib.cp_head_workspace_bytes(ctypes.byref(binding.make_desc(4, 8, 16, 2, 2, 0)), 9,
+    assert lib.cp_head_workspace_bytes(ctypes.byref(binding.make_desc(4, 8, 16, 2, 2, 0)), 99,
                                        ctypes.byref(out)) == -1
 
 
