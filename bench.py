@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token', 'full_heads', 'full_heads_7b'")
+    ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token', 'full_heads', 'full_heads_7b', 'distill_7b'")
     ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per two threads)")
@@ -155,6 +155,78 @@ def bench_full(args):
                                "sample": f"{len(sel)} seeded positions of the workload at full d, V, n, r; fp64 forward "
                                          f"+ backward with all gradients; {dtc:.1f} s wall"}
     return out
+
+
+def bench_distill(args):
+    """fwd+bwd step of the head-only fine-tuning loss (eq. 14) at the headline shape, unembedding frozen
+    (dU = NULL), beta = 0.9, discount = 0.8.  The 4.2 GB of teacher logits are drawn on the device (seeded
+    torch generator, N(0, 1.5^2)): timing only, parity is shown by the tests on seeded host inputs."""
+    import torch
+    from paper_2410_17765_amd import binding, head, synth
+
+    binding.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.CONFIGS["head_7b"]
+    inp = synth.make_inputs(cfg)
+    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    H = head.to_device(inp["H"], cfg.dtype)
+    X = torch.from_numpy(inp["X"]).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED_TEACHER)
+    TZ = torch.empty((cfg.T, cfg.n, cfg.V), dtype=torch.bfloat16, device=dev)
+    for t0 in range(0, cfg.T, 2048):
+        TZ[t0:t0 + 2048] = (torch.randn((min(2048, cfg.T - t0), cfg.n, cfg.V), generator=gen, device=dev) * 1.5).to(torch.bfloat16)
+    ds = h.desc(cfg.T)
+    ctx = torch.empty(binding.cp_head_distill_ctx_bytes(ds), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(binding.cp_head_workspace_bytes(ds, binding.OP_DISTILL_FWD),
+                         binding.cp_head_workspace_bytes(ds, binding.OP_DISTILL_BWD)), dtype=torch.uint8, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    loss = torch.empty(cfg.T, **f32)
+    dH = torch.empty((cfg.T, cfg.d), **f32)
+    dW = torch.empty((cfg.n, cfg.r, cfg.d, cfg.d), **f32)
+    dG = torch.empty((cfg.r, cfg.d), **f32)
+    scale = 1.0 / cfg.T
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        binding.cp_head_distill_loss_fwd(ds, H, h.W, h.U, h.G, X, TZ, 0.9, 0.8, loss, ctx, ws, stream)
+        binding.cp_head_distill_loss_bwd(ds, H, h.W, h.U, h.G, X, TZ, None, scale, ctx, dH, dW, None, dG, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.cp_head_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    binding.cp_head_profile_enable(False)
+    kernels = binding.cp_head_profile_read()
+    ms_per_step = dt * 1e3 / args.steps
+    gemms = [k for k in kernels if "gemm_" in k[0]]
+    dom = max(gemms, key=lambda k: k[2])
+    achieved = dom[3] / (dom[2] * 1e-3) / 1e12
+    # algorithmic products: y, z (log-normalisers), z again (mixture over the experts), dY, dH, dW
+    model_flops = (2.0 * cfg.n * cfg.r * cfg.d * (3 * cfg.d + 3 * cfg.V)) * cfg.T
+    return {
+        "metric": "CP-head fine-tuning loss fwd+bwd tokens/s", "value": cfg.T * args.steps / dt, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic (teacher logits drawn on the device)",
+        "config": {"workload": "distill_7b", "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
+                   "beta": 0.9, "discount": 0.8, "frozen_u": True, "token": "one position (n future tokens each)"},
+        "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
+        "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "mean_loss": float(loss.mean()),
+        "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "launches": dom[1],
+                     "avg_ms": dom[2] / dom[1]},
+        "kernels": [{"name": k[0], "launches": k[1], "ms_per_step": k[2] / args.steps,
+                     "rate": (k[3] / (k[2] * 1e-3) / 1e12) if k[2] > 0 else None,
+                     "rate_unit": "TFLOP/s" if "gemm_" in k[0] else "TB/s"} for k in kernels],
+    }
 
 
 def bench_loss(args):
@@ -374,6 +446,8 @@ def main():
         out = bench_draft(args, args.workload)
     elif args.workload in ("full_heads", "full_heads_7b"):
         out = bench_full(args)
+    elif args.workload == "distill_7b":
+        out = bench_distill(args)
     else:
         out = bench_loss(args)
     print(json.dumps(out))

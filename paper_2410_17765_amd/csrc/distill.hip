@@ -273,35 +273,61 @@ struct EpiDzDistill {
     long ldzt;
     const float4 *rowinfo;   // chunk-relative [Mc] {lse, log qhat, c1, c2} (upstream gradient folded in)
     const float4 *grp;       // chunk-relative [Mc / R] {tlse, c3, target as int bits, -}
-    const bf16_t *TZ;        // chunk-relative [Mc / R, V]
+    const bf16_t *TZ;        // chunk-relative [Mc / R, V]; Mc / R * V < 2^31
     int Mc, Mcp, V, Vp;
     template <class C>
     __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
     {
+        constexpr int RG = R < 4 ? R : 4;        // rows of one token among the four registers of a group
+        constexpr int NG = 4 / RG;               // tokens among them
+        auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
+        // 64 rows at a time: turn their logits into gradients and write them out at once, so that the
+        // finished values do not stay in registers
+        convert<C, RG, NG, 0>(acc, row0, col0, lane);
+        store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+        if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
+        if (C::TM > 2) {
+            convert<C, RG, NG, 1>(acc, row0, col0, lane);
+            store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+            if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
+        }
+    }
+
+    // logits -> gradients, in place, for the 32-row blocks 2 IP and 2 IP + 1
+    template <class C, int RG, int NG, int IP>
+    __device__ __forceinline__ void convert(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane) const
+    {
+        static_assert(C::TM == 2 || C::TM == 4, "sub-tiles of 64 or 128 rows");
         const int half = lane >> 5;
+        const float4 *__restrict__ rinfo = rowinfo;
+        const float4 *__restrict__ ginfo = grp;
+        const bf16_t *__restrict__ tz = TZ;
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i) {
+        for (int i = 2 * IP; i < 2 * IP + 2; ++i) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int rbase = row0 + 32 * i + 8 * q + 4 * half;
-                float lse_[4], lq_[4], c1_[4], c2_[4], c3_[4], tl_[4];
-                int x_[4];
-                size_t trow_[4];
+                float lse_[4], lq_[4], c1_[4], c2_[4];
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
                     const int row = rbase + jj;
-                    const int rc = min(row, Mc - 1);
-                    const float4 ri = rowinfo[rc];
-                    const float4 gi = grp[rc / R];
-                    const bool rv = row < Mc;
+                    const float4 ri = rinfo[min(row, Mc - 1)];
                     lse_[jj] = ri.x;
                     lq_[jj] = ri.y;
-                    c1_[jj] = rv ? ri.z : 0.f;
-                    c2_[jj] = rv ? ri.w : 0.f;
-                    tl_[jj] = gi.x;
-                    c3_[jj] = rv ? gi.y : 0.f;
-                    x_[jj] = __float_as_int(gi.z);
-                    trow_[jj] = (size_t)(rc / R) * V;
+                    c1_[jj] = row < Mc ? ri.z : 0.f;
+                    c2_[jj] = row < Mc ? ri.w : 0.f;
+                }
+                float tl_[NG], c3_[NG];
+                int x_[NG], toff_[NG];
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi) {
+                    const int row = rbase + gi * RG;
+                    const int g = min(row, Mc - 1) / R;
+                    const float4 gv = ginfo[g];
+                    tl_[gi] = gv.x;
+                    c3_[gi] = row < Mc ? gv.y : 0.f;
+                    x_[gi] = __float_as_int(gv.z);
+                    toff_[gi] = g * V;
                 }
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j) {
@@ -312,27 +338,22 @@ struct EpiDzDistill {
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) l[jj] = acc[i][j][4 * q + jj] - lse_[jj] + lq_[jj];
                     group_log_mixture<R>(l, lm);
-                    float lpc[4];
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        if (R >= 4 && jj > 0) lpc[jj] = lpc[0];
-                        else if (R == 2 && (jj & 1)) lpc[jj] = lpc[jj - 1];
-                        else lpc[jj] = bf16_to_f32(TZ[trow_[jj] + cc]) - tl_[jj];
-                    }
+                    for (int gi = 0; gi < NG; ++gi) {
+                        const float lpc = bf16_to_f32(tz[toff_[gi] + cc]) - tl_[gi];
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        const float P = __expf(l[jj] - lq_[jj]);
-                        const float g = c1_[jj] * P - c3_[jj] * __expf(lpc[jj] + l[jj] - lm[jj]) + (col == x_[jj] ? c2_[jj] : 0.f);
-                        acc[i][j][4 * q + jj] = cv ? g : 0.f;
+                        for (int e = 0; e < RG; ++e) {
+                            const int jj = gi * RG + e;
+                            const float P = __expf(l[jj] - lq_[jj]);
+                            const float g = c1_[jj] * P - c3_[gi] * __expf(lpc + l[jj] - lm[jj]) + (col == x_[gi] ? c2_[jj] : 0.f);
+                            acc[i][j][4 * q + jj] = cv ? g : 0.f;
+                        }
                     }
                 }
                 // keeps the row loads of later groups from being hoisted (they would spill registers)
                 asm volatile("" ::: "memory");
             }
         }
-        auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
-        store_tile_bf16<C>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
-        if (dZt) store_tile_bf16_transposed<C>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
     }
 };
 

@@ -114,11 +114,26 @@ struct EpiDz {
     template <class C>
     __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
     {
+        static_assert(C::TM == 2 || C::TM == 4, "sub-tiles of 64 or 128 rows");
+        auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
+        // 64 rows at a time: turn their logits into gradients in place and write them out at once, so that
+        // the finished values do not stay in registers
+        convert<C, 0>(acc, row0, col0, lane);
+        store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+        if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
+        if (C::TM > 2) {
+            convert<C, 1>(acc, row0, col0, lane);
+            store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+            if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
+        }
+    }
+
+    template <class C, int IP>
+    __device__ __forceinline__ void convert(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane) const
+    {
         const float4 *__restrict__ info = rowinfo;
-        // turn the logits into their gradients in place, one 32-row block at a time (the compiler
-        // barrier keeps the per-row loads of later blocks from being hoisted and spilling registers)
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i) {
+        for (int i = 2 * IP; i < 2 * IP + 2; ++i) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = row0 + acc_row(i, v, lane);
@@ -133,11 +148,9 @@ struct EpiDz {
                     acc[i][j][v] = col < V ? g : 0.f;
                 }
             }
+            // keeps the per-row loads of the next block from being hoisted (they would spill registers)
             asm volatile("" ::: "memory");
         }
-        auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
-        store_tile_bf16<C>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
-        if (dZt) store_tile_bf16_transposed<C>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
     }
 };
 

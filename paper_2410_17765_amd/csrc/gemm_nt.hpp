@@ -543,7 +543,8 @@ __device__ __forceinline__ float row16_sum(float v)
 // global coordinates are (row, col).  All loops are fully unrolled so that the accumulators are
 // only ever indexed with constants and stay in registers.
 // ---------------------------------------------------------------------------------------------
-template <class Cfg, class F>
+// I0, I1 restrict the call to the 32-row blocks I0 .. I1-1 of the sub-tile (default: all of them).
+template <class Cfg, class F, int I0 = 0, int I1 = Cfg::TM>
 __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, int row0, int col0, int row_limit,
                                                 int col_limit /* multiple of 8 */, bf16_t *__restrict__ dst, long ld,
                                                 F value)
@@ -555,7 +556,7 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
     char *stage = smem + wave * (32 * RS);
     __syncthreads();                                    // every wavefront is done reading operand tiles
 #pragma unroll
-    for (int i = 0; i < Cfg::TM; ++i) {
+    for (int i = I0; i < I1; ++i) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -582,7 +583,8 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
 // rows of one column per accumulator group, so the sub-tile is laid out column-major in LDS (64 rows at
 // a time, 8-byte writes) and leaves as 16-byte pieces of 128-byte column segments.
 // row_limit and ld are multiples of 8; rows are written up to row_limit, columns up to col_limit.
-template <class Cfg, class F>
+// IP0, IP1 restrict the call to the 64-row passes IP0 .. IP1-1 (default: all of them).
+template <class Cfg, class F, int IP0 = 0, int IP1 = Cfg::TM / 2>
 __device__ __forceinline__ void store_tile_bf16_transposed(char *smem, int wave, int lane, int row0, int col0,
                                                            int row_limit, int col_limit, bf16_t *__restrict__ dst,
                                                            long ld, F value)
@@ -593,7 +595,7 @@ __device__ __forceinline__ void store_tile_bf16_transposed(char *smem, int wave,
     char *stage = smem + wave * (Cfg::WTN * CS);
     __syncthreads();
 #pragma unroll
-    for (int ip = 0; ip < Cfg::TM / 2; ++ip) {
+    for (int ip = IP0; ip < IP1; ++ip) {
 #pragma unroll
         for (int ii = 0; ii < 2; ++ii) {
             const int i = ip * 2 + ii;
