@@ -118,3 +118,56 @@ def test_frozen_unembedding_unsupported_rank_and_empty_batch(gpu):
     g = h.distill_loss_bwd(H0, X0, T0, want_dU=True)
     torch.cuda.synchronize()
     assert float(g["dW"].abs().max()) == 0.0 and float(g["dU"].abs().max()) == 0.0
+
+
+def test_headline_shape_on_sampled_positions(gpu, oracle):
+    """d, V, n, r of the headline workload (two chunks of head rows, 125 vocabulary tiles, K = 4096) on its
+    first 2048 positions; loss and gradients against the oracle on 8 sampled positions, as in the
+    full-size tests of the training loss (the unembedding is frozen: dU is not asked for)."""
+    import torch
+    full = synth.CONFIGS["head_7b"]
+    cfg = full.with_(T=2048)
+    print(f"[distill] generating {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    TZ = synth.teacher_logits(cfg)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    H = gpu.to_device(inp["H"], cfg.dtype)
+    X = torch.from_numpy(inp["X"]).cuda()
+    tz = gpu.to_device(TZ, cfg.dtype)
+    beta, disc, scale = 0.9, 0.8, 1.0 / cfg.T
+    print("[distill] running on the GPU", flush=True)
+    loss = h.distill_loss_fwd(H, X, tz, beta, disc)
+    grads = h.distill_loss_bwd(H, X, tz, None, scale=scale)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(loss).all())
+    sel = synth.position_subset(cfg.T, 8)
+    print(f"[distill] oracle on positions {sel.tolist()}", flush=True)
+    args = (inp["H"][sel], inp["W"], inp["U"], inp["G"], inp["X"][sel], TZ[sel])
+    ref = oracle.distill_loss_fwd(*args, beta=beta, disc=disc)
+    err = np.abs(loss.cpu().numpy()[sel] - ref).max()
+    print(f"  loss max abs err {err:.3e} (mean loss {ref.mean():.3f})", flush=True)
+    assert err <= LOSS_ATOL
+    rg = oracle.distill_loss_bwd(*args, beta=beta, disc=disc, dloss=np.full(len(sel), scale), want=("dH", "dW", "dG"))
+    e = rel_fro(grads["dH"][torch.from_numpy(sel).cuda()].cpu().numpy(), rg["dH"])
+    print(f"  dH rows rel fro {e:.3e}", flush=True)
+    assert e <= GRAD_REL_FRO
+    # weight gradients: a GPU call on exactly these positions
+    Hs, Xs, tzs = gpu.to_device(inp["H"][sel], cfg.dtype), torch.from_numpy(inp["X"][sel]).cuda(), gpu.to_device(TZ[sel], cfg.dtype)
+    h.distill_loss_fwd(Hs, Xs, tzs, beta, disc)
+    g = h.distill_loss_bwd(Hs, Xs, tzs, None, scale=scale)
+    torch.cuda.synchronize()
+    for k in ("dW", "dG", "dH"):
+        e = rel_fro(g[k].cpu().numpy(), rg[k])
+        print(f"  subset {k} rel fro {e:.3e}", flush=True)
+        assert e <= GRAD_REL_FRO, k
+    # the batch gradient is the sum of the gradients of its halves
+    half = cfg.T // 2
+    tot = None
+    for lo, hi in ((0, half), (half, cfg.T)):
+        h.distill_loss_fwd(H[lo:hi].contiguous(), X[lo:hi].contiguous(), tz[lo:hi].contiguous(), beta, disc)
+        gh = h.distill_loss_bwd(H[lo:hi].contiguous(), X[lo:hi].contiguous(), tz[lo:hi].contiguous(), None, scale=scale)
+        torch.cuda.synchronize()
+        tot = gh["dW"].clone() if tot is None else tot + gh["dW"]
+    rel = float((tot - grads["dW"]).double().norm() / grads["dW"].double().norm())
+    print(f"  dW: |full - (first half + second half)| / |full| = {rel:.3e}", flush=True)
+    assert rel <= 2e-3
