@@ -130,3 +130,17 @@ def test_draft_boundaries(gpu):
     top = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
     a, tok, _ = h.draft_sample(H, torch.full((4, 3), top, device="cuda"))
     assert (a.cpu().numpy() == cfg.r - 1).all() and (tok.cpu().numpy() == cfg.V - 1).all()
+
+
+def test_tiny_workload_against_stored_reference(gpu):
+    """The same numbers the oracle wrote to tests/golden/tiny_reference.txt (see make_golden.py there)."""
+    from tests.test_oracle_pins import read_golden
+    vals = read_golden()
+    cfg = synth.CONFIGS["tiny"]
+    inp = synth.make_inputs(cfg)
+    loss, grads = run_loss(gpu, cfg, inp, dloss=np.full(cfg.T, 1.0 / cfg.T, dtype=np.float32))
+    for t in range(8):
+        assert abs(loss[t] - vals[f"loss {t}"]) <= LOSS_ATOL
+    assert abs(loss.mean() - vals["mean_loss"]) <= LOSS_ATOL
+    for k in ("dH", "dW", "dU", "dG"):
+        assert abs(np.linalg.norm(grads[k].ravel()) / vals[f"norm_{k}"] - 1.0) <= GRAD_REL_FRO

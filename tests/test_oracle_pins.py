@@ -601,3 +601,44 @@ def test_distill_dropped_token(oracle):
     # same as a two-token head
     np.testing.assert_allclose(loss, oracle.distill_loss_fwd(H, W[:2].copy(), U, G, X[:, :2].copy(), TZ[:, :2].copy()),
                                rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# stored reference values (written by tests/golden/make_golden.py from the oracle alone)
+# ---------------------------------------------------------------------------
+
+def read_golden():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_reference.txt")
+    vals = {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        parts = line.split()
+        vals[" ".join(parts[:-1])] = float(parts[-1])
+    return vals
+
+
+def test_oracle_reproduces_the_stored_tiny_workload(oracle):
+    vals = read_golden()
+    cfg = synth.CONFIGS["tiny"]
+    inp = synth.make_inputs(cfg)
+    args = (inp["H"], inp["W"], inp["U"], inp["G"], inp["X"])
+    loss = oracle.loss_fwd(*args)
+    for t in range(8):
+        np.testing.assert_allclose(loss[t], vals[f"loss {t}"], rtol=1e-13)
+    np.testing.assert_allclose(loss.mean(), vals["mean_loss"], rtol=1e-13)
+    # at the prescribed initialisation the loss sits near n log V (checked as a closed form elsewhere)
+    assert abs(vals["mean_loss"] - cfg.n * np.log(cfg.V)) < 0.6
+    g = oracle.loss_bwd(*args, np.full(cfg.T, 1.0 / cfg.T))
+    for k in ("dH", "dW", "dU", "dG"):
+        np.testing.assert_allclose(np.linalg.norm(g[k].ravel()), vals[f"norm_{k}"], rtol=1e-11)
+
+
+def test_zero_weights_closed_form(oracle):
+    # all logits zero: every factor is uniform, every expert equal, so loss = n log V exactly
+    H, W, U, G, X = small_problem()
+    loss = oracle.loss_fwd(H, np.zeros_like(W), U, G, X)
+    np.testing.assert_allclose(loss, X.shape[1] * np.log(U.shape[0]), rtol=1e-14)
+    loss = oracle.loss_fwd(H, W, np.zeros_like(U), G, X)
+    np.testing.assert_allclose(loss, X.shape[1] * np.log(U.shape[0]), rtol=1e-14)
