@@ -37,6 +37,10 @@ CASES = [
     (synth.HeadConfig("mfma_chunked", T=200, d=64, V=515, n=2, r=4), 2),     # one tile of rows per chunk
     (synth.HeadConfig("mfma_one_position", T=1, d=64, V=300, n=1, r=1), 0),
     (synth.HeadConfig("mfma_wide_rank", T=40, d=64, V=260, n=2, r=33), 0),
+    # the limits of the interface: vocabulary below one tile and not a multiple of 8, maximal rank, maximal n
+    (synth.HeadConfig("mfma_tiny_vocab", T=300, d=64, V=5, n=2, r=2, targets="uniform"), 0),
+    (synth.HeadConfig("mfma_max_rank", T=9, d=64, V=70, n=1, r=64, targets="uniform"), 0),
+    (synth.HeadConfig("mfma_max_heads", T=5, d=64, V=70, n=64, r=1, targets="uniform"), 0),
 ]
 
 
@@ -50,12 +54,34 @@ def test_loss_and_gradients(gpu, oracle, cfg, flags):
     ref = oracle.loss_fwd(inp["H"], inp["W"], inp["U"], inp["G"], inp["X"])
     err = np.abs(loss - ref).max()
     print(f"  loss max abs err {err:.3e}", flush=True)
-    assert err <= LOSS_ATOL
+    # The log-normalisers come from logits of y rounded to bf16 (rms error about 1.1e-3 per logit); over a
+    # vocabulary of hundreds or more the softmax weights average that down, over five tokens they do not, and
+    # the largest of the few thousand logit errors of that case (4 to 5 sigma, two factors per position) shows.
+    # The loss is a sum over the n factors, each with its own log-normaliser: the bound is stated for the
+    # workloads' n <= 4 and grows with n beyond that.
+    assert err <= (LOSS_ATOL if cfg.V >= 64 else 1e-2) * max(1.0, cfg.n / 4)
     gref = oracle.loss_bwd(inp["H"], inp["W"], inp["U"], inp["G"], inp["X"], dloss)
     for k, v in gref.items():
+        if k == "dG" and cfg.r == 1:
+            # one expert: the gate weight is the constant 1 and its gradient vanishes identically
+            assert np.abs(v).max() <= 1e-12 and np.abs(grads[k]).max() <= 1e-5
+            continue
         e = rel_fro(grads[k], v)
         print(f"  {k} rel fro {e:.3e}", flush=True)
         assert e <= GRAD_REL_FRO, (k, e)
+
+
+def test_single_token_vocabulary(gpu):
+    """V = 1: every factor is the constant 1, so the loss is zero and the heads have no gradient.  The
+    target logit (fp32 from y = hi + lo) and the log-normaliser (the same single logit from bf16 y) differ by
+    the rounding of y, so the loss is zero to the tiny-vocabulary bound of the test above and the gate sees a
+    gradient of that size."""
+    cfg = synth.HeadConfig("mfma_v1", T=70, d=64, V=1, n=2, r=3, targets="uniform")
+    inp = synth.make_inputs(cfg)
+    loss, grads = run_loss(gpu, cfg, inp)
+    assert np.abs(loss).max() <= 1e-2
+    assert np.abs(grads["dW"]).max() == 0.0 and np.abs(grads["dU"]).max() == 0.0
+    assert np.abs(grads["dH"]).max() <= 2e-2 and np.abs(grads["dG"]).max() <= 2e-1
 
 
 def test_matches_plain_path_and_frozen_unembedding(gpu):
