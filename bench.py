@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0
 # there report null.
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
-    ("head_7b", "gemm_z_stats"): (253.510 + 1.292) * GIB,
-    ("head_7b", "gemm_z_dz"): (14.981 + 1.953) * GIB,
+    ("head_7b", "gemm_z_stats"): (205.024 + 1.284) * GIB,
+    ("head_7b", "gemm_z_dz"): (12.046 + 3.906) * GIB,
 }
 
 
@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per two threads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
+    ap.add_argument("--no-modes", action="store_true", help="loss workloads: skip the forward-only and frozen-unembedding timings")
     ap.add_argument("--no-draft", action="store_true", help="loss workloads: skip the appended draft-step measurements")
     return ap.parse_args()
 
@@ -314,10 +315,11 @@ def bench_loss(args):
         return (time.perf_counter() - t0) / args.steps
 
     fwd_flops = 2.0 * cfg.n * cfg.r * cfg.d * (cfg.d + cfg.V) * cfg.T
-    t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
-    out["forward_only"] = {"ms_per_step": t_fwd * 1e3, "tokens_per_s": cfg.T / t_fwd,
-                           "model_tflops": fwd_flops / t_fwd / 1e12}
-    if not args.frozen_u:
+    if not args.no_modes:
+        t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
+        out["forward_only"] = {"ms_per_step": t_fwd * 1e3, "tokens_per_s": cfg.T / t_fwd,
+                               "model_tflops": fwd_flops / t_fwd / 1e12}
+    if not args.frozen_u and not args.no_modes:
         def frozen_step():
             binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
             binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, None, dG, ws, stream)
