@@ -143,3 +143,45 @@ def test_draft_boundaries(gpu):
     top = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
     a, tok, _ = h.draft_sample(H, torch.full((4, 3), top, device="cuda"))
     assert (a.cpu().numpy() == cfg.r - 1).all() and (tok.cpu().numpy() == cfg.V - 1).all()
+
+
+def test_loss_step_replays_from_a_hip_graph(gpu):
+    """The calls only enqueue kernels on the stream they are given (no allocation, no memset nodes), so a
+    training step can be captured once and replayed: every replay must reproduce the eager result."""
+    import torch
+    from paper_2410_17765_amd import binding
+    cfg = synth.HeadConfig("mfma_graph", T=520, d=128, V=1000, n=2, r=4)
+    inp = synth.make_inputs(cfg)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=2)        # several chunks in the backward pass
+    H = gpu.to_device(inp["H"], "bf16")
+    X = torch.from_numpy(inp["X"]).cuda()
+    ds = h.desc(cfg.T)
+    dev = H.device
+    ctx = torch.empty(binding.cp_head_ctx_bytes(ds), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD),
+                         binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_BWD)), dtype=torch.uint8, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = [torch.empty(cfg.T, **f32), torch.empty((cfg.T, cfg.d), **f32), torch.empty((cfg.n, cfg.r, cfg.d, cfg.d), **f32),
+           torch.empty((cfg.V, cfg.d), **f32), torch.empty((cfg.r, cfg.d), **f32)]
+
+    def step(stream):
+        binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, out[0], ctx, ws, stream)
+        binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, 1.0 / cfg.T, ctx, out[1], out[2], out[3], out[4], ws, stream)
+
+    step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ref = [o.clone() for o in out]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(side.cuda_stream)
+    for _ in range(3):
+        for o in out:
+            o.fill_(float("nan"))
+        ctx.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, r in zip(out, ref):
+            assert torch.equal(o, r)
