@@ -1,4 +1,4 @@
-"""Convenience holder of device buffers for the three C-ABI calls.
+"""Convenience holders of device buffers for the C-ABI calls.
 
 Only memory management lives here (torch tensors on ``cuda:0`` for inputs,
 outputs, ctx and workspace); every computation is a call through ``binding``.
