@@ -185,3 +185,27 @@ def test_loss_step_replays_from_a_hip_graph(gpu):
         torch.cuda.synchronize()
         for o, r in zip(out, ref):
             assert torch.equal(o, r)
+
+
+def test_optional_gradient_outputs(gpu):
+    """dW, dU and dG may each be NULL: the remaining outputs are unchanged."""
+    import torch
+    from paper_2410_17765_amd import binding
+    cfg = synth.HeadConfig("mfma_optional", T=300, d=64, V=515, n=2, r=3)
+    inp = synth.make_inputs(cfg)
+    for flags in (0, binding.FORCE_GENERIC):
+        h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=flags)
+        H = gpu.to_device(inp["H"], "bf16")
+        X = torch.from_numpy(inp["X"]).cuda()
+        h.loss_fwd(H, X)
+        full = h.loss_bwd(H, X)
+        ds = h.desc(cfg.T)
+        ws = torch.empty(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_BWD), dtype=torch.uint8, device="cuda")
+        dH = torch.full_like(full["dH"], float("nan"))
+        binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, 1.0, h._ctx, dH, None, None, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(dH, full["dH"]), flags
+        dW = torch.full_like(full["dW"], float("nan"))
+        binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, 1.0, h._ctx, dH, dW, None, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(dW, full["dW"]), flags
