@@ -172,7 +172,6 @@ int cp_head_first_token_logprob(const cp_head_desc *desc,
  * needs no expert draw: uniforms[B,n] fp32 in [0,1), one per token; inverse-CDF convention and
  * the bf16 rounding of y as in cp_head_draft_sample.  Outputs: tokens[B,n] int32, logq[B] fp32
  * (may be NULL) = joint log-probability of the drawn tuple.
- * Matrix-core path only (bf16, d a multiple of 64): other shapes return CP_HEAD_ERR_UNSUPPORTED.
  */
 int cp_head_draft_sample_sequential(const cp_head_desc *desc,
                                     const void *H, const void *W, const void *U, const void *G,

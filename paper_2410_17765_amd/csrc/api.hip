@@ -66,7 +66,7 @@ size_t workspace_need(const cp_head_desc &ds, int op)
         return distill_supported(ds) ? distill_workspace_bytes(ds, op) : 256;
     if (use_fast_path(ds)) return fast_workspace_bytes(ds, op);
     if (op == CP_HEAD_OP_FIRST_TOKEN) return generic_first_token_workspace_bytes(ds);
-    if (op == CP_HEAD_OP_DRAFT_SEQUENTIAL) return 256;   // not served on the plain path
+    if (op == CP_HEAD_OP_DRAFT_SEQUENTIAL) return generic_workspace_bytes(ds, CP_HEAD_OP_DRAFT);   // same buffers
     return generic_workspace_bytes(ds, op);
 }
 
@@ -217,9 +217,10 @@ int cp_head_draft_sample_sequential(const cp_head_desc *desc, const void *H, con
     if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
     if (desc->T > 0 && (!H || !uniforms || !tokens)) return CP_HEAD_ERR_INVALID_ARG;
     if (!workspace || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
-    if (!use_fast_path(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DRAFT_SEQUENTIAL)) return CP_HEAD_ERR_WORKSPACE;
-    return fast_draft_sequential(*desc, H, W, U, G, uniforms, tokens, logq, workspace, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_fast_path(*desc)) return fast_draft_sequential(*desc, H, W, U, G, uniforms, tokens, logq, workspace, st);
+    return generic_draft_sequential(*desc, H, W, U, G, uniforms, tokens, logq, workspace, st);
 }
 
 int cp_head_aux_balance(const cp_head_desc *desc, const void *H, const void *G, int64_t *counts, float *laux,

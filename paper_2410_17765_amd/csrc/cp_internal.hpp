@@ -83,6 +83,8 @@ int generic_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const
 int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                   const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 
+int generic_draft_sequential(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                             const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 size_t generic_first_token_workspace_bytes(const cp_head_desc &ds);
 int generic_first_token(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                         float *logp, void *ws, hipStream_t st);

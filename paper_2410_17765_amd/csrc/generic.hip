@@ -345,6 +345,84 @@ __global__ void __launch_bounds__(kWave) k_logq_generic(int V, int n, int r, con
     if (lane == 0) logq[b] = mx + logf(sum);
 }
 
+// The paper's sequential scheme (eq. 11-13) from stored logits, one block per row b of the batch: for every
+// token the conditional sum_a qhat_a P^(s)(. | a) is scanned in vocabulary order (thread i owns a contiguous
+// run of tokens, run sums in fp64), then the expert log-weights take the drawn token's log-probabilities.
+__global__ void __launch_bounds__(kBlock) k_sample_sequential_generic(int V, int n, int r, const float *__restrict__ z,
+                                                                      const float *__restrict__ lse,
+                                                                      const float *__restrict__ logw,
+                                                                      const float *__restrict__ uniforms,
+                                                                      int32_t *__restrict__ tokens,
+                                                                      float *__restrict__ logq)
+{
+    __shared__ double seg_sum[kBlock];
+    __shared__ double base;
+    __shared__ float q_s[64], qh_s[64];
+    __shared__ int chosen, tok_sh;
+    const size_t b = blockIdx.x;
+    const int tid = threadIdx.x;
+    if (tid < r) q_s[tid] = logw[b * r + tid];
+    __syncthreads();
+    for (int s = 0; s < n; ++s) {
+        const size_t row0 = (b * n + s) * r;
+        const double u = (double)uniforms[b * n + s];
+        if (tid == 0) {
+            float mx = q_s[0];
+            for (int a = 1; a < r; ++a) mx = fmaxf(mx, q_s[a]);
+            float sm = 0.f;
+            for (int a = 0; a < r; ++a) sm += expf(q_s[a] - mx);
+            const float qn = mx + logf(sm);
+            for (int a = 0; a < r; ++a) qh_s[a] = expf(q_s[a] - qn);
+        }
+        __syncthreads();
+        const int seg = (V + kBlock - 1) / kBlock;
+        const int lo = min(V, tid * seg), hi = min(V, lo + seg);
+        double sum = 0.0;
+        for (int v = lo; v < hi; ++v) {
+            float p = 0.f;
+            for (int a = 0; a < r; ++a) p += qh_s[a] * expf(z[(row0 + a) * V + v] - lse[row0 + a]);
+            sum += (double)p;
+        }
+        seg_sum[tid] = sum;
+        __syncthreads();
+        if (tid == 0) {
+            double c = 0.0;
+            int pick = -1;
+            for (int i = 0; i < kBlock; ++i) {
+                if (c + seg_sum[i] > u) { pick = i; break; }
+                c += seg_sum[i];
+            }
+            chosen = pick;
+            base = c;
+            if (pick < 0) tok_sh = V - 1;
+        }
+        __syncthreads();
+        if (tid == chosen) {
+            double c = base;
+            int tok = hi - 1;
+            for (int v = lo; v < hi; ++v) {
+                float p = 0.f;
+                for (int a = 0; a < r; ++a) p += qh_s[a] * expf(z[(row0 + a) * V + v] - lse[row0 + a]);
+                c += (double)p;
+                if (c > u) { tok = v; break; }
+            }
+            tok_sh = tok;
+        }
+        __syncthreads();
+        const int tok = tok_sh;
+        if (tid == 0) tokens[b * n + s] = tok;
+        if (tid < r) q_s[tid] += z[(row0 + tid) * V + tok] - lse[row0 + tid];
+        __syncthreads();
+    }
+    if (logq && tid == 0) {
+        float mx = q_s[0];
+        for (int a = 1; a < r; ++a) mx = fmaxf(mx, q_s[a]);
+        float sm = 0.f;
+        for (int a = 0; a < r; ++a) sm += expf(q_s[a] - mx);
+        logq[b] = mx + logf(sm);
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // next-token distribution (eq. 11) and the balancing statistic (eq. 10)
 // ------------------------------------------------------------------------------------------
@@ -518,7 +596,35 @@ int draft_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, co
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
+template <typename TIn>
+int draft_sequential_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G,
+                       const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st)
+{
+    const GenericWs g = generic_ws(ds, CP_HEAD_OP_DRAFT);
+    const size_t B = (size_t)ds.T, M = B * ds.n * ds.r;
+    float *logw = at<float>(ws, g.logw), *w = at<float>(ws, g.w), *Y = at<float>(ws, g.Y);
+    float *z = at<float>(ws, g.z), *lse = at<float>(ws, g.lse);
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    const int round_y = ds.dtype == CP_HEAD_BF16 ? 1 : 0;
+    k_gate<TIn><<<(unsigned)B, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
+    k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, Y, round_y);
+    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, nullptr, lse, nullptr, z);
+    k_sample_sequential_generic<<<(unsigned)B, kBlock, 0, st>>>(ds.V, ds.n, ds.r, z, lse, logw, uniforms, tokens, logq);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
 }  // namespace
+
+int generic_draft_sequential(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                             const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (ds.dtype == CP_HEAD_FP32)
+        return draft_sequential_t<float>(ds, (const float *)H, (const float *)W, (const float *)U, (const float *)G,
+                                         uniforms, tokens, logq, ws, st);
+    return draft_sequential_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G,
+                                      uniforms, tokens, logq, ws, st);
+}
 
 size_t generic_workspace_bytes(const cp_head_desc &ds, int op) { return generic_ws(ds, op).total; }
 

@@ -117,7 +117,7 @@ def check_draft(oracle, H, W, U, G, u, alpha_gpu, tokens_gpu, logq_gpu, round_y,
     return stats
 
 
-def check_sequential(oracle, H, W, U, G, u, tokens_gpu, logq_gpu, logq_atol=1e-3):
+def check_sequential(oracle, H, W, U, G, u, tokens_gpu, logq_gpu, logq_atol=1e-3, round_y=True):
     """Compare one call of the sequential sampler (one uniform per token, u[B,n]) with the oracle.
     Every draw must lie inside the CDF band of the oracle's conditional under the prefix the GPU drew,
     and logq must be the oracle's joint log-probability of the drawn tuple; a row that fails either is
@@ -125,8 +125,8 @@ def check_sequential(oracle, H, W, U, G, u, tokens_gpu, logq_gpu, logq_atol=1e-3
     Returns match statistics."""
     B, n = tokens_gpu.shape
     V = U.shape[0]
-    tok_o, _, cdf = oracle.draft_sample_sequential(H, W, U, G, u, round_y=True, want_cdf=True)
-    lq_err = np.abs(-oracle.loss_fwd(H, W, U, G, tokens_gpu.astype(np.int32), round_y=True) - logq_gpu)
+    tok_o, _, cdf = oracle.draft_sample_sequential(H, W, U, G, u, round_y=round_y, want_cdf=True)
+    lq_err = np.abs(-oracle.loss_fwd(H, W, U, G, tokens_gpu.astype(np.int32), round_y=round_y) - logq_gpu)
     stats = {"tokens_exact": 0, "tokens_total": B * n, "tie_rows": 0}
     for b in range(B):
         ok = lq_err[b] <= logq_atol
@@ -136,11 +136,12 @@ def check_sequential(oracle, H, W, U, G, u, tokens_gpu, logq_gpu, logq_atol=1e-3
             if (tokens_gpu[b, :s] == tok_o[b, :s]).all():
                 c = cdf[b, s]
             else:   # an admissible other draw earlier in the row: the oracle's conditional under that prefix
-                c = np.cumsum(oracle.sequential_conditional(H, W, U, G, b, list(tokens_gpu[b, :s]), round_y=True))
+                c = np.cumsum(oracle.sequential_conditional(H, W, U, G, b, list(tokens_gpu[b, :s]), round_y=round_y))
             ok = ok and band_valid(c, v, float(u[b, s]))
             stats["tokens_exact"] += int(v == tok_o[b, s])
         if ok:
             continue
+        assert round_y, ("row off", b, tokens_gpu[b], tok_o[b], lq_err[b])
         args = (H[b:b + 1], W, U, G)
         y = oracle.draft_sample(*args, np.zeros((1, 1 + n)), want_y=True)[-1]                     # [1,n,r,d]
         explained = False

@@ -88,6 +88,13 @@ SEQ_CASES = [
 ]
 
 
+SEQ_CASES += [
+    # the plain path: fp32 storage with odd sizes, and bf16 storage forced onto it (flag 1)
+    synth.HeadConfig("seq_plain_fp32", T=7, d=50, V=203, n=3, r=3, dtype="fp32", targets="uniform", u_scale=4.0),
+    synth.HeadConfig("seq_plain_bf16", T=6, d=64, V=300, n=2, r=5, targets="uniform", u_scale=4.0),
+]
+
+
 @pytest.mark.parametrize("cfg", SEQ_CASES, ids=lambda c: c.name)
 def test_sequential_sampling(gpu, oracle, cfg):
     import torch
@@ -95,20 +102,19 @@ def test_sequential_sampling(gpu, oracle, cfg):
     inp = synth.make_inputs(cfg)
     H, W, U, G = inp["H"], inp["W"], inp["U"], inp["G"]
     u = seq_uniforms(cfg.T, cfg.n)
-    h = gpu.CpHead(W, U, G, dtype=cfg.dtype)
+    h = gpu.CpHead(W, U, G, dtype=cfg.dtype, flags=1 if cfg.name.startswith("seq_plain") else 0)
     tokens, logq = h.draft_sample_sequential(gpu.to_device(H, cfg.dtype), torch.from_numpy(u).cuda())
     torch.cuda.synchronize()
     tokens, logq = tokens.cpu().numpy(), logq.cpu().numpy()
-    stats = check_sequential(oracle, H, W, U, G, u, tokens, logq)
+    stats = check_sequential(oracle, H, W, U, G, u, tokens, logq, round_y=(cfg.dtype == "bf16"))
     print(f"  {stats}", flush=True)
     assert stats["tie_rows"] <= 1
     # the CDF steps at these sizes are far wider than the band
     assert stats["tokens_exact"] >= (cfg.T - stats["tie_rows"]) * cfg.n
 
 
-def test_sequential_boundaries_and_plain_path(gpu):
+def test_sequential_boundaries(gpu):
     import torch
-    from paper_2410_17765_amd import binding
     cfg = synth.HeadConfig("seq_edge", T=4, d=64, V=300, n=2, r=3, targets="uniform")
     inp = synth.make_inputs(cfg)
     h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16")
@@ -118,10 +124,11 @@ def test_sequential_boundaries_and_plain_path(gpu):
     top = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
     tok, _ = h.draft_sample_sequential(H, torch.full((4, 2), top, device="cuda"))
     assert (tok.cpu().numpy() == cfg.V - 1).all()
-    # the plain path does not serve this call and says so
-    hp = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=1)
-    with pytest.raises(binding.CpHeadError):
-        hp.draft_sample_sequential(H, torch.zeros((4, 2), device="cuda"))
+    hp = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=1)       # the plain path
+    tok, _ = hp.draft_sample_sequential(H, torch.zeros((4, 2), device="cuda"))
+    assert (tok.cpu().numpy() == 0).all()
+    tok, _ = hp.draft_sample_sequential(H, torch.full((4, 2), top, device="cuda"))
+    assert (tok.cpu().numpy() == cfg.V - 1).all()
 
 
 def test_sequential_and_expert_first_draw_agree_for_one_expert(gpu):

@@ -117,10 +117,10 @@ def test_new_calls_reject_bad_arguments_before_launch(lib):
         assert lib.cp_head_first_token_logprob(*bad) == -1
         bad = list(args); bad[7] = need - 1
         assert lib.cp_head_first_token_logprob(*bad) == -3
-    # sequential sampler and full heads: matrix-core path only
-    args = [ctypes.byref(fp), p, p, p, p, p, p, p, p, 1 << 20, None]
-    assert lib.cp_head_draft_sample_sequential(*args) == -2
-    args[0] = ctypes.byref(bf); args[9] = 0
+    # sequential sampler: both paths; full heads: matrix-core path only
+    args = [ctypes.byref(fp), p, p, p, p, p, p, p, p, 0, None]
+    assert lib.cp_head_draft_sample_sequential(*args) == -3
+    args[0] = ctypes.byref(bf)
     assert lib.cp_head_draft_sample_sequential(*args) == -3
     args[5] = None                                           # uniforms
     assert lib.cp_head_draft_sample_sequential(*args) == -1
