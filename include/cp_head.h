@@ -201,7 +201,6 @@ int cp_head_aux_balance(const cp_head_desc *desc, const void *H, const void *G,
  * scale as in cp_head_loss_bwd); dH[T,d] (required), dF[n,r,V,d] and dG[r,d] (either may be NULL)
  * are fp32 and overwritten.  Logits are recomputed head by head for a bounded chunk of positions;
  * nothing of size T*n*r*V is ever stored.
- * Matrix-core path only (bf16, d a multiple of 64): other shapes return CP_HEAD_ERR_UNSUPPORTED.
  */
 int cp_head_full_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
 int cp_head_full_loss_fwd(const cp_head_desc *desc,

@@ -60,8 +60,8 @@ bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) 
 size_t workspace_need(const cp_head_desc &ds, int op)
 {
     if (op == CP_HEAD_OP_AUX_BALANCE) return 256;   // none needed; a token size keeps the calling pattern uniform
-    if (op == CP_HEAD_OP_FULL_LOSS_FWD || op == CP_HEAD_OP_FULL_LOSS_BWD)   // not served on the plain path
-        return use_fast_path(ds) ? fast_workspace_bytes(ds, op) : 256;
+    if (op == CP_HEAD_OP_FULL_LOSS_FWD || op == CP_HEAD_OP_FULL_LOSS_BWD)
+        return use_fast_path(ds) ? fast_workspace_bytes(ds, op) : generic_full_workspace_bytes(ds);
     if (op == CP_HEAD_OP_DISTILL_FWD || op == CP_HEAD_OP_DISTILL_BWD)
         return distill_supported(ds) ? distill_workspace_bytes(ds, op) : 256;
     if (use_fast_path(ds)) return fast_workspace_bytes(ds, op);
@@ -252,9 +252,10 @@ int cp_head_full_loss_fwd(const cp_head_desc *desc, const void *H, const void *F
     if (!F || !G) return CP_HEAD_ERR_INVALID_ARG;
     if (desc->T > 0 && (!H || !X || !loss)) return CP_HEAD_ERR_INVALID_ARG;
     if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
-    if (!use_fast_path(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_FULL_LOSS_FWD)) return CP_HEAD_ERR_WORKSPACE;
-    return fast_full_loss_fwd(*desc, H, F, G, X, loss, ctx, workspace, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_fast_path(*desc)) return fast_full_loss_fwd(*desc, H, F, G, X, loss, ctx, workspace, st);
+    return generic_full_loss_fwd(*desc, H, F, G, X, loss, ctx, workspace, st);
 }
 
 int cp_head_full_loss_bwd(const cp_head_desc *desc, const void *H, const void *F, const void *G, const int32_t *X,
@@ -266,10 +267,10 @@ int cp_head_full_loss_bwd(const cp_head_desc *desc, const void *H, const void *F
     if (!F || !G) return CP_HEAD_ERR_INVALID_ARG;
     if (desc->T > 0 && (!H || !X || !dH)) return CP_HEAD_ERR_INVALID_ARG;
     if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
-    if (!use_fast_path(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_FULL_LOSS_BWD)) return CP_HEAD_ERR_WORKSPACE;
-    return fast_full_loss_bwd(*desc, H, F, G, X, dloss, scale, ctx, dH, dF, dG, workspace,
-                              static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_fast_path(*desc)) return fast_full_loss_bwd(*desc, H, F, G, X, dloss, scale, ctx, dH, dF, dG, workspace, st);
+    return generic_full_loss_bwd(*desc, H, F, G, X, dloss, scale, ctx, dH, dF, dG, workspace, st);
 }
 
 int cp_head_distill_ctx_bytes(const cp_head_desc *desc, size_t *bytes)

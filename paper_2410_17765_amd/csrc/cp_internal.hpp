@@ -85,6 +85,12 @@ int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const vo
 
 int generic_draft_sequential(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                              const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st);
+size_t generic_full_workspace_bytes(const cp_head_desc &ds);
+int generic_full_loss_fwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
+                          float *loss, void *ctx, void *ws, hipStream_t st);
+int generic_full_loss_bwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
+                          const float *dloss, float scale, const void *ctx, float *dH, float *dF, float *dG, void *ws,
+                          hipStream_t st);
 size_t generic_first_token_workspace_bytes(const cp_head_desc &ds);
 int generic_first_token(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                         float *logp, void *ws, hipStream_t st);

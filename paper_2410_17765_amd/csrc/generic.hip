@@ -424,6 +424,102 @@ __global__ void __launch_bounds__(kBlock) k_sample_sequential_generic(int V, int
 }
 
 // ------------------------------------------------------------------------------------------
+// full heads (eq. 6 as printed): z_sa = F_sa h with one V x d matrix per (s, a); rows m = (t n + s) r + a
+// ------------------------------------------------------------------------------------------
+
+// running statistics of z = F_sa h for one head row, C = z[x] - lse; with dZ != NULL (backward) the
+// second sweep writes dz[v] = coef (softmax(z)[v] - 1[v = x]) for chunk row m - m0 instead
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_full_row_generic(int d, int V, int n, int r, size_t m0,
+                                                             const TIn *__restrict__ H, const TIn *__restrict__ F,
+                                                             const int32_t *__restrict__ X, float *__restrict__ lse_io,
+                                                             float *__restrict__ C_out,
+                                                             const float *__restrict__ gamma,
+                                                             const float *__restrict__ dloss, float scale,
+                                                             float *__restrict__ dZ)
+{
+    extern __shared__ float hs[];
+    __shared__ float red_m[kWavesPerBlock], red_l[kWavesPerBlock], red_zt;
+    const size_t mc = blockIdx.x, m = m0 + mc;
+    const int nr = n * r;
+    const size_t t = m / nr;
+    const int sa = (int)(m % nr), a = sa % r;
+    for (int k = threadIdx.x; k < d; k += kBlock) hs[k] = ld_f32(H, t * d + k);
+    if (threadIdx.x == 0) red_zt = 0.f;
+    __syncthreads();
+    const TIn *Fsa = F + (size_t)sa * V * d;
+    const int x = X[m / r];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    if (!dZ) {
+        float mx = -INFINITY, l = 0.f;
+        for (int v = wave; v < V; v += kWavesPerBlock) {
+            float p = 0.f;
+            for (int k = lane; k < d; k += kWave) p += ld_f32(Fsa, (size_t)v * d + k) * hs[k];
+            const float z = wave_sum(p);
+            if (z > mx) { l = l * expf(mx - z) + 1.f; mx = z; }
+            else l += expf(z - mx);
+            if (v == x && lane == 0) red_zt = z;
+        }
+        if (lane == 0) { red_m[wave] = mx; red_l[wave] = l; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float Mx = red_m[0];
+            for (int i = 1; i < kWavesPerBlock; ++i) Mx = fmaxf(Mx, red_m[i]);
+            float L = 0.f;
+            for (int i = 0; i < kWavesPerBlock; ++i) L += red_l[i] * expf(red_m[i] - Mx);
+            const float lse = Mx + logf(L);
+            lse_io[m] = lse;
+            C_out[m] = (x >= 0) ? red_zt - lse : 0.f;
+        }
+    } else {
+        const float up = dloss ? dloss[t] * scale : scale;
+        const float coef = up * gamma[t * r + a];
+        const float l = lse_io[m];
+        for (int v = wave; v < V; v += kWavesPerBlock) {
+            float p = 0.f;
+            for (int k = lane; k < d; k += kWave) p += ld_f32(Fsa, (size_t)v * d + k) * hs[k];
+            const float z = wave_sum(p);
+            if (lane == 0) dZ[mc * V + v] = (x < 0) ? 0.f : coef * (expf(z - l) - (v == x ? 1.f : 0.f));
+        }
+    }
+}
+
+// dF[sa,v,j] (+)= sum over the positions t0 .. t0+Tc-1 of dZ[(t - t0) nr + sa, v] H[t, j]
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_df_generic(int d, int V, int nr, size_t t0, size_t Tc,
+                                                       const TIn *__restrict__ H, const float *__restrict__ dZ,
+                                                       float *__restrict__ dF, int accumulate)
+{
+    const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= (size_t)nr * V * d) return;
+    const int j = (int)(idx % d);
+    const size_t sav = idx / d;
+    const int v = (int)(sav % V);
+    const size_t sa = sav / V;
+    float acc = accumulate ? dF[idx] : 0.f;
+    for (size_t tc = 0; tc < Tc; ++tc) acc += dZ[(tc * nr + sa) * V + v] * ld_f32(H, (t0 + tc) * d + j);
+    dF[idx] = acc;
+}
+
+// dH[t,j] = sum_{sa,v} dZ[(t - t0) nr + sa, v] F[sa,v,j] + sum_a dg[t,a] G[a,j] for the positions of the chunk
+template <typename TIn>
+__global__ void __launch_bounds__(kBlock) k_dh_full_generic(int d, int V, int nr, int r, size_t t0, size_t Tc,
+                                                            const TIn *__restrict__ F, const TIn *__restrict__ G,
+                                                            const float *__restrict__ dZ, const float *__restrict__ dg,
+                                                            float *__restrict__ dH)
+{
+    const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= Tc * d) return;
+    const size_t tc = idx / d, t = t0 + tc;
+    const int j = (int)(idx % d);
+    float acc = 0.f;
+    for (int sa = 0; sa < nr; ++sa)
+        for (int v = 0; v < V; ++v) acc += dZ[(tc * nr + sa) * V + v] * ld_f32(F, ((size_t)sa * V + v) * d + j);
+    for (int a = 0; a < r; ++a) acc += dg[t * r + a] * ld_f32(G, (size_t)a * d + j);
+    dH[t * d + j] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
 // next-token distribution (eq. 11) and the balancing statistic (eq. 10)
 // ------------------------------------------------------------------------------------------
 
@@ -742,6 +838,102 @@ int aux_balance(const cp_head_desc &ds, const void *H, const void *G, int64_t *c
     }
     k_aux_finish<<<1, kWave, 0, st>>>((size_t)ds.T, ds.r, c, laux);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+// ---- full heads on the plain path
+struct GenericFullWs {
+    size_t logw, C, dg, dZ, total;
+    size_t chunk_pos;
+};
+static GenericFullWs generic_full_ws(const cp_head_desc &ds)
+{
+    GenericFullWs g;
+    const size_t T = (size_t)ds.T, nr = (size_t)ds.n * ds.r;
+    // whole positions per chunk: at most 512 MiB of fp32 logit gradients at a time, at least one position
+    size_t pos = ((size_t)1 << 27) / ((size_t)ds.V * nr);
+    if (pos < 1) pos = 1;
+    g.chunk_pos = pos < T ? pos : (T ? T : 1);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    g.logw = take(T * ds.r * 4);
+    g.C = take(T * nr * 4);
+    g.dg = take(T * ds.r * 4);
+    g.dZ = take(g.chunk_pos * nr * ds.V * 4);
+    g.total = off;
+    return g;
+}
+size_t generic_full_workspace_bytes(const cp_head_desc &ds) { return generic_full_ws(ds).total; }
+
+template <typename TIn>
+static int full_fwd_t(const cp_head_desc &ds, const TIn *H, const TIn *F, const TIn *G, const int32_t *X, float *loss,
+                      void *ctx, void *ws, hipStream_t st)
+{
+    const CtxLayout cl = ctx_layout(ds, false);      // lse, w, gamma at the same offsets; no y is kept
+    const GenericFullWs g = generic_full_ws(ds);
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    float *logw = at<float>(ws, g.logw), *C = at<float>(ws, g.C);
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    k_gate<TIn><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
+    k_full_row_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.n, ds.r, 0, H, F, X, lse, C, nullptr, nullptr,
+                                                              0.f, nullptr);
+    k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, loss, gamma, -1.f);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+template <typename TIn>
+static int full_bwd_t(const cp_head_desc &ds, const TIn *H, const TIn *F, const TIn *G, const int32_t *X,
+                      const float *dloss, float scale, const void *ctx, float *dH, float *dF, float *dG, void *ws,
+                      hipStream_t st)
+{
+    const CtxLayout cl = ctx_layout(ds, false);
+    const GenericFullWs g = generic_full_ws(ds);
+    const size_t T = (size_t)ds.T, Tr = T * ds.r;
+    const int nr = ds.n * ds.r;
+    float *lse = const_cast<float *>(at<float>(ctx, cl.lse));
+    const float *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    float *dg = at<float>(ws, g.dg), *dZ = at<float>(ws, g.dZ);
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    k_dgate<<<blocks_for(Tr, kBlock), kBlock, 0, st>>>(Tr, ds.r, w, gamma, dloss, scale, dg);
+    int first = 1;
+    for (size_t t0 = 0; t0 < T; t0 += g.chunk_pos) {
+        const size_t Tc = (T - t0 < g.chunk_pos) ? T - t0 : g.chunk_pos;
+        k_full_row_generic<TIn><<<(unsigned)(Tc * nr), kBlock, lds, st>>>(ds.d, ds.V, ds.n, ds.r, t0 * nr, H, F, X, lse,
+                                                                          nullptr, gamma, dloss, scale, dZ);
+        k_dh_full_generic<TIn><<<blocks_for(Tc * ds.d, kBlock), kBlock, 0, st>>>(ds.d, ds.V, nr, ds.r, t0, Tc, F, G, dZ,
+                                                                                 dg, dH);
+        if (dF)
+            k_df_generic<TIn><<<blocks_for((size_t)nr * ds.V * ds.d, kBlock), kBlock, 0, st>>>(ds.d, ds.V, nr, t0, Tc, H,
+                                                                                               dZ, dF, first ? 0 : 1);
+        first = 0;
+    }
+    if (dG) k_dg_generic<TIn><<<blocks_for((size_t)ds.r * ds.d, kBlock), kBlock, 0, st>>>(T, ds.d, ds.r, H, dg, dG);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+int generic_full_loss_fwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
+                          float *loss, void *ctx, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (ds.dtype == CP_HEAD_FP32)
+        return full_fwd_t<float>(ds, (const float *)H, (const float *)F, (const float *)G, X, loss, ctx, ws, st);
+    return full_fwd_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)F, (const bf16_t *)G, X, loss, ctx, ws, st);
+}
+
+int generic_full_loss_bwd(const cp_head_desc &ds, const void *H, const void *F, const void *G, const int32_t *X,
+                          const float *dloss, float scale, const void *ctx, float *dH, float *dF, float *dG, void *ws,
+                          hipStream_t st)
+{
+    if (ds.T == 0) {
+        launch_fill_zero(dF, (size_t)ds.n * ds.r * ds.V * ds.d, st);
+        launch_fill_zero(dG, (size_t)ds.r * ds.d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (ds.dtype == CP_HEAD_FP32)
+        return full_bwd_t<float>(ds, (const float *)H, (const float *)F, (const float *)G, X, dloss, scale, ctx, dH, dF, dG,
+                                 ws, st);
+    return full_bwd_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)F, (const bf16_t *)G, X, dloss, scale, ctx, dH, dF,
+                              dG, ws, st);
 }
 
 void launch_gate(const cp_head_desc &ds, const void *H, const void *G, float *logw, float *w, hipStream_t st)

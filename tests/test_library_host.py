@@ -117,7 +117,7 @@ def test_new_calls_reject_bad_arguments_before_launch(lib):
         assert lib.cp_head_first_token_logprob(*bad) == -1
         bad = list(args); bad[7] = need - 1
         assert lib.cp_head_first_token_logprob(*bad) == -3
-    # sequential sampler: both paths; full heads: matrix-core path only
+    # sequential sampler and full heads: both paths
     args = [ctypes.byref(fp), p, p, p, p, p, p, p, p, 0, None]
     assert lib.cp_head_draft_sample_sequential(*args) == -3
     args[0] = ctypes.byref(bf)
@@ -126,10 +126,9 @@ def test_new_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cp_head_draft_sample_sequential(*args) == -1
     out = ctypes.c_size_t()
     assert lib.cp_head_full_ctx_bytes(ctypes.byref(bf), ctypes.byref(out)) == 0 and out.value >= 4 * 2 * 2 * 4
-    argsf = [ctypes.byref(fp), p, p, p, p, p, p, p, 1 << 20, None]
-    assert lib.cp_head_full_loss_fwd(*argsf) == -2
-    argsf[0] = ctypes.byref(bf); argsf[8] = 0
-    assert lib.cp_head_full_loss_fwd(*argsf) == -3
+    for ds in (fp, bf):
+        argsf = [ctypes.byref(ds), p, p, p, p, p, p, p, 0, None]
+        assert lib.cp_head_full_loss_fwd(*argsf) == -3
     argsb = [ctypes.byref(bf), p, p, p, p, None, 1.0, p, None, p, p, p, 1 << 30, None]
     assert lib.cp_head_full_loss_bwd(*argsb) == -1           # dH is required
     # fine-tuning loss: supported ranks only, beta in [0, 1], teacher logits required
