@@ -55,7 +55,8 @@ enum {
                                    matrix-core path applies (a second opinion in tests) */
     CP_HEAD_MIN_WORKSPACE = 2   /* flags bit 1: the backward pass holds logit gradients for one
                                    tile of 256 head rows at a time (least workspace, slower)
-                                   instead of its default of about 2 GiB worth of rows */
+                                   instead of its default of about 2 GiB worth of rows (0.5 GiB
+                                   on the plain path) */
 };
 
 enum {
@@ -230,9 +231,11 @@ int cp_head_full_loss_bwd(const cp_head_desc *desc,
  * cp_head_distill_ctx_bytes sizes the `ctx` shared by the two calls; workspaces are sized by
  * cp_head_workspace_bytes with CP_HEAD_OP_DISTILL_FWD / _BWD.  Backward: gradients of
  * sum_t dloss[t] * loss[t] with TZ constant; dloss/scale and the outputs as in cp_head_loss_bwd
- * (dU = NULL for the frozen unembedding of fine tuning).  No logits are stored: the mixture over the
- * experts is formed inside the tiles of two further vocabulary-sized products.
- * Served for bf16 storage, d a multiple of 64 and r in {1, 2, 4, 8}; otherwise CP_HEAD_ERR_UNSUPPORTED.
+ * (dU = NULL for the frozen unembedding of fine tuning).  Every entry of TZ must be finite, also in the
+ * rows of dropped tokens.  For bf16 storage with d a multiple of 64 and r in {1, 2, 4, 8} no logits are
+ * stored: the mixture over the experts is formed inside the tiles of two further vocabulary-sized
+ * products on the matrix cores.  Every other shape and fp32 storage run on the plain fp32 path, which
+ * keeps the fp32 logits of one chunk of rows at a time in the workspace.
  */
 int cp_head_distill_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
 int cp_head_distill_loss_fwd(const cp_head_desc *desc,

@@ -63,7 +63,7 @@ size_t workspace_need(const cp_head_desc &ds, int op)
     if (op == CP_HEAD_OP_FULL_LOSS_FWD || op == CP_HEAD_OP_FULL_LOSS_BWD)
         return use_fast_path(ds) ? fast_workspace_bytes(ds, op) : generic_full_workspace_bytes(ds);
     if (op == CP_HEAD_OP_DISTILL_FWD || op == CP_HEAD_OP_DISTILL_BWD)
-        return distill_supported(ds) ? distill_workspace_bytes(ds, op) : 256;
+        return distill_workspace_bytes(ds, op);
     if (use_fast_path(ds)) return fast_workspace_bytes(ds, op);
     if (op == CP_HEAD_OP_FIRST_TOKEN) return generic_first_token_workspace_bytes(ds);
     if (op == CP_HEAD_OP_DRAFT_SEQUENTIAL) return generic_workspace_bytes(ds, CP_HEAD_OP_DRAFT);   // same buffers
@@ -278,7 +278,6 @@ int cp_head_distill_ctx_bytes(const cp_head_desc *desc, size_t *bytes)
     if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
     const int rc = check_desc(desc);
     if (rc != CP_HEAD_OK) return rc;
-    if (!distill_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     *bytes = distill_ctx_bytes(*desc);
     return CP_HEAD_OK;
 }
@@ -293,7 +292,6 @@ int cp_head_distill_loss_fwd(const cp_head_desc *desc, const void *H, const void
     if (desc->T > 0 && (!H || !X || !TZ || !loss)) return CP_HEAD_ERR_INVALID_ARG;
     if (!(beta >= 0.f && beta <= 1.f) || !(discount >= 0.f)) return CP_HEAD_ERR_INVALID_ARG;
     if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
-    if (!distill_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DISTILL_FWD)) return CP_HEAD_ERR_WORKSPACE;
     return distill_loss_fwd(*desc, H, W, U, G, X, TZ, beta, discount, loss, ctx, workspace,
                             static_cast<hipStream_t>(stream));
@@ -309,7 +307,6 @@ int cp_head_distill_loss_bwd(const cp_head_desc *desc, const void *H, const void
     if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
     if (desc->T > 0 && (!H || !X || !TZ || !dH)) return CP_HEAD_ERR_INVALID_ARG;
     if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
-    if (!distill_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DISTILL_BWD)) return CP_HEAD_ERR_WORKSPACE;
     return distill_loss_bwd(*desc, H, W, U, G, X, TZ, dloss, scale, ctx, dH, dW, dU, dG, workspace,
                             static_cast<hipStream_t>(stream));

@@ -83,6 +83,24 @@ int generic_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const
 int generic_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                   const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 
+// Pieces of the plain path that the fine-tuning loss builds on.  generic_fwd_rows runs the per-row part of the
+// training loss's forward pass (gate, y, lse, C) into ctx / ws laid out as for generic_loss_fwd;
+// generic_logits_rows writes the fp32 logits of the rows [m0, m0 + Mc) to z[Mc, V]; generic_bwd_from_dz runs the
+// training loss's backward pass below the logit gradients, which `fn` produces one chunk of
+// generic_bwd_chunk_rows() rows (a multiple of r) at a time.  ws is laid out as for generic_loss_bwd.
+struct GenericFwdBuffers {
+    float *lse, *w, *gamma, *Y, *logw, *C;
+};
+int generic_fwd_rows(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, void *ctx, void *ws, GenericFwdBuffers *out, hipStream_t st);
+void generic_logits_rows(const cp_head_desc &ds, const void *U, const float *Y, size_t m0, size_t Mc, float *z,
+                         hipStream_t st);
+size_t generic_bwd_chunk_rows(const cp_head_desc &ds);
+typedef void (*GenericDzLaunch)(void *user, size_t m0, size_t Mc, float *dZ, hipStream_t st);
+int generic_bwd_from_dz(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                        const float *Y, const float *dg, float *dH, float *dW, float *dU, float *dG, void *ws,
+                        GenericDzLaunch fn, void *user, hipStream_t st);
+
 int generic_draft_sequential(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                              const float *uniforms, int32_t *tokens, float *logq, void *ws, hipStream_t st);
 size_t generic_full_workspace_bytes(const cp_head_desc &ds);
@@ -158,7 +176,7 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *H, const void *F, con
                        hipStream_t st);
 
 // ---------------------------------------------------------------- fine-tuning (distillation) loss
-bool distill_supported(const cp_head_desc &ds);
+// matrix-core path for bf16, d % 64 == 0, r in {1, 2, 4, 8}; the plain path otherwise
 size_t distill_ctx_bytes(const cp_head_desc &ds);
 size_t distill_workspace_bytes(const cp_head_desc &ds, int op);
 int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,

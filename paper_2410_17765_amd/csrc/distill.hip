@@ -1,4 +1,5 @@
-// Head-only fine-tuning loss ("Fine tuning", eq. 14 and the discounted sum after it) on the matrix-core path.
+// Head-only fine-tuning loss ("Fine tuning", eq. 14 and the discounted sum after it): the matrix-core path
+// (bf16, d % 64 == 0, r in {1, 2, 4, 8}) and, at the end of the file, the plain fp32 path for every other shape.
 //
 // Reading of the paper's open points (the same as the CPU checker's):
 //   p^d_k[v] = sum_a qhat^(k)_a P^(k)(v | a),  qhat^(k) = softmax_a(log w_a + sum_{j<k} C_ja)   (eq. 13, true prefix)
@@ -31,15 +32,16 @@ constexpr int kBlock = 256;
 // small kernels
 // ------------------------------------------------------------------------------------------
 
-// log-normaliser of every teacher row TZ[g, :] (bf16), one block per row
-__global__ void __launch_bounds__(kBlock) k_teacher_lse(int V, const bf16_t *__restrict__ TZ, float *__restrict__ tlse)
+// log-normaliser of every teacher row TZ[g, :], one block per row
+template <typename TT>
+__global__ void __launch_bounds__(kBlock) k_teacher_lse(int V, const TT *__restrict__ TZ, float *__restrict__ tlse)
 {
     __shared__ float red[kBlock / kWave];
     const size_t g = blockIdx.x;
-    const bf16_t *row = TZ + g * V;
+    const TT *row = TZ + g * V;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float mx = -INFINITY;
-    for (int v = threadIdx.x; v < V; v += kBlock) mx = fmaxf(mx, bf16_to_f32(row[v]));
+    for (int v = threadIdx.x; v < V; v += kBlock) mx = fmaxf(mx, ld_f32(row, v));
     mx = wave_max(mx);
     if (lane == 0) red[wave] = mx;
     __syncthreads();
@@ -48,7 +50,7 @@ __global__ void __launch_bounds__(kBlock) k_teacher_lse(int V, const bf16_t *__r
     for (int w = 1; w < kBlock / kWave; ++w) Mx = fmaxf(Mx, red[w]);
     __syncthreads();
     float l = 0.f;
-    for (int v = threadIdx.x; v < V; v += kBlock) l += expf(bf16_to_f32(row[v]) - Mx);
+    for (int v = threadIdx.x; v < V; v += kBlock) l += expf(ld_f32(row, v) - Mx);
     l = wave_sum(l);
     if (lane == 0) red[wave] = l;
     __syncthreads();
@@ -62,14 +64,15 @@ __global__ void __launch_bounds__(kBlock) k_teacher_lse(int V, const bf16_t *__r
 
 // Per position: the expert weights of every token's conditional (eq. 13 under the true prefix) and what
 // follows from the target column alone.  rowa[m] = {lse, log qhat}; rhox[m] = qhat_a P_a[x] / p^d[x];
-// ce[t, k] = -log p^d_k[x_k].  A dropped token (x < 0) gets log qhat = 0, rhox = 0, ce = 0.
+// ce[t, k] = -log p^d_k[x_k].  A dropped token (x < 0) gets log qhat = 0, rhox = 0, ce = 0.  r <= MAXR.
+template <int MAXR>
 __global__ void k_distill_weights(size_t T, int n, int r, const float *__restrict__ logw, const float *__restrict__ C,
                                   const float *__restrict__ lse, const int32_t *__restrict__ X,
                                   float2 *__restrict__ rowa, float *__restrict__ rhox, float *__restrict__ ce)
 {
     const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
-    float q[8];
+    float q[MAXR];
     for (int a = 0; a < r; ++a) q[a] = logw[t * r + a];
     for (int k = 0; k < n; ++k) {
         const size_t m0 = (t * n + k) * r;
@@ -116,7 +119,8 @@ __global__ void __launch_bounds__(kBlock) k_sum_parts(size_t M, int parts, const
 // Per position: the loss and the row coefficients of the backward pass (for an upstream gradient of one):
 //   R_a = beta S_a + (1 - beta) rhox_a,  dq_ka = g_k (qhat_a - R_a),  D_ka = sum_{k' > k} dq_k'a
 //   c1[m] = g_k R_a - D_ka,  c2[m] = D_ka - (1 - beta) g_k rhox_a,  c3[t, k] = beta g_k,  dgsum[t, a] = sum_k dq_ka
-// with g_k = disc^k for a kept token and 0 for a dropped one.
+// with g_k = disc^k for a kept token and 0 for a dropped one.  r <= MAXR.
+template <int MAXR>
 __global__ void k_distill_finish(size_t T, int n, int r, float beta, float disc, const int32_t *__restrict__ X,
                                  const float2 *__restrict__ rowa, const float *__restrict__ rhox,
                                  const float *__restrict__ ce, const float2 *__restrict__ SK,
@@ -125,7 +129,7 @@ __global__ void k_distill_finish(size_t T, int n, int r, float beta, float disc,
 {
     const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
-    float D[8];
+    float D[MAXR];
     for (int a = 0; a < r; ++a) D[a] = 0.f;
     // last token to first, so that D accumulates the tokens after k
     float total = 0.f;
@@ -365,11 +369,15 @@ struct EpiDzDistill {
 struct DistillCtx {
     size_t base, rowa, c1, c2, c3, tlse, dgsum, total;
 };
+bool on_matrix_cores(const cp_head_desc &ds)
+{
+    return use_fast_path(ds) && (ds.r == 1 || ds.r == 2 || ds.r == 4 || ds.r == 8);
+}
 DistillCtx distill_ctx(const cp_head_desc &ds)
 {
     DistillCtx c;
     const size_t M = (size_t)ds.T * ds.n * ds.r, Tn = (size_t)ds.T * ds.n, Tr = (size_t)ds.T * ds.r;
-    size_t off = ctx_layout(ds, true).total;
+    size_t off = ctx_layout(ds, on_matrix_cores(ds)).total;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     c.base = 0;
     c.rowa = take(M * 8);
@@ -444,19 +452,7 @@ void distill_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0,
                         st);
 }
 
-}  // namespace
-
-bool distill_supported(const cp_head_desc &ds)
-{
-    return use_fast_path(ds) && (ds.r == 1 || ds.r == 2 || ds.r == 4 || ds.r == 8);
-}
-size_t distill_ctx_bytes(const cp_head_desc &ds) { return distill_ctx(ds).total; }
-size_t distill_workspace_bytes(const cp_head_desc &ds, int op)
-{
-    return op == CP_HEAD_OP_DISTILL_FWD ? distill_fwd_ws(ds).total : distill_bwd_ws(ds).total;
-}
-
-int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,
+int mfma_distill_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,
                      const int32_t *X, const void *TZv, float beta, float disc, float *loss, void *ctx, void *ws,
                      hipStream_t st)
 {
@@ -474,8 +470,8 @@ int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const
     float *rhox = at<float>(ws, f.rhox), *ce = at<float>(ws, f.ce);
     float2 *SK = at<float2>(ws, f.SK), *part = at<float2>(ws, f.part);
 
-    k_teacher_lse<<<(unsigned)Tn, kBlock, 0, st>>>(ds.V, TZ, tlse);
-    k_distill_weights<<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, fb.logw, fb.C, fb.lse, X, rowa, rhox, ce);
+    k_teacher_lse<bf16_t><<<(unsigned)Tn, kBlock, 0, st>>>(ds.V, TZ, tlse);
+    k_distill_weights<8><<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, fb.logw, fb.C, fb.lse, X, rowa, rhox, ce);
     switch (ds.r) {
     case 1: launch_stats<1>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
     case 2: launch_stats<2>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
@@ -483,12 +479,12 @@ int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const
     default: launch_stats<8>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
     }
     k_sum_parts<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, f.parts, part, SK);
-    k_distill_finish<<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, beta, disc, X, rowa, rhox, ce, SK, loss, c1, c2,
-                                                               c3, dgsum);
+    k_distill_finish<8><<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, beta, disc, X, rowa, rhox, ce, SK, loss, c1,
+                                                                  c2, c3, dgsum);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
-int distill_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,
+int mfma_distill_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,
                      const int32_t *X, const void *TZv, const float *dloss, float scale, const void *ctx, float *dH,
                      float *dW, float *dU, float *dG, void *ws, hipStream_t st)
 {
@@ -515,6 +511,227 @@ int distill_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const
     FastDzLaunch fn = ds.r == 1 ? distill_dz_launch<1> : ds.r == 2 ? distill_dz_launch<2>
                     : ds.r == 4 ? distill_dz_launch<4> : distill_dz_launch<8>;
     return fast_bwd_from_dz(ds, H, W, Uv, G, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, fn, &args, st);
+}
+
+
+// ------------------------------------------------------------------------------------------
+// plain fp32 path: any r <= 64, any d, fp32 or bf16 storage.  The logits of one chunk of rows are written
+// out in fp32 and the per-token mixture is formed from them by one block per token.
+// ------------------------------------------------------------------------------------------
+constexpr int kMaxRank = 64;
+
+// One block per token g = g0 + blockIdx.x of the chunk whose logits are zc[(gi r + a), V]:
+// SK[g r + a] = {S_a, KL} with S_a = sum_v p^c[v] rho_a[v], KL = sum_v p^c[v] (log p^c[v] - log p^d[v]).
+// Lane a of every wavefront accumulates S_a (r <= 64).
+template <typename TT>
+__global__ void __launch_bounds__(kBlock) k_distill_kl_plain(int V, int r, size_t g0, const float *__restrict__ zc,
+                                                             const float2 *__restrict__ rowa, const TT *__restrict__ TZ,
+                                                             const float *__restrict__ tlse, float2 *__restrict__ SK)
+{
+    __shared__ float lse_s[kMaxRank], lq_s[kMaxRank], S_s[kBlock / kWave][kMaxRank], kl_s[kBlock / kWave];
+    const size_t gi = blockIdx.x, g = g0 + gi;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if ((int)threadIdx.x < r) {
+        const float2 ra = rowa[g * r + threadIdx.x];
+        lse_s[threadIdx.x] = ra.x;
+        lq_s[threadIdx.x] = ra.y;
+    }
+    __syncthreads();
+    const float tl = tlse[g];
+    const float *zrow = zc + gi * r * (size_t)V;
+    const TT *trow = TZ + g * (size_t)V;
+    float Sacc = 0.f, kl = 0.f;
+    // every lane of a wavefront runs the same number of rounds, so that the sums over lanes see all of them
+    for (int v0 = wave * kWave; v0 < V; v0 += kBlock) {
+        const int v = v0 + lane;
+        const bool cv = v < V;
+        const int vc = cv ? v : V - 1;
+        float mx = -INFINITY;
+        for (int a = 0; a < r; ++a) mx = fmaxf(mx, zrow[(size_t)a * V + vc] - lse_s[a] + lq_s[a]);
+        float sum = 0.f;
+        for (int a = 0; a < r; ++a) sum += expf(zrow[(size_t)a * V + vc] - lse_s[a] + lq_s[a] - mx);
+        const float lm = mx + logf(sum);
+        const float lpc = ld_f32(trow, (size_t)vc) - tl;
+        const float pc = cv ? expf(lpc) : 0.f;
+        kl += pc * (lpc - lm);
+        for (int a = 0; a < r; ++a) {
+            const float s = wave_sum(pc * expf(zrow[(size_t)a * V + vc] - lse_s[a] + lq_s[a] - lm));
+            if (lane == a) Sacc += s;
+        }
+    }
+    kl = wave_sum(kl);
+    S_s[wave][lane] = Sacc;
+    if (lane == 0) kl_s[wave] = kl;
+    __syncthreads();
+    if ((int)threadIdx.x < r) {
+        float S = 0.f, K = 0.f;
+        for (int w = 0; w < kBlock / kWave; ++w) { S += S_s[w][threadIdx.x]; K += kl_s[w]; }
+        SK[g * r + threadIdx.x] = make_float2(S, K);
+    }
+}
+
+// One block per token of the chunk: the chunk's logits in dZ become, in place,
+// dz = c1 P - c3 p^c rho + c2 1[v = x] (every entry is read and written by the same thread).
+template <typename TT>
+__global__ void __launch_bounds__(kBlock) k_distill_dz_plain(int V, int r, size_t g0, float *__restrict__ dZ,
+                                                             const float4 *__restrict__ rowinfo,
+                                                             const float4 *__restrict__ grp, const TT *__restrict__ TZ)
+{
+    __shared__ float4 ri_s[kMaxRank];
+    const size_t gi = blockIdx.x, g = g0 + gi;
+    if ((int)threadIdx.x < r) ri_s[threadIdx.x] = rowinfo[g * r + threadIdx.x];
+    __syncthreads();
+    const float4 gv = grp[g];
+    const float tl = gv.x, c3 = gv.y;
+    const int x = __float_as_int(gv.z);
+    float *zrow = dZ + gi * r * (size_t)V;
+    const TT *trow = TZ + g * (size_t)V;
+    for (int v = threadIdx.x; v < V; v += kBlock) {
+        float mx = -INFINITY;
+        for (int a = 0; a < r; ++a) mx = fmaxf(mx, zrow[(size_t)a * V + v] - ri_s[a].x + ri_s[a].y);
+        float sum = 0.f;
+        for (int a = 0; a < r; ++a) sum += expf(zrow[(size_t)a * V + v] - ri_s[a].x + ri_s[a].y - mx);
+        const float lm = mx + logf(sum);
+        const float lpc = ld_f32(trow, (size_t)v) - tl;
+        for (int a = 0; a < r; ++a) {
+            const float4 ri = ri_s[a];
+            const float lP = zrow[(size_t)a * V + v] - ri.x;
+            zrow[(size_t)a * V + v] = ri.z * expf(lP) - c3 * expf(lpc + lP + ri.y - lm) + (v == x ? ri.w : 0.f);
+        }
+    }
+}
+
+// forward workspace: the plain training loss's, then {rhox [M], ce [T n], SK [M] float2, zc [chunk, V]}
+struct PlainFwdWs {
+    size_t rhox, ce, SK, zc, total;
+};
+PlainFwdWs plain_fwd_ws(const cp_head_desc &ds)
+{
+    PlainFwdWs f;
+    const size_t M = (size_t)ds.T * ds.n * ds.r, Tn = (size_t)ds.T * ds.n;
+    size_t off = align_up(generic_workspace_bytes(ds, CP_HEAD_OP_LOSS_FWD));
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    f.rhox = take(M * 4);
+    f.ce = take(Tn * 4);
+    f.SK = take(M * 8);
+    f.zc = take(generic_bwd_chunk_rows(ds) * ds.V * 4);
+    f.total = off;
+    return f;
+}
+DistillBwdWs plain_bwd_ws(const cp_head_desc &ds)
+{
+    DistillBwdWs b;
+    const size_t M = (size_t)ds.T * ds.n * ds.r, Tn = (size_t)ds.T * ds.n, Tr = (size_t)ds.T * ds.r;
+    size_t off = align_up(generic_workspace_bytes(ds, CP_HEAD_OP_LOSS_BWD));
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    b.rowinfo = take(M * 16);
+    b.grp = take(Tn * 16);
+    b.dg = take(Tr * 4);
+    b.total = off;
+    return b;
+}
+
+template <typename TT>
+int plain_distill_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                      const int32_t *X, const TT *TZ, float beta, float disc, float *loss, void *ctx, void *ws,
+                      hipStream_t st)
+{
+    GenericFwdBuffers fb;
+    const int rc = generic_fwd_rows(ds, H, W, U, G, X, ctx, ws, &fb, st);
+    if (rc != CP_HEAD_OK) return rc;
+    const DistillCtx dc = distill_ctx(ds);
+    const PlainFwdWs f = plain_fwd_ws(ds);
+    const size_t T = (size_t)ds.T, M = T * ds.n * ds.r, Tn = T * ds.n;
+    float2 *rowa = at<float2>(ctx, dc.rowa);
+    float *c1 = at<float>(ctx, dc.c1), *c2 = at<float>(ctx, dc.c2), *c3 = at<float>(ctx, dc.c3);
+    float *tlse = at<float>(ctx, dc.tlse), *dgsum = at<float>(ctx, dc.dgsum);
+    float *rhox = at<float>(ws, f.rhox), *ce = at<float>(ws, f.ce), *zc = at<float>(ws, f.zc);
+    float2 *SK = at<float2>(ws, f.SK);
+    k_teacher_lse<TT><<<(unsigned)Tn, kBlock, 0, st>>>(ds.V, TZ, tlse);
+    k_distill_weights<kMaxRank><<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, fb.logw, fb.C, fb.lse, X, rowa,
+                                                                          rhox, ce);
+    const size_t chunk = generic_bwd_chunk_rows(ds);
+    for (size_t m0 = 0; m0 < M; m0 += chunk) {
+        const size_t Mc = (M - m0 < chunk) ? M - m0 : chunk;
+        generic_logits_rows(ds, U, fb.Y, m0, Mc, zc, st);
+        k_distill_kl_plain<TT><<<(unsigned)(Mc / ds.r), kBlock, 0, st>>>(ds.V, ds.r, m0 / ds.r, zc, rowa, TZ, tlse, SK);
+    }
+    k_distill_finish<kMaxRank><<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, beta, disc, X, rowa, rhox, ce, SK,
+                                                                         loss, c1, c2, c3, dgsum);
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+template <typename TT>
+struct PlainDzArgs {
+    const cp_head_desc *ds;
+    const void *U;
+    const float *Y;
+    const TT *TZ;
+    const float4 *rowinfo, *grp;
+};
+template <typename TT>
+void plain_dz_launch(void *user, size_t m0, size_t Mc, float *dZ, hipStream_t st)
+{
+    const PlainDzArgs<TT> *a = static_cast<const PlainDzArgs<TT> *>(user);
+    const cp_head_desc &ds = *a->ds;
+    generic_logits_rows(ds, a->U, a->Y, m0, Mc, dZ, st);
+    k_distill_dz_plain<TT><<<(unsigned)(Mc / ds.r), kBlock, 0, st>>>(ds.V, ds.r, m0 / ds.r, dZ, a->rowinfo, a->grp, a->TZ);
+}
+
+template <typename TT>
+int plain_distill_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                      const int32_t *X, const TT *TZ, const float *dloss, float scale, const void *ctx, float *dH,
+                      float *dW, float *dU, float *dG, void *ws, hipStream_t st)
+{
+    const DistillCtx dc = distill_ctx(ds);
+    const DistillBwdWs b = plain_bwd_ws(ds);
+    const CtxLayout cl = ctx_layout(ds, false);
+    const size_t M = (size_t)ds.T * ds.n * ds.r;
+    const float2 *rowa = at<float2>(ctx, dc.rowa);
+    const float *c1 = at<float>(ctx, dc.c1), *c2 = at<float>(ctx, dc.c2), *c3 = at<float>(ctx, dc.c3);
+    const float *tlse = at<float>(ctx, dc.tlse), *dgsum = at<float>(ctx, dc.dgsum);
+    float4 *rowinfo = at<float4>(ws, b.rowinfo), *grp = at<float4>(ws, b.grp);
+    float *dg = at<float>(ws, b.dg);
+    k_distill_bwd_rows<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, ds.n, ds.r, rowa, c1, c2, c3, tlse, dgsum, dloss, scale, X,
+                                                                 rowinfo, grp, dg);
+    PlainDzArgs<TT> args{&ds, U, at<float>(ctx, cl.Y), TZ, rowinfo, grp};
+    return generic_bwd_from_dz(ds, H, W, U, G, at<float>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, plain_dz_launch<TT>, &args, st);
+}
+
+}  // namespace
+
+size_t distill_ctx_bytes(const cp_head_desc &ds) { return distill_ctx(ds).total; }
+size_t distill_workspace_bytes(const cp_head_desc &ds, int op)
+{
+    if (on_matrix_cores(ds)) return op == CP_HEAD_OP_DISTILL_FWD ? distill_fwd_ws(ds).total : distill_bwd_ws(ds).total;
+    return op == CP_HEAD_OP_DISTILL_FWD ? plain_fwd_ws(ds).total : plain_bwd_ws(ds).total;
+}
+
+int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, const void *TZ, float beta, float disc, float *loss, void *ctx, void *ws,
+                     hipStream_t st)
+{
+    if (ds.T == 0) return CP_HEAD_OK;
+    if (on_matrix_cores(ds)) return mfma_distill_fwd(ds, H, W, U, G, X, TZ, beta, disc, loss, ctx, ws, st);
+    if (ds.dtype == CP_HEAD_FP32)
+        return plain_distill_fwd<float>(ds, H, W, U, G, X, (const float *)TZ, beta, disc, loss, ctx, ws, st);
+    return plain_distill_fwd<bf16_t>(ds, H, W, U, G, X, (const bf16_t *)TZ, beta, disc, loss, ctx, ws, st);
+}
+
+int distill_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, const void *TZ, const float *dloss, float scale, const void *ctx, float *dH,
+                     float *dW, float *dU, float *dG, void *ws, hipStream_t st)
+{
+    if (ds.T == 0) {
+        launch_fill_zero(dW, (size_t)ds.n * ds.r * ds.d * ds.d, st);
+        launch_fill_zero(dU, (size_t)ds.V * ds.d, st);
+        launch_fill_zero(dG, (size_t)ds.r * ds.d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (on_matrix_cores(ds)) return mfma_distill_bwd(ds, H, W, U, G, X, TZ, dloss, scale, ctx, dH, dW, dU, dG, ws, st);
+    if (ds.dtype == CP_HEAD_FP32)
+        return plain_distill_bwd<float>(ds, H, W, U, G, X, (const float *)TZ, dloss, scale, ctx, dH, dW, dU, dG, ws, st);
+    return plain_distill_bwd<bf16_t>(ds, H, W, U, G, X, (const bf16_t *)TZ, dloss, scale, ctx, dH, dW, dU, dG, ws, st);
 }
 
 }  // namespace cph

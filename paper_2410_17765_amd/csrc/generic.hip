@@ -72,17 +72,18 @@ __global__ void __launch_bounds__(kBlock) k_y_generic(int d, int nr, const TIn *
 
 // ------------------------------------------------------------------------------------------
 // z = U y for one head row; running (max, sum exp) over the vocabulary gives the
-// log-normaliser (eq. 5); C = z[x] - lse (eq. 8).  z is written only if z_out != NULL.
+// log-normaliser (eq. 5); C = z[x] - lse (eq. 8).  Block b serves row m0 + b; lse and C are indexed by the row,
+// z_out (written only if not NULL) by the block.
 // ------------------------------------------------------------------------------------------
 template <typename TIn>
-__global__ void __launch_bounds__(kBlock) k_zstats_generic(int d, int V, int r, const TIn *__restrict__ U,
+__global__ void __launch_bounds__(kBlock) k_zstats_generic(int d, int V, int r, size_t m0, const TIn *__restrict__ U,
                                                            const float *__restrict__ Y, const int32_t *__restrict__ X,
                                                            float *__restrict__ lse_out, float *__restrict__ C_out,
                                                            float *__restrict__ z_out)
 {
     extern __shared__ float ys[];
     __shared__ float red_m[kWavesPerBlock], red_l[kWavesPerBlock], red_zt;
-    const size_t m = blockIdx.x;
+    const size_t m = m0 + blockIdx.x;
     for (int k = threadIdx.x; k < d; k += kBlock) ys[k] = Y[m * d + k];
     if (threadIdx.x == 0) red_zt = 0.f;
     __syncthreads();
@@ -93,7 +94,7 @@ __global__ void __launch_bounds__(kBlock) k_zstats_generic(int d, int V, int r, 
         float p = 0.f;
         for (int k = lane; k < d; k += kWave) p += ld_f32(U, (size_t)v * d + k) * ys[k];
         const float z = wave_sum(p);
-        if (z_out && lane == 0) z_out[m * V + v] = z;
+        if (z_out && lane == 0) z_out[(size_t)blockIdx.x * V + v] = z;
         if (z > mx) { l = l * expf(mx - z) + 1.f; mx = z; }
         else l += expf(z - mx);
         if (v == x && lane == 0) red_zt = z;
@@ -106,7 +107,7 @@ __global__ void __launch_bounds__(kBlock) k_zstats_generic(int d, int V, int r, 
         float L = 0.f;
         for (int i = 0; i < kWavesPerBlock; ++i) L += red_l[i] * expf(red_m[i] - Mx);
         const float lse = Mx + logf(L);
-        lse_out[m] = lse;
+        if (lse_out) lse_out[m] = lse;
         if (C_out) C_out[m] = (x >= 0) ? red_zt - lse : 0.f;
     }
 }
@@ -584,13 +585,16 @@ __global__ void __launch_bounds__(kWave) k_aux_finish(size_t T, int r, const uns
     if (lane == 0) *laux = s;
 }
 
-// rows of the dZ chunk on this path: at most 512 MiB of fp32 logit gradients at a time
+// rows of the dZ chunk on this path: about 512 MiB of fp32 logit gradients at a time (256 rows with the
+// least-workspace flag), and the r rows of one token never split over two chunks
 inline size_t generic_chunk_rows(const cp_head_desc &ds)
 {
     const size_t M = (size_t)ds.T * ds.n * ds.r;
     size_t rows = ((size_t)1 << 27) / (size_t)ds.V;
-    if (rows < 1) rows = 1;
-    return rows < M ? rows : (M ? M : 1);
+    if (ds.flags & CP_HEAD_MIN_WORKSPACE) rows = 256;
+    rows = rows / ds.r * ds.r;
+    if (rows < (size_t)ds.r) rows = (size_t)ds.r;
+    return rows < M ? rows : (M ? M : (size_t)ds.r);
 }
 
 struct GenericWs {
@@ -635,30 +639,26 @@ int loss_fwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U,
     const size_t lds = (size_t)ds.d * sizeof(float);
     k_gate<TIn><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
     k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, Y, 0);
-    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, X, lse, C, nullptr);
+    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, 0, U, Y, X, lse, C, nullptr);
     k_mixture<<<(unsigned)ds.T, kWave, 0, st>>>(ds.n, ds.r, logw, C, loss, gamma, -1.f);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
+// Everything below the logit gradients, shared by the training loss and the fine-tuning loss: `fn` fills dZ with
+// the gradients of the rows [m0, m0 + Mc) of one chunk, which is then contracted into dY and dU; dW, dH, dG follow.
 template <typename TIn>
-int loss_bwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const int32_t *X,
-               const float *dloss, float scale, const void *ctx, float *dH, float *dW, float *dU, float *dG,
-               void *ws, hipStream_t st)
+int bwd_from_dz_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const float *Y,
+                  const float *dg, float *dH, float *dW, float *dU, float *dG, void *ws, GenericDzLaunch fn, void *user,
+                  hipStream_t st)
 {
-    const CtxLayout cl = ctx_layout(ds, false);
     const GenericWs g = generic_ws(ds, CP_HEAD_OP_LOSS_BWD);
-    const size_t T = (size_t)ds.T, M = T * ds.n * ds.r, Tr = T * ds.r;
-    const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
-    const float *Y = at<float>(ctx, cl.Y);
-    float *dY = at<float>(ws, g.dY), *dZ = at<float>(ws, g.dZ), *dg = at<float>(ws, g.dg);
-    const size_t lds = (size_t)ds.d * sizeof(float);
+    const size_t T = (size_t)ds.T, M = T * ds.n * ds.r;
+    float *dY = at<float>(ws, g.dY), *dZ = at<float>(ws, g.dZ);
     const size_t chunk = generic_chunk_rows(ds);
-    k_dgate<<<blocks_for(Tr, kBlock), kBlock, 0, st>>>(Tr, ds.r, w, gamma, dloss, scale, dg);
     int first = 1;
     for (size_t m0 = 0; m0 < M; m0 += chunk) {
         const size_t Mc = (M - m0 < chunk) ? M - m0 : chunk;
-        k_dz_generic<TIn><<<(unsigned)Mc, kBlock, lds, st>>>(ds.d, ds.V, ds.n, ds.r, m0, U, Y, X, lse, gamma, dloss,
-                                                             scale, dZ);
+        fn(user, m0, Mc, dZ, st);
         k_dy_generic<TIn><<<blocks_for(Mc * ds.d, kBlock), kBlock, 0, st>>>(ds.d, ds.V, m0, Mc, U, dZ, dY);
         if (dU)
             k_du_generic<<<blocks_for((size_t)ds.V * ds.d, kBlock), kBlock, 0, st>>>(ds.d, ds.V, m0, Mc, dZ, Y, dU,
@@ -674,6 +674,39 @@ int loss_bwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U,
 }
 
 template <typename TIn>
+struct LossDzArgs {
+    const cp_head_desc *ds;
+    const TIn *U;
+    const float *Y, *lse, *gamma, *dloss;
+    const int32_t *X;
+    float scale;
+};
+template <typename TIn>
+void loss_dz_launch(void *user, size_t m0, size_t Mc, float *dZ, hipStream_t st)
+{
+    const LossDzArgs<TIn> *a = static_cast<const LossDzArgs<TIn> *>(user);
+    const cp_head_desc &ds = *a->ds;
+    k_dz_generic<TIn><<<(unsigned)Mc, kBlock, (size_t)ds.d * sizeof(float), st>>>(ds.d, ds.V, ds.n, ds.r, m0, a->U, a->Y, a->X,
+                                                                                  a->lse, a->gamma, a->dloss, a->scale, dZ);
+}
+
+template <typename TIn>
+int loss_bwd_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const int32_t *X,
+               const float *dloss, float scale, const void *ctx, float *dH, float *dW, float *dU, float *dG,
+               void *ws, hipStream_t st)
+{
+    const CtxLayout cl = ctx_layout(ds, false);
+    const GenericWs g = generic_ws(ds, CP_HEAD_OP_LOSS_BWD);
+    const size_t Tr = (size_t)ds.T * ds.r;
+    const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
+    const float *Y = at<float>(ctx, cl.Y);
+    float *dg = at<float>(ws, g.dg);
+    k_dgate<<<blocks_for(Tr, kBlock), kBlock, 0, st>>>(Tr, ds.r, w, gamma, dloss, scale, dg);
+    LossDzArgs<TIn> args{&ds, U, Y, lse, gamma, dloss, X, scale};
+    return bwd_from_dz_t<TIn>(ds, H, W, U, G, Y, dg, dH, dW, dU, dG, ws, loss_dz_launch<TIn>, &args, st);
+}
+
+template <typename TIn>
 int draft_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const float *uniforms,
             int32_t *alpha, int32_t *tokens, float *logq, void *ws, hipStream_t st)
 {
@@ -686,7 +719,7 @@ int draft_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, co
     k_gate<TIn><<<(unsigned)B, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
     k_pick_alpha<<<blocks_for(B, kWave), kWave, 0, st>>>(B, ds.n, ds.r, w, uniforms, alpha);
     k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, Y, round_y);
-    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, nullptr, lse, nullptr, z);
+    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, 0, U, Y, nullptr, lse, nullptr, z);
     k_sample_generic<<<(unsigned)(B * ds.n), kBlock, 0, st>>>(ds.V, ds.n, ds.r, z, lse, alpha, uniforms, tokens);
     if (logq) k_logq_generic<<<(unsigned)B, kWave, 0, st>>>(ds.V, ds.n, ds.r, logw, z, lse, tokens, logq);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
@@ -704,7 +737,7 @@ int draft_sequential_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const
     const int round_y = ds.dtype == CP_HEAD_BF16 ? 1 : 0;
     k_gate<TIn><<<(unsigned)B, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
     k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, Y, round_y);
-    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, nullptr, lse, nullptr, z);
+    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, 0, U, Y, nullptr, lse, nullptr, z);
     k_sample_sequential_generic<<<(unsigned)B, kBlock, 0, st>>>(ds.V, ds.n, ds.r, z, lse, logw, uniforms, tokens, logq);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
@@ -723,6 +756,63 @@ int generic_draft_sequential(const cp_head_desc &ds, const void *H, const void *
 }
 
 size_t generic_workspace_bytes(const cp_head_desc &ds, int op) { return generic_ws(ds, op).total; }
+
+size_t generic_bwd_chunk_rows(const cp_head_desc &ds) { return generic_chunk_rows(ds); }
+
+namespace {
+template <typename TIn>
+void fwd_rows_t(const cp_head_desc &ds, const TIn *H, const TIn *W, const TIn *U, const TIn *G, const int32_t *X,
+                const GenericFwdBuffers &b, hipStream_t st)
+{
+    const size_t M = (size_t)ds.T * ds.n * ds.r, lds = (size_t)ds.d * sizeof(float);
+    k_gate<TIn><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, H, G, b.logw, b.w);
+    k_y_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.n * ds.r, H, W, b.Y, 0);
+    k_zstats_generic<TIn><<<(unsigned)M, kBlock, lds, st>>>(ds.d, ds.V, ds.r, 0, U, b.Y, X, b.lse, b.C, nullptr);
+}
+}  // namespace
+
+int generic_fwd_rows(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                     const int32_t *X, void *ctx, void *ws, GenericFwdBuffers *out, hipStream_t st)
+{
+    const CtxLayout cl = ctx_layout(ds, false);
+    const GenericWs g = generic_ws(ds, CP_HEAD_OP_LOSS_FWD);
+    GenericFwdBuffers b;
+    b.lse = at<float>(ctx, cl.lse);
+    b.w = at<float>(ctx, cl.w);
+    b.gamma = at<float>(ctx, cl.gamma);
+    b.Y = at<float>(ctx, cl.Y);
+    b.logw = at<float>(ws, g.logw);
+    b.C = at<float>(ws, g.C);
+    if (ds.dtype == CP_HEAD_FP32)
+        fwd_rows_t<float>(ds, (const float *)H, (const float *)W, (const float *)U, (const float *)G, X, b, st);
+    else
+        fwd_rows_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G, X, b, st);
+    *out = b;
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+void generic_logits_rows(const cp_head_desc &ds, const void *U, const float *Y, size_t m0, size_t Mc, float *z,
+                         hipStream_t st)
+{
+    const size_t lds = (size_t)ds.d * sizeof(float);
+    if (ds.dtype == CP_HEAD_FP32)
+        k_zstats_generic<float><<<(unsigned)Mc, kBlock, lds, st>>>(ds.d, ds.V, ds.r, m0, (const float *)U, Y, nullptr,
+                                                                   nullptr, nullptr, z);
+    else
+        k_zstats_generic<bf16_t><<<(unsigned)Mc, kBlock, lds, st>>>(ds.d, ds.V, ds.r, m0, (const bf16_t *)U, Y, nullptr,
+                                                                    nullptr, nullptr, z);
+}
+
+int generic_bwd_from_dz(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                        const float *Y, const float *dg, float *dH, float *dW, float *dU, float *dG, void *ws,
+                        GenericDzLaunch fn, void *user, hipStream_t st)
+{
+    if (ds.dtype == CP_HEAD_FP32)
+        return bwd_from_dz_t<float>(ds, (const float *)H, (const float *)W, (const float *)U, (const float *)G, Y, dg,
+                                    dH, dW, dU, dG, ws, fn, user, st);
+    return bwd_from_dz_t<bf16_t>(ds, (const bf16_t *)H, (const bf16_t *)W, (const bf16_t *)U, (const bf16_t *)G, Y, dg,
+                                 dH, dW, dU, dG, ws, fn, user, st);
+}
 
 int generic_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                      const int32_t *X, float *loss, void *ctx, void *ws, hipStream_t st)
@@ -809,7 +899,7 @@ static int first_token_t(const cp_head_desc &ds, const TIn *H, const TIn *W, con
     k_gate<TIn><<<(unsigned)ds.T, kWave, 0, st>>>(ds.d, ds.r, H, G, logw, w);
     // the first head's matrices are the first r blocks of W, so its rows are (b, a) with nr = r
     k_y_generic<TIn><<<(unsigned)rows, kBlock, lds, st>>>(ds.d, ds.r, H, W, Y, round_y);
-    k_zstats_generic<TIn><<<(unsigned)rows, kBlock, lds, st>>>(ds.d, ds.V, ds.r, U, Y, nullptr, lse, nullptr, z);
+    k_zstats_generic<TIn><<<(unsigned)rows, kBlock, lds, st>>>(ds.d, ds.V, ds.r, 0, U, Y, nullptr, lse, nullptr, z);
     launch_first_token_mix(ds, z, (size_t)ds.V, lse, logw, logp, st);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }

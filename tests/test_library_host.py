@@ -131,9 +131,9 @@ def test_new_calls_reject_bad_arguments_before_launch(lib):
         assert lib.cp_head_full_loss_fwd(*argsf) == -3
     argsb = [ctypes.byref(bf), p, p, p, p, None, 1.0, p, None, p, p, p, 1 << 30, None]
     assert lib.cp_head_full_loss_bwd(*argsb) == -1           # dH is required
-    # fine-tuning loss: supported ranks only, beta in [0, 1], teacher logits required
+    # fine-tuning loss: both paths, beta in [0, 1], teacher logits required
     r3 = binding.make_desc(4, 64, 300, 2, 3, binding.BF16)
-    assert lib.cp_head_distill_ctx_bytes(ctypes.byref(r3), ctypes.byref(out)) == -2
+    assert lib.cp_head_distill_ctx_bytes(ctypes.byref(r3), ctypes.byref(out)) == 0
     assert lib.cp_head_distill_ctx_bytes(ctypes.byref(bf), ctypes.byref(out)) == 0
     assert out.value > binding.cp_head_ctx_bytes(bf)
     argsd = [ctypes.byref(bf), p, p, p, p, p, p, 0.9, 1.0, p, p, p, 1 << 30, None]
@@ -143,8 +143,8 @@ def test_new_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cp_head_distill_loss_fwd(*bad) == -1
     bad = list(argsd); bad[12] = 0
     assert lib.cp_head_distill_loss_fwd(*bad) == -3
-    bad = list(argsd); bad[0] = ctypes.byref(r3)
-    assert lib.cp_head_distill_loss_fwd(*bad) == -2
+    bad = list(argsd); bad[0] = ctypes.byref(r3); bad[12] = 0
+    assert lib.cp_head_distill_loss_fwd(*bad) == -3
     # balancing statistic: outputs required
     assert lib.cp_head_aux_balance(ctypes.byref(bf), p, p, None, p, p, 256, None) == -1
 
