@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token', 'full_heads', 'full_heads_7b', 'distill_7b'")
     ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per two threads)")
+    ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per four threads for the loss, per two for the full heads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
     ap.add_argument("--no-modes", action="store_true", help="loss workloads: skip the forward-only and frozen-unembedding timings")
     ap.add_argument("--no-draft", action="store_true", help="loss workloads: skip the appended draft-step measurements")
@@ -53,7 +53,7 @@ def cpu_baseline_loss(cfg, inp, positions):
     from paper_2410_17765_amd import synth
     cp_oracle.build()
     cores = cp_oracle.num_threads()
-    S = positions or max(1, cores // 2)
+    S = positions or max(1, cores // 4)     # about 25 s of wall time at the headline size
     sel = synth.position_subset(cfg.T, S)
     H, X = inp["H"][sel], inp["X"][sel]
     t0 = time.time()
