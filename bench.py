@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token', 'full_heads', 'full_heads_7b', 'distill_7b'")
     ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per four threads for the loss, per two for the full heads)")
+    ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per thread for the loss, per two threads for the full heads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
     ap.add_argument("--no-modes", action="store_true", help="loss workloads: skip the forward-only and frozen-unembedding timings")
     ap.add_argument("--no-draft", action="store_true", help="loss workloads: skip the appended draft-step measurements")
@@ -53,7 +53,7 @@ def cpu_baseline_loss(cfg, inp, positions):
     from paper_2410_17765_amd import synth
     cp_oracle.build()
     cores = cp_oracle.num_threads()
-    S = positions or max(1, cores // 4)     # about 25 s of wall time at the headline size
+    S = positions or cores      # the oracle threads over positions: one each keeps every thread busy
     sel = synth.position_subset(cfg.T, S)
     H, X = inp["H"][sel], inp["X"][sel]
     t0 = time.time()
@@ -114,14 +114,18 @@ def bench_full(args):
         step()
     torch.cuda.synchronize()
     binding.cp_head_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the launch stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     binding.cp_head_profile_enable(False)
     kernels = binding.cp_head_profile_read()
     ms_per_step = dt * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     gemms = [k for k in kernels if "gemm_" in k[0]]
     dom = max(gemms, key=lambda k: k[2])
     achieved = dom[3] / (dom[2] * 1e-3) / 1e12
@@ -198,14 +202,18 @@ def bench_distill(args):
         step()
     torch.cuda.synchronize()
     binding.cp_head_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the launch stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     binding.cp_head_profile_enable(False)
     kernels = binding.cp_head_profile_read()
     ms_per_step = dt * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     gemms = [k for k in kernels if "gemm_" in k[0]]
     dom = max(gemms, key=lambda k: k[2])
     achieved = dom[3] / (dom[2] * 1e-3) / 1e12
@@ -267,14 +275,18 @@ def bench_loss(args):
         step()
     torch.cuda.synchronize()
     binding.cp_head_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the launch stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     binding.cp_head_profile_enable(False)
     kernels = binding.cp_head_profile_read()
     ms_per_step = dt * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     value = cfg.T * args.steps / dt
     mean_loss = float(loss.mean())
 
@@ -295,8 +307,11 @@ def bench_loss(args):
         "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
                    "frozen_u": bool(args.frozen_u), "token": "one position (n future tokens each)"},
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
         "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "hardware_flop_frac_of_bf16_peak": sum(k[3] for k in gemms) / args.steps / (ms_per_step * 1e-3) / 1e12
+                                           / PEAK_BF16_TFLOPS,
         "mean_loss": mean_loss,
         "roofline": roof,
         "kernels": [{"name": k[0], "launches": k[1], "ms_per_step": k[2] / args.steps,
@@ -319,6 +334,10 @@ def bench_loss(args):
         t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
         out["forward_only"] = {"ms_per_step": t_fwd * 1e3, "tokens_per_s": cfg.T / t_fwd,
                                "model_tflops": fwd_flops / t_fwd / 1e12}
+        # backward alone, on the ctx the last forward call left
+        t_bwd = timed(lambda: binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, dU, dG, ws,
+                                                       stream))
+        out["backward_only"] = {"ms_per_step": t_bwd * 1e3, "model_tflops": (model_flops - fwd_flops) / t_bwd / 1e12}
     if not args.frozen_u and not args.no_modes:
         def frozen_step():
             binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
