@@ -7,6 +7,25 @@ GRAD_REL_FRO = 1e-2       # relative Frobenius error of each gradient tensor
 CDF_BAND = 1e-5           # a draw may differ only if its uniform is this close to a CDF boundary
 
 
+def loss_atol_bf16(cfg) -> float:
+    """Loss bound for the matrix-core path at shapes beyond the workloads'.  The path's one rounding after the
+    inputs is y -> bf16 (an operand of the d -> V contraction); everything below is its consequence.
+    * Each log-normaliser moves by dlse = sum_v p_v dz_v = dy . (U^T p).  With rows of U ~ N(0, I/d) the
+      softmax-weighted mean row U^T p is y/d to first order, so dlse = sum_k y_k^2 eps_k / d with eps the
+      relative rounding errors (rms about 1e-3): rms 1e-3 sqrt(3/d).  That does not average down over the
+      vocabulary: 3e-5 at d = 4096, but 2.4e-4 at d = 64, where the largest of a few thousand positions
+      (n factors each) reaches 2.5e-3.  The bound of the workloads (d >= 2048) is kept down to d = 256
+      and grows as sqrt(256/d) below.
+    * The loss sums n factors, each with its own log-normaliser: stated for n <= 4, it grows with n beyond.
+    * Under V = 64 entries the softmax weights average nothing: a log-normaliser carries the error of its
+      few logits in full (1e-2).
+    fp32 storage runs on the plain path, which rounds nothing after the inputs: the workloads' bound as it is."""
+    if cfg.dtype == "fp32":
+        return LOSS_ATOL
+    tol = LOSS_ATOL if cfg.V >= 64 else 1e-2
+    return tol * max(1.0, cfg.n / 4) * max(1.0, (256.0 / cfg.d) ** 0.5)
+
+
 def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)

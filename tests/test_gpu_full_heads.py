@@ -67,6 +67,30 @@ def test_loss_and_gradients(gpu, oracle, cfg, flags):
         assert e <= GRAD_REL_FRO, k
 
 
+def random_shapes(count=8, seed=20241022, budget=4e8):
+    """Seeded random shapes over both paths, sized so that the oracle's T n r V d multiply-adds stay small."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    out = []
+    for i in range(count):
+        kind = int(rng.integers(0, 4))                 # 0, 1: matrix-core path; 2: plain bf16; 3: plain fp32
+        d = int(rng.integers(20, 200)) if kind == 3 else 64 * int(rng.integers(1, 4))
+        V = int(rng.integers(64, 1200))
+        n = int(rng.integers(1, 4))
+        r = int(rng.integers(1, 7))
+        T = int(rng.integers(1, 700))
+        if float(T) * n * r * V * d > budget:
+            T = max(1, int(budget / (float(n) * r * V * d)))
+        flags = 1 if kind == 2 else (2 if rng.integers(0, 3) == 0 else 0)
+        out.append((synth.HeadConfig(f"full_random_{i}", T=T, d=d, V=V, n=n, r=r, dtype="fp32" if kind == 3 else "bf16",
+                                     u_scale=float(rng.choice([1.0, 2.0, 3.0]))), flags))
+    return out
+
+
+@pytest.mark.parametrize("cfg,flags", random_shapes(), ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_loss_and_gradients_random_shapes(gpu, oracle, cfg, flags):
+    test_loss_and_gradients(gpu, oracle, cfg, flags)
+
+
 def test_frozen_heads_scale_and_determinism(gpu):
     cfg = synth.HeadConfig("full_opts", T=130, d=64, V=300, n=2, r=2, u_scale=2.0)
     inp = make(cfg)

@@ -66,6 +66,28 @@ def test_first_token_logprob(gpu, oracle, cfg, flags):
     assert norm <= 1e-4
 
 
+def random_shapes(prefix, count, seed, max_T=40):
+    """Seeded random shapes over both paths (bf16 with d a multiple of 64, bf16 forced onto the plain path,
+    fp32 with any d), peaked and flat heads."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    out = []
+    for i in range(count):
+        kind = int(rng.integers(0, 4))                 # 0, 1: matrix-core path; 2: plain bf16; 3: plain fp32
+        d = int(rng.integers(20, 200)) if kind == 3 else 64 * int(rng.integers(1, 5))
+        cfg = synth.HeadConfig(f"{prefix}_random_{i}", T=int(rng.integers(1, max_T)), d=d,
+                               V=int(rng.integers(70, 2500)), n=int(rng.integers(1, 5)), r=int(rng.integers(1, 10)),
+                               dtype="fp32" if kind == 3 else "bf16", targets="uniform",
+                               u_scale=float(rng.choice([1.0, 3.0, 6.0])))
+        out.append((cfg, 1 if kind == 2 else 0))
+    return out
+
+
+@pytest.mark.parametrize("cfg,flags", random_shapes("first", 10, 20241020),
+                         ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_first_token_logprob_random_shapes(gpu, oracle, cfg, flags):
+    test_first_token_logprob(gpu, oracle, cfg, flags)
+
+
 def test_first_token_matches_between_paths(gpu):
     import torch
     cfg = synth.HeadConfig("first_both", T=20, d=128, V=515, n=2, r=5, targets="uniform", u_scale=4.0)
@@ -97,12 +119,22 @@ SEQ_CASES += [
 
 @pytest.mark.parametrize("cfg", SEQ_CASES, ids=lambda c: c.name)
 def test_sequential_sampling(gpu, oracle, cfg):
+    run_sequential(gpu, oracle, cfg, 1 if cfg.name.startswith("seq_plain") else 0)
+
+
+@pytest.mark.parametrize("cfg,flags", random_shapes("seq", 10, 20241021, max_T=20),
+                         ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_sequential_sampling_random_shapes(gpu, oracle, cfg, flags):
+    run_sequential(gpu, oracle, cfg, flags)
+
+
+def run_sequential(gpu, oracle, cfg, flags):
     import torch
-    print(f"case {cfg}", flush=True)
+    print(f"case {cfg} flags={flags}", flush=True)
     inp = synth.make_inputs(cfg)
     H, W, U, G = inp["H"], inp["W"], inp["U"], inp["G"]
     u = seq_uniforms(cfg.T, cfg.n)
-    h = gpu.CpHead(W, U, G, dtype=cfg.dtype, flags=1 if cfg.name.startswith("seq_plain") else 0)
+    h = gpu.CpHead(W, U, G, dtype=cfg.dtype, flags=flags)
     tokens, logq = h.draft_sample_sequential(gpu.to_device(H, cfg.dtype), torch.from_numpy(u).cuda())
     torch.cuda.synchronize()
     tokens, logq = tokens.cpu().numpy(), logq.cpu().numpy()
