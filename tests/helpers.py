@@ -106,7 +106,7 @@ def check_draft(oracle, H, W, U, G, u, alpha_gpu, tokens_gpu, logq_gpu, round_y,
     a_o, tok_o, logq_o, cdf_w, cdf_tok, y_exact = oracle.draft_sample(H, W, U, G, u, round_y=round_y, want_cdf=True,
                                                                       want_y=True)
     stats = {"alpha_exact": int((a_o == alpha_gpu).sum()), "alpha_total": B,
-             "tokens_exact": 0, "tokens_total": B * n, "tie_draws": 0}
+             "tokens_exact": 0, "tokens_total": B * n, "tie_draws": 0, "band_draws": 0, "tie_logq_rows": 0}
     for b in range(B):
         assert band_valid(cdf_w[b], int(alpha_gpu[b]), float(u[b, 0])), ("alpha out of band", b)
     if (a_o != alpha_gpu).any():
@@ -124,15 +124,35 @@ def check_draft(oracle, H, W, U, G, u, alpha_gpu, tokens_gpu, logq_gpu, round_y,
                 assert flips > 0, ("token out of band", b, s, v, int(tok_o[b, s]))
                 stats["tie_draws"] += 1
                 tie_rows.add(b)
+            elif v != tok_o[b, s]:
+                stats["band_draws"] += 1        # another token than the oracle's, inside the band
             stats["tokens_exact"] += int(v == tok_o[b, s])
     if logq_gpu is not None:
         # log-probability of the tuple the GPU drew, by the oracle's loss at those tokens
         lq = -oracle.loss_fwd(H, W, U, G, tokens_gpu.astype(np.int32), round_y=round_y)
+        errs = np.abs(lq - logq_gpu.astype(np.float64))
+        for b in range(B):
+            if b in tie_rows or errs[b] <= logq_atol:
+                continue
+            # logq reads all n r rows of y: an element of any of them on a bf16 rounding tie moves it; the
+            # row must then be the oracle's under another rounding of those elements, draws included
+            assert round_y, ("logq", b, errs[b])
+            explained = False
+            for flips, nd in tie_variants(y_exact[b]):
+                if not flips:
+                    continue
+                out = oracle.draft_sample(H[b:b + 1], W, U, G, u[b:b + 1], round_y=True,
+                                          alpha_in=np.array([alpha_gpu[b]], np.int32), want_cdf=True, y_nudge=nd[None])
+                if abs(out[2][0] - logq_gpu[b]) <= logq_atol and all(
+                        band_valid(out[4][0, s], int(tokens_gpu[b, s]), float(u[b, 1 + s])) for s in range(n)):
+                    explained = True
+                    break
+            assert explained, ("logq off with no rounding tie to explain it", b, errs[b])
+            stats["tie_logq_rows"] += 1
+            errs[b] = 0.0
         keep = np.array([b not in tie_rows for b in range(B)])
         if keep.any():
-            err = np.abs(lq - logq_gpu.astype(np.float64))[keep].max()
-            assert err <= logq_atol, ("logq", err)
-            stats["logq_err"] = float(err)
+            stats["logq_err"] = float(errs[keep].max())
     return stats
 
 

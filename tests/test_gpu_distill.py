@@ -75,7 +75,8 @@ def test_loss_and_gradients(gpu, oracle, cfg, flags, beta, disc):
     for k in ("dH", "dW", "dU", "dG"):
         if k == "dG" and cfg.r == 1:
             # one expert: the gate weight is the constant 1 and its gradient vanishes identically
-            assert np.abs(rg[k]).max() <= 1e-12 and np.abs(g[k]).max() <= 1e-5
+            # (on the GPU: a sum over positions of fp32 rounding noise of size 1e-6 each)
+            assert np.abs(rg[k]).max() <= 1e-12 and np.abs(g[k]).max() <= 2e-6 * max(cfg.T, 8)
             continue
         e = rel_fro(g[k], rg[k])
         print(f"  {k} rel fro {e:.3e}", flush=True)
