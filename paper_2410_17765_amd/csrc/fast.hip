@@ -115,7 +115,11 @@ struct EpiDz {
     __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
     {
         static_assert(C::TM == 2 || C::TM == 4, "sub-tiles of 64 or 128 rows");
-        auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
+        // after convert() the even accumulator of a pair of rows holds both gradients as two bf16
+        auto dz = [&](int i, int j, int v, int, int) {
+            const uint32_t pk = __float_as_uint(acc[i][j][v & ~1]);
+            return (bf16_t)((v & 1) ? (pk >> 16) : (pk & 0xFFFFu));
+        };
         // 64 rows at a time: turn their logits into gradients in place and write them out at once, so that
         // the finished values do not stay in registers
         convert<C, 0>(acc, row0, col0, lane);
@@ -128,25 +132,50 @@ struct EpiDz {
         }
     }
 
+    // Logits -> gradients for the 32-row blocks 2 IP and 2 IP + 1, two consecutive rows at a time; the pair
+    // is rounded to bf16 by one conversion and kept in the even row's accumulator.  The one-hot term touches
+    // one element of a row, so it is a branch that a wavefront takes only where a target falls into its
+    // columns.
     template <class C, int IP>
     __device__ __forceinline__ void convert(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane) const
     {
         const float4 *__restrict__ info = rowinfo;
+        const int lcol = col0 + (lane & 31);
+        const bool ragged = col0 + 32 * C::TN > V;       // the same for the whole wavefront
 #pragma unroll
         for (int i = 2 * IP; i < 2 * IP + 2; ++i) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + acc_row(i, v, lane);
-                const float4 ri = info[row < Mc ? row : Mc - 1];
-                const float l = ri.x;
-                const float cf = row < Mc ? ri.y : 0.f;
-                const int x = __float_as_int(ri.z);
+            for (int v = 0; v < 16; v += 2) {
+                const int row = row0 + acc_row(i, v, lane);          // rows row and row + 1
+                const float4 ra = info[row < Mc ? row : Mc - 1];
+                const float4 rb = info[row + 1 < Mc ? row + 1 : Mc - 1];
+                // rows past the chunk hold zero logits: coefficient 0 and offset 0 keep their product finite
+                const float cfa = row < Mc ? ra.y : 0.f, cfb = row + 1 < Mc ? rb.y : 0.f;
+                const float la = row < Mc ? ra.x : 0.f, lb = row + 1 < Mc ? rb.x : 0.f;
+                float ga[C::TN], gb[C::TN];
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j) {
-                    const int col = col0 + acc_col(j, lane);
-                    const float g = cf * (__expf(acc[i][j][v] - l) - (col == x ? 1.f : 0.f));
-                    acc[i][j][v] = col < V ? g : 0.f;
+                    // z - lse first: exact where the logit is close to the log-normaliser (p close to 1)
+                    ga[j] = cfa * __builtin_amdgcn_exp2f((acc[i][j][v] - la) * kLog2e);
+                    gb[j] = cfb * __builtin_amdgcn_exp2f((acc[i][j][v + 1] - lb) * kLog2e);
                 }
+                const int xa = __float_as_int(ra.z) - lcol, xb = __float_as_int(rb.z) - lcol;   // 32 j at the target
+                const bool ha = (xa & 31) == 0 && (unsigned)xa < 32u * C::TN;
+                const bool hb = (xb & 31) == 0 && (unsigned)xb < 32u * C::TN;
+                if (ha || hb) {
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j) {
+                        if (ha && xa == 32 * j) ga[j] -= cfa;
+                        if (hb && xb == 32 * j) gb[j] -= cfb;
+                    }
+                }
+                if (ragged) {
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j)
+                        if (lcol + 32 * j >= V) { ga[j] = 0.f; gb[j] = 0.f; }
+                }
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j) acc[i][j][v] = __uint_as_float(f32x2_to_bf16x2(ga[j], gb[j]));
             }
             // keeps the per-row loads of the next block from being hoisted (they would spill registers)
             asm volatile("" ::: "memory");
