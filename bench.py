@@ -34,8 +34,8 @@ TRAFFIC_BYTES = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="head_7b", help="a name from synth.CONFIGS (loss workloads), or 'draft', 'draft_sequential', 'first_token', 'full_heads', 'full_heads_7b', 'distill_7b'")
     ap.add_argument("--batch", type=int, default=8, help="draft workload: rows per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -60,9 +60,14 @@ def cpu_baseline_loss(cfg, inp, positions):
     cp_oracle.loss_fwd(H, inp["W"], inp["U"], inp["G"], X)
     cp_oracle.loss_bwd(H, inp["W"], inp["U"], inp["G"], X, np.ones(len(sel)))
     dt = time.time() - t0
-    return {"value": len(sel) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"{len(sel)} seeded positions of the workload at full d, V, n, r; fp64 forward + backward "
-                      f"with all gradients; {dt:.1f} s wall"}
+    # the oracle threads over positions, so with at most one position per thread the wall time is also
+    # the time one thread needs for one position
+    out = {"value": len(sel) / dt, "unit": "tokens/s", "cores": min(cores, len(sel)), "kind": "oracle",
+           "sample": f"{len(sel)} seeded positions of the workload at full d, V, n, r; fp64 forward + backward "
+                     f"with all gradients; {dt:.1f} s wall"}
+    if len(sel) <= cores:
+        out["seconds_per_position_one_thread"] = dt
+    return out
 
 
 def bench_full(args):
@@ -308,6 +313,7 @@ def bench_loss(args):
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
                    "frozen_u": bool(args.frozen_u), "token": "one position (n future tokens each)"},
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "predicted_tokens_per_s": value * cfg.n,      # every position predicts n tokens
         "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
         "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "hardware_flop_frac_of_bf16_peak": sum(k[3] for k in gemms) / args.steps / (ms_per_step * 1e-3) / 1e12
