@@ -156,3 +156,30 @@ def test_full_head_workspace_is_bounded_in_positions(lib):
     wb = binding.cp_head_workspace_bytes(b, binding.OP_FULL_LOSS_BWD)
     # doubling T adds per-position bookkeeping only (row info, transposed H), never logit-sized rows
     assert (wb - wa) / (1 << 16) < 4 * 8 * 16 + 4096 * 2 + 8 * 4 + 4096
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other count ends with a message and a non-zero status, before
+    anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0 and "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_bench_defaults_and_roofline_constants():
+    import importlib.util
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_under_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    argv, sys.argv = sys.argv, ["bench.py"]
+    try:
+        args = bench.parse()
+    finally:
+        sys.argv = argv
+    assert args.gpus == 1 and args.steps >= 10 and args.warmup >= 3 and args.workload == "head_7b"
+    assert bench.PEAK_BF16_TFLOPS == 2500.0                      # dense bf16 matrix peak of the MI355X
