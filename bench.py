@@ -28,6 +28,8 @@ GIB = float(1 << 30)
 TRAFFIC_BYTES = {
     ("head_7b", "gemm_z_stats"): (191.801 + 1.227) * GIB,
     ("head_7b", "gemm_z_dz"): (11.936 + 3.906) * GIB,
+    # draft step at B = 8: L2 fills of its five kernels (profiles/draft_b8_kernel_stats.md), per step
+    ("draft", 8): (1.0006 + 1.0108 + 0.0020 + 0.0316 + 0.0022) * GIB,
 }
 
 
@@ -459,7 +461,8 @@ def bench_draft(args, mode="draft"):
         "ms_per_step_graph": ms_graph, "graph_replays_match_eager": graph_ok,
         "graph_gbs": weight_bytes / (ms_graph * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": gbs / PEAK_HBM_GBS, "traffic": None},
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get((mode, cfg.T)),
+                     "traffic_unit": "bytes per step"},
         "kernels": [{"name": k[0], "launches": k[1], "ms_per_step": k[2] / args.steps} for k in kernels],
     }
 
