@@ -62,11 +62,7 @@ __device__ __forceinline__ bool tile_of_block(int bid, int nblocks, int tiles_m,
     const int per_xcd = nblocks >> 3;
     const int lid = (bid & 7) * per_xcd + (bid >> 3);
     if (lid >= tiles_m * tiles_n) return false;
-#ifdef CPH_GM
-    constexpr int GM = CPH_GM;
-#else
-    constexpr int GM = 8;
-#endif
+    constexpr int GM = 8;     // 4, 16 and 32 tile rows per group were measured slower
     const int per_group = GM * tiles_n;
     const int group = lid / per_group;
     const int first_m = group * GM;
@@ -169,169 +165,6 @@ __device__ __forceinline__ void gemm_nt_mainloop(const GemmOperands &g, int tm, 
     }
 }
 
-// Software-pipelined variant of the main loop.  One K-step of 64 is four MFMA phases of 16 MFMAs
-// per wavefront; fragments are double-buffered in registers so that the LDS reads of phase p+1,
-// the LDS writes of the next operand tile and the buffer loads of the tile after that are all
-// issued in the shadow of the MFMAs of phase p.  The single workgroup barrier of a K-step sits
-// between phases 2 and 3, so MFMAs are queued on both sides of it.  The loop body is branch-free:
-// loads past the end of K stay inside the buffer descriptor (or read as zero) and are never used.
-template <class Cfg>
-__device__ __forceinline__ void gemm_nt_mainloop_pipelined(const GemmOperands &g, int tm, int tn, char *smem,
-                                                           f32x16_t (&acc)[Cfg::TM][Cfg::TN])
-{
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
-    static_assert(BK == 64, "four phases of k = 16");
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave / Cfg::WN) * Cfg::WTM;
-    const int wn0 = (wave % Cfg::WN) * Cfg::WTN;
-
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int rows_a = min(BM, g.M - m0), rows_b = min(BN, g.N - n0);
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A + (size_t)m0 * g.lda, (unsigned)((size_t)rows_a * g.lda * 2));
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.B + (size_t)n0 * g.ldb, (unsigned)((size_t)rows_b * g.ldb * 2));
-
-    const int lrow = tid >> 3, lchunk = tid & 7;
-    const unsigned voff_a = (unsigned)lrow * (unsigned)g.lda * 2u + lchunk * 16u;
-    const unsigned voff_b = (unsigned)lrow * (unsigned)g.ldb * 2u + lchunk * 16u;
-    const unsigned pass_a = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.lda * 2u;
-    const unsigned pass_b = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.ldb * 2u;
-    const int lds_w = lrow * 128 + ((lchunk ^ ((lrow >> 1) & 7)) << 4);
-
-    const int frag_row = lane & 31, frag_half = lane >> 5, frag_sw = (lane >> 1) & 7;
-    const int lds_ra = (wm0 + frag_row) * 128;
-    const int lds_rb = Cfg::A_BYTES + (wn0 + frag_row) * 128;
-    int coff[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) coff[kk] = ((kk * 2 + frag_half) ^ frag_sw) << 4;
-
-    // two sets of staging registers: while one operand tile moves from registers to LDS the loads
-    // of the next two tiles are in flight (about 128 KB per compute unit)
-    u32x4_t sa[2][Cfg::A_PASSES], sb[2][Cfg::B_PASSES];
-    bf16x8_t fa[2][TM], fb[2][TN];
-
-    auto load_global = [&](int kt, int set) {
-        const int soff = kt * BK * 2;
-#pragma unroll
-        for (int p = 0; p < Cfg::A_PASSES; ++p)
-            sa[set][p] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(voff_a + p * pass_a), soff, 0);
-#pragma unroll
-        for (int p = 0; p < Cfg::B_PASSES; ++p)
-            sb[set][p] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(voff_b + p * pass_b), soff, 0);
-    };
-    auto store_lds = [&](int stage, int set) {
-        char *base = smem + stage * Cfg::STAGE_BYTES + lds_w;
-#pragma unroll
-        for (int p = 0; p < Cfg::A_PASSES; ++p)
-            *reinterpret_cast<u32x4_t *>(base + p * Cfg::ROWS_PER_PASS * 128) = sa[set][p];
-#pragma unroll
-        for (int p = 0; p < Cfg::B_PASSES; ++p)
-            *reinterpret_cast<u32x4_t *>(base + Cfg::A_BYTES + p * Cfg::ROWS_PER_PASS * 128) = sb[set][p];
-    };
-    auto keep_alive = [&](int set) {
-#pragma unroll
-        for (int p = 0; p < Cfg::A_PASSES; ++p) asm volatile("" ::"v"(sa[set][p]));
-#pragma unroll
-        for (int p = 0; p < Cfg::B_PASSES; ++p) asm volatile("" ::"v"(sb[set][p]));
-    };
-    auto load_frags = [&](const char *st, int kk, int buf) {
-        fa[buf][0] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + coff[kk]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[buf][j] = *reinterpret_cast<const bf16x8_t *>(st + lds_rb + j * 32 * 128 + coff[kk]);
-#pragma unroll
-        for (int i = 1; i < TM; ++i)
-            fa[buf][i] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + i * 32 * 128 + coff[kk]);
-    };
-    auto mfmas = [&](int buf) {
-#ifndef CPH_DBG_NO_MFMA
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
-#endif
-    };
-    // issue order inside one phase: after every few MFMAs one LDS read and a share of the other memory operations
-    constexpr int kMfma = 0x008, kVmemRead = 0x020, kDsRead = 0x100, kDsWrite = 0x200;
-    constexpr int kReads = TM + TN, kMfmaN = TM * TN;
-#ifdef CPH_NO_SCHED
-#define CPH_PHASE_ORDER(OTHER_MASK, OTHER_TOTAL)
-#else
-#define CPH_PHASE_ORDER(OTHER_MASK, OTHER_TOTAL)                                                   \
-    _Pragma("unroll") for (int q = 0; q < kReads; ++q) {                                           \
-        __builtin_amdgcn_sched_group_barrier(kMfma, kMfmaN / kReads, 0);                           \
-        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);                                       \
-        if ((OTHER_TOTAL) > 0) __builtin_amdgcn_sched_group_barrier(OTHER_MASK, (OTHER_TOTAL) / kReads, 0); \
-    }
-#endif
-    // one K-step: compute on stage `cur`, move tile kt+1 (register set `set`) into the other stage,
-    // then refill that register set with tile kt+3
-#if !defined(CPH_DBG_NO_GLOBAL) && !defined(CPH_DBG_NO_DSWRITE)
-#define CPH_DBG_DSWRITE(x) x
-#elif defined(CPH_DBG_NO_DSWRITE)
-#define CPH_DBG_DSWRITE(x) keep_alive(SET_);
-#else
-#define CPH_DBG_DSWRITE(x)
-#endif
-#if !defined(CPH_DBG_NO_GLOBAL) && !defined(CPH_DBG_NO_VMEM)
-#define CPH_DBG_VMEM(x) x
-#else
-#define CPH_DBG_VMEM(x)
-#endif
-#ifndef CPH_DBG_NO_FRAGS
-#define CPH_DBG_FRAGS(x) x
-#else
-#define CPH_DBG_FRAGS(x)
-#endif
-#define CPH_K_STEP(KT_, CUR, SET)                                                                  \
-    {                                                                                              \
-        constexpr int SET_ = SET;                                                                  \
-        (void)SET_;                                                                                \
-        const char *st = smem + (CUR) * Cfg::STAGE_BYTES;                                          \
-        const char *nx = smem + ((CUR) ^ 1) * Cfg::STAGE_BYTES;                                    \
-        CPH_DBG_FRAGS(load_frags(st, 1, 1);)                                                       \
-        CPH_DBG_DSWRITE(store_lds((CUR) ^ 1, SET);)                                                \
-        mfmas(0);                                                                                  \
-        CPH_PHASE_ORDER(kDsWrite, Cfg::A_PASSES + Cfg::B_PASSES)                                   \
-        CPH_DBG_FRAGS(load_frags(st, 2, 0);)                                                       \
-        CPH_DBG_VMEM(load_global((KT_) + 3, SET);)                                                 \
-        mfmas(1);                                                                                  \
-        CPH_PHASE_ORDER(kVmemRead, Cfg::A_PASSES + Cfg::B_PASSES)                                  \
-        CPH_DBG_FRAGS(load_frags(st, 3, 1);)                                                       \
-        mfmas(0);                                                                                  \
-        CPH_PHASE_ORDER(0, 0)                                                                      \
-        __syncthreads(); /* the other stage is complete and nobody reads this one any more */     \
-        CPH_DBG_FRAGS(load_frags(nx, 0, 0);)                                                       \
-        mfmas(1);                                                                                  \
-        CPH_PHASE_ORDER(0, 0)                                                                      \
-    }
-
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int KT = g.K / BK;
-    load_global(0, 0);
-    store_lds(0, 0);
-    __syncthreads();
-    load_global(1, 0);
-    load_global(2, 1);
-    load_frags(smem, 0, 0);
-
-    int kt = 0;
-    for (; kt + 1 < KT; kt += 2) {
-        CPH_K_STEP(kt, 0, 0)
-        CPH_K_STEP(kt + 1, 1, 1)
-    }
-    if (kt < KT) CPH_K_STEP(kt, 0, 0)
-#undef CPH_K_STEP
-#undef CPH_PHASE_ORDER
-}
-
 // Main loop with direct global->LDS loads (no staging registers, no LDS write instructions).
 // Each wavefront load instruction moves 64 x 16 bytes = 8 operand rows of 128 bytes into 1 KB of
 // consecutive LDS; the XOR swizzle is realised by permuting which 16-byte chunk of its row each
@@ -353,11 +186,7 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     constexpr int NLOAD = Cfg::A_PASSES + Cfg::B_PASSES;     // direct loads per wavefront and K-step
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
     static_assert(BK == 64, "four phases of k = 16");
-#ifdef CPH_LOADS_EARLY
-    constexpr int NEARLY = CPH_LOADS_EARLY;                  // loads of tile kt+2 issued right after the barrier
-#else
-    constexpr int NEARLY = NLOAD / 2;
-#endif
+    constexpr int NEARLY = NLOAD / 2;                        // loads of tile kt+2 issued right after the barrier
     static_assert(NEARLY >= 0 && NEARLY <= NLOAD && NFRAG <= NMFMA, "schedule slots");
     typedef __attribute__((address_space(3))) void lds_void;
     const int tid = threadIdx.x;
@@ -485,9 +314,7 @@ __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi ep
     if (!tile_of_block(blockIdx.x, gridDim.x, g.tiles_m, g.tiles_n, tm, tn)) return;
     f32x16_t acc[Cfg::TM][Cfg::TN];
 #if defined(CPH_MAINLOOP_SIMPLE)
-    gemm_nt_mainloop<Cfg>(g, tm, tn, smem, acc);
-#elif defined(CPH_MAINLOOP_STAGED)
-    gemm_nt_mainloop_pipelined<Cfg>(g, tm, tn, smem, acc);
+    gemm_nt_mainloop<Cfg>(g, tm, tn, smem, acc);          // plain reference loop, for debugging builds only
 #else
     gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
 #endif
