@@ -54,6 +54,31 @@ MUTANTS = [
       "test_full_heads_reduce_to_the_shared_unembedding_head"]),
     ("bf16_rounding_width", "double q = nearbyint(ldexp(m, 8));", "double q = nearbyint(ldexp(m, 7));", None,
      ["test_bf16_rounding_helper"]),
+    ("draft_logq_without_gate", "for (int al = 0; al < r; ++al) a[al] = logw[al];",
+     "for (int al = 0; al < r; ++al) a[al] = 0.0 * logw[al];", 2,
+     ["test_draft_frequencies_follow_the_joint"]),
+    ("sequential_weights_not_updated", "for (int al = 0; al < r; ++al) q[al] += lp[(size_t)al * V + tok];",
+     "for (int al = 0; al < r; ++al) q[al] += 0.0 * lp[(size_t)al * V + tok];", None,
+     ["test_sequential_scheme_uses_the_pinned_conditionals", "test_sequential_scheme_samples_the_joint"]),
+    ("balance_target_share", "- 1.0 / r;", "- 1.0 / (r + 1);", None, ["test_aux_balance"]),
+    ("weight_gradient_transposed", "for (int j = 0; j < d; ++j) out[j] += dyk * (double)h[j];",
+     "for (int j = 0; j < d; ++j) out[j] += dyk * (double)h[d - 1 - j];", 0,
+     [("test_gradients_match_central_differences", "W")]),
+    ("unembedding_gradient_without_y", "for (int k = 0; k < d; ++k) out[k] += dzv * y[k];",
+     "for (int k = 0; k < d; ++k) out[k] += dzv;", None,
+     [("test_gradients_match_central_differences", "U")]),
+    ("distill_discount_squared", "for (int k = 0; k < n; ++k, weight *= disc) {",
+     "for (int k = 0; k < n; ++k, weight *= disc * disc) {", 0,
+     ["test_distill_terms_against_library_routines"]),
+    ("distill_terms_swapped", "total += weight * (beta * kl + (1.0 - beta) * ce);",
+     "total += weight * ((1.0 - beta) * kl + beta * ce);", None,
+     ["test_distill_terms_against_library_routines"]),
+    ("distill_prefix_not_applied", "for (int al = 0; al < r; ++al) q[al] += lp[(size_t)al * V + x];",
+     "for (int al = 0; al < r; ++al) q[al] += 0.0 * lp[(size_t)al * V + x];", None,
+     ["test_distill_without_teacher_term_is_the_joint_likelihood", "test_distill_terms_against_library_routines"]),
+    ("distill_backward_discount", "for (int k = 0; k < n; ++k, weight *= disc) {",
+     "for (int k = 0; k < n; ++k, weight *= 1.0) {", 1,
+     [("test_distill_gradients_match_central_differences", "H"), ("test_distill_gradients_match_central_differences", "W")]),
 ]
 
 
