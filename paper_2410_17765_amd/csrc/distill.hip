@@ -8,7 +8,8 @@
 //
 // The per-token distribution p^d_k is a mixture over the r experts, so its logarithm couples the r head rows
 // of one (t, k).  Those rows are adjacent (m = (t n + k) r + a) and, for r in {1, 2, 4, 8}, sit in the four
-// accumulator registers of one 8-row group of the MFMA result layout (and, for r = 8, in both lane halves):
+// accumulator registers a lane holds of one 16x16 block of the MFMA result (and, for r = 8, in two neighbouring
+// 16-lane groups):
 // the epilogues below form log p^d_k[v] inside the tile, with no logits stored.
 //
 // Forward:  the per-row part of the training loss (gate, y, statistics of z, lse, C) -> teacher log-normalisers
@@ -173,7 +174,7 @@ __global__ void k_distill_bwd_rows(size_t M, int n, int r, const float2 *__restr
 // epilogues
 // ------------------------------------------------------------------------------------------
 
-// log of the mixture over the R experts of a token, for the four registers jj of one 8-row group:
+// log of the mixture over the R experts of a token, for the four registers jj (four consecutive rows) of a block:
 // l[jj] = log(qhat_a P_a[v]) of this lane's column; on return lm[jj] = log sum_a exp(l_a) of jj's group.
 template <int R>
 __device__ __forceinline__ void group_log_mixture(const float (&l)[4], float (&lm)[4])
@@ -191,9 +192,9 @@ __device__ __forceinline__ void group_log_mixture(const float (&l)[4], float (&l
         }
     } else {
         float mx = fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3]));
-        if (R == 8) mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));            // the other four rows: other lane half
+        if (R == 8) mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));            // the other four rows: neighbouring 16-lane group
         float s = __expf(l[0] - mx) + __expf(l[1] - mx) + __expf(l[2] - mx) + __expf(l[3] - mx);
-        if (R == 8) s += __shfl_xor(s, 32, kWave);
+        if (R == 8) s += __shfl_xor(s, 16, kWave);
         const float v = mx + __logf(s);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) lm[jj] = v;
@@ -211,58 +212,53 @@ struct EpiDistillStats {
     const float *tlse;       // [M / R]
     int M, V;
     template <class C>
-    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int tn, char *) const
+    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int tn, char *) const
     {
         const int slot = tn * C::WN + (wave % C::WN);
-        const int half = lane >> 5;
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i) {
+        for (int i = 0; i < C::TM16; ++i) {
+            const int rbase = row0 + 16 * i + 4 * (lane >> 4);
+            float lse_[4], lq_[4], tl_[4];
+            size_t trow_[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int rbase = row0 + 32 * i + 8 * q + 4 * half;
-                float lse_[4], lq_[4], tl_[4];
-                size_t trow_[4];
+            for (int jj = 0; jj < 4; ++jj) {
+                const int rc = min(rbase + jj, M - 1);
+                const float2 ra = rowa[rc];
+                lse_[jj] = ra.x;
+                lq_[jj] = ra.y;
+                const int g = rc / R;
+                tl_[jj] = tlse[g];
+                trow_[jj] = (size_t)g * V;
+            }
+            float S[4] = {0.f, 0.f, 0.f, 0.f}, KL[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < C::TN16; ++j) {
+                const int col = col0 + acc_col(j, lane);
+                const bool cv = col < V;
+                const int cc = cv ? col : V - 1;
+                float l[4], lm[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) l[jj] = acc[i][j][jj] - lse_[jj] + lq_[jj];
+                group_log_mixture<R>(l, lm);
+                float lpc[4];
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
-                    const int rc = min(rbase + jj, M - 1);
-                    const float2 ra = rowa[rc];
-                    lse_[jj] = ra.x;
-                    lq_[jj] = ra.y;
-                    const int g = rc / R;
-                    tl_[jj] = tlse[g];
-                    trow_[jj] = (size_t)g * V;
-                }
-                float S[4] = {0.f, 0.f, 0.f, 0.f}, KL[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < C::TN; ++j) {
-                    const int col = col0 + acc_col(j, lane);
-                    const bool cv = col < V;
-                    const int cc = cv ? col : V - 1;
-                    float l[4], lm[4];
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) l[jj] = acc[i][j][4 * q + jj] - lse_[jj] + lq_[jj];
-                    group_log_mixture<R>(l, lm);
-                    float lpc[4];
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        if (R >= 4 && jj > 0) lpc[jj] = lpc[0];                      // one token per four rows
-                        else if (R == 2 && (jj & 1)) lpc[jj] = lpc[jj - 1];
-                        else lpc[jj] = bf16_to_f32(TZ[trow_[jj] + cc]) - tl_[jj];
-                    }
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        const float pc = cv ? __expf(lpc[jj]) : 0.f;
-                        S[jj] += pc * __expf(l[jj] - lm[jj]);
-                        KL[jj] += pc * (lpc[jj] - lm[jj]);
-                    }
+                    if (R >= 4 && jj > 0) lpc[jj] = lpc[0];                      // one token per four rows
+                    else if (R == 2 && (jj & 1)) lpc[jj] = lpc[jj - 1];
+                    else lpc[jj] = bf16_to_f32(TZ[trow_[jj] + cc]) - tl_[jj];
                 }
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
-                    const float s = row16_sum(S[jj]), kl = row16_sum(KL[jj]);
-                    const float so = dpp_move<0x142, 0xA>(0.f, s), ko = dpp_move<0x142, 0xA>(0.f, kl);
-                    const int row = rbase + jj;
-                    if ((lane & 31) == 16 && row < M) part[(size_t)row * parts + slot] = make_float2(s + so, kl + ko);
+                    const float pc = cv ? __expf(lpc[jj]) : 0.f;
+                    S[jj] += pc * __expf(l[jj] - lm[jj]);
+                    KL[jj] += pc * (lpc[jj] - lm[jj]);
                 }
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const float s = row16_sum(S[jj]), kl = row16_sum(KL[jj]);
+                const int row = rbase + jj;
+                if ((lane & 15) == 0 && row < M) part[(size_t)row * parts + slot] = make_float2(s, kl);
             }
         }
     }
@@ -280,9 +276,10 @@ struct EpiDzDistill {
     const bf16_t *TZ;        // chunk-relative [Mc / R, V]; Mc / R * V < 2^31
     int Mc, Mcp, V, Vp;
     template <class C>
-    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
-        constexpr int RG = R < 4 ? R : 4;        // rows of one token among the four registers of a group
+        static_assert(C::WTM == 64 || C::WTM == 128, "sub-tiles of 64 or 128 rows");
+        constexpr int RG = R < 4 ? R : 4;        // rows of one token among the four registers of a block
         constexpr int NG = 4 / RG;               // tokens among them
         auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
         // 64 rows at a time: turn their logits into gradients and write them out at once, so that the
@@ -290,73 +287,68 @@ struct EpiDzDistill {
         convert<C, RG, NG, 0>(acc, row0, col0, lane);
         store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
         if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
-        if (C::TM > 2) {
+        if (C::WTM > 64) {
             convert<C, RG, NG, 1>(acc, row0, col0, lane);
             store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
             if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         }
     }
 
-    // logits -> gradients, in place, for the 32-row blocks 2 IP and 2 IP + 1
+    // logits -> gradients, in place, for the 16-row blocks 4 IP .. 4 IP + 3
     template <class C, int RG, int NG, int IP>
-    __device__ __forceinline__ void convert(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane) const
+    __device__ __forceinline__ void convert(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane) const
     {
-        static_assert(C::TM == 2 || C::TM == 4, "sub-tiles of 64 or 128 rows");
-        const int half = lane >> 5;
         const float4 *__restrict__ rinfo = rowinfo;
         const float4 *__restrict__ ginfo = grp;
         const bf16_t *__restrict__ tz = TZ;
 #pragma unroll
-        for (int i = 2 * IP; i < 2 * IP + 2; ++i) {
+        for (int i = 4 * IP; i < 4 * IP + 4; ++i) {
+            const int rbase = row0 + 16 * i + 4 * (lane >> 4);
+            float lse_[4], lq_[4], c1_[4], c2_[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int rbase = row0 + 32 * i + 8 * q + 4 * half;
-                float lse_[4], lq_[4], c1_[4], c2_[4];
+            for (int jj = 0; jj < 4; ++jj) {
+                const int row = rbase + jj;
+                const float4 ri = rinfo[min(row, Mc - 1)];
+                lse_[jj] = ri.x;
+                lq_[jj] = ri.y;
+                c1_[jj] = row < Mc ? ri.z : 0.f;
+                c2_[jj] = row < Mc ? ri.w : 0.f;
+            }
+            float tl_[NG], c3_[NG];
+            int x_[NG], toff_[NG];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const int row = rbase + jj;
-                    const float4 ri = rinfo[min(row, Mc - 1)];
-                    lse_[jj] = ri.x;
-                    lq_[jj] = ri.y;
-                    c1_[jj] = row < Mc ? ri.z : 0.f;
-                    c2_[jj] = row < Mc ? ri.w : 0.f;
-                }
-                float tl_[NG], c3_[NG];
-                int x_[NG], toff_[NG];
+            for (int gi = 0; gi < NG; ++gi) {
+                const int row = rbase + gi * RG;
+                const int g = min(row, Mc - 1) / R;
+                const float4 gv = ginfo[g];
+                tl_[gi] = gv.x;
+                c3_[gi] = row < Mc ? gv.y : 0.f;
+                x_[gi] = __float_as_int(gv.z);
+                toff_[gi] = g * V;
+            }
+#pragma unroll
+            for (int j = 0; j < C::TN16; ++j) {
+                const int col = col0 + acc_col(j, lane);
+                const bool cv = col < V;
+                const int cc = cv ? col : V - 1;
+                float l[4], lm[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) l[jj] = acc[i][j][jj] - lse_[jj] + lq_[jj];
+                group_log_mixture<R>(l, lm);
 #pragma unroll
                 for (int gi = 0; gi < NG; ++gi) {
-                    const int row = rbase + gi * RG;
-                    const int g = min(row, Mc - 1) / R;
-                    const float4 gv = ginfo[g];
-                    tl_[gi] = gv.x;
-                    c3_[gi] = row < Mc ? gv.y : 0.f;
-                    x_[gi] = __float_as_int(gv.z);
-                    toff_[gi] = g * V;
-                }
+                    const float lpc = bf16_to_f32(tz[toff_[gi] + cc]) - tl_[gi];
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j) {
-                    const int col = col0 + acc_col(j, lane);
-                    const bool cv = col < V;
-                    const int cc = cv ? col : V - 1;
-                    float l[4], lm[4];
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) l[jj] = acc[i][j][4 * q + jj] - lse_[jj] + lq_[jj];
-                    group_log_mixture<R>(l, lm);
-#pragma unroll
-                    for (int gi = 0; gi < NG; ++gi) {
-                        const float lpc = bf16_to_f32(tz[toff_[gi] + cc]) - tl_[gi];
-#pragma unroll
-                        for (int e = 0; e < RG; ++e) {
-                            const int jj = gi * RG + e;
-                            const float P = __expf(l[jj] - lq_[jj]);
-                            const float g = c1_[jj] * P - c3_[gi] * __expf(lpc + l[jj] - lm[jj]) + (col == x_[gi] ? c2_[jj] : 0.f);
-                            acc[i][j][4 * q + jj] = cv ? g : 0.f;
-                        }
+                    for (int e = 0; e < RG; ++e) {
+                        const int jj = gi * RG + e;
+                        const float P = __expf(l[jj] - lq_[jj]);
+                        const float g = c1_[jj] * P - c3_[gi] * __expf(lpc + l[jj] - lm[jj]) + (col == x_[gi] ? c2_[jj] : 0.f);
+                        acc[i][j][jj] = cv ? g : 0.f;
                     }
                 }
-                // keeps the row loads of later groups from being hoisted (they would spill registers)
-                asm volatile("" ::: "memory");
             }
+            // keeps the row loads of later blocks from being hoisted (they would spill registers)
+            asm volatile("" ::: "memory");
         }
     }
 };

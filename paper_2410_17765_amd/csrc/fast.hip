@@ -30,7 +30,7 @@ struct EpiStoreBf16 {
     long ldc;
     int M, N;
     template <class C>
-    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
         store_tile_bf16<C>(smem, wave, lane, row0, col0, M, N, hi, ldc,
                            [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); });
@@ -49,7 +49,7 @@ struct EpiStoreF32 {
     int M, N;
     int accumulate;
     template <class Cf>
-    __device__ void run(f32x16_t (&acc)[Cf::TM][Cf::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    __device__ void run(f32x4_t (&acc)[Cf::TM16][Cf::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
         store_tile_f32<Cf>(smem, wave, lane, row0, col0, M, N, C, ldc, accumulate != 0,
                            [&](int i, int j, int v, int, int) { return acc[i][j][v]; });
@@ -59,43 +59,37 @@ struct EpiStoreF32 {
 // Running statistics of the logits (eq. 5 in log space): for every row of the wavefront's
 // sub-tile the maximum and the sum of exp(z - max) over its columns.  One (max, sum) pair per
 // row and per (tile column, wavefront column) goes to `part`; the logits themselves are dropped.
-// Each 16-lane row first forms its own (max, sum); the two rows that share an output row are merged
-// in lanes 16..31 / 48..63, whose first lane writes the pair.
+// A row of the sub-tile lives in one 16-lane group (its column blocks in the lane's registers), so a
+// wavefront reduces four rows at a time with moves inside 16 lanes; the group's first lane writes the pair.
 struct EpiRowStats {
     float2 *part;   // [M, parts]
     int parts;      // tiles_n * WN
     int M, V;
     template <class C>
-    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int tn, char *) const
+    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int tn, char *) const
     {
         const int slot = tn * C::WN + (wave % C::WN);
-        bool valid[C::TN];
+        bool valid[C::TN16];
 #pragma unroll
-        for (int j = 0; j < C::TN; ++j) valid[j] = col0 + acc_col(j, lane) < V;
+        for (int j = 0; j < C::TN16; ++j) valid[j] = col0 + acc_col(j, lane) < V;
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i)
+        for (int i = 0; i < C::TM16; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
+            for (int v = 0; v < 4; ++v) {
                 float mx = -INFINITY;
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j)
+                for (int j = 0; j < C::TN16; ++j)
                     if (valid[j]) mx = fmaxf(mx, acc[i][j][v]);
                 mx = row16_max(mx);
                 const float ref = (mx == -INFINITY) ? 0.f : mx;
                 float s = 0.f;
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j)
+                for (int j = 0; j < C::TN16; ++j)
                     if (valid[j]) s += __expf(acc[i][j][v] - ref);
                 s = row16_sum(s);
-                // rows 1 and 3 of the wavefront fetch the pair of rows 0 and 2 and merge
-                const float mo = dpp_move<0x142, 0xA>(-INFINITY, mx);
-                const float so = dpp_move<0x142, 0xA>(0.f, s);
-                const float mm = fmaxf(mx, mo);
-                const float mref = (mm == -INFINITY) ? 0.f : mm;
-                const float ss = s * __expf(ref - mref) + so * __expf(((mo == -INFINITY) ? 0.f : mo) - mref);
                 const int r = row0 + acc_row(i, v, lane);
-                if ((lane & 31) == 16 && r < M)
-                    part[(size_t)r * parts + slot] = make_float2(mm, (mm == -INFINITY) ? 0.f : ss);
+                if ((lane & 15) == 0 && r < M)
+                    part[(size_t)r * parts + slot] = make_float2(mx, (mx == -INFINITY) ? 0.f : s);
             }
     }
 };
@@ -112,9 +106,9 @@ struct EpiDz {
     const float4 *rowinfo;   // chunk-relative: {lse, coef (zero for dropped factors), target as int bits, -}
     int Mc, Mcp, V, Vp;
     template <class C>
-    __device__ void run(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane, int wave, int, char *smem) const
+    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
-        static_assert(C::TM == 2 || C::TM == 4, "sub-tiles of 64 or 128 rows");
+        static_assert(C::WTM == 64 || C::WTM == 128, "sub-tiles of 64 or 128 rows");
         // after convert() the even accumulator of a pair of rows holds both gradients as two bf16
         auto dz = [&](int i, int j, int v, int, int) {
             const uint32_t pk = __float_as_uint(acc[i][j][v & ~1]);
@@ -125,57 +119,57 @@ struct EpiDz {
         convert<C, 0>(acc, row0, col0, lane);
         store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
         if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
-        if (C::TM > 2) {
+        if (C::WTM > 64) {
             convert<C, 1>(acc, row0, col0, lane);
             store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
             if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         }
     }
 
-    // Logits -> gradients for the 32-row blocks 2 IP and 2 IP + 1, two consecutive rows at a time; the pair
+    // Logits -> gradients for the 16-row blocks 4 IP .. 4 IP + 3, two consecutive rows at a time; the pair
     // is rounded to bf16 by one conversion and kept in the even row's accumulator.  The one-hot term touches
     // one element of a row, so it is a branch that a wavefront takes only where a target falls into its
     // columns.
     template <class C, int IP>
-    __device__ __forceinline__ void convert(f32x16_t (&acc)[C::TM][C::TN], int row0, int col0, int lane) const
+    __device__ __forceinline__ void convert(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane) const
     {
         const float4 *__restrict__ info = rowinfo;
-        const int lcol = col0 + (lane & 31);
-        const bool ragged = col0 + 32 * C::TN > V;       // the same for the whole wavefront
+        const int lcol = col0 + (lane & 15);
+        const bool ragged = col0 + 16 * C::TN16 > V;     // the same for the whole wavefront
 #pragma unroll
-        for (int i = 2 * IP; i < 2 * IP + 2; ++i) {
+        for (int i = 4 * IP; i < 4 * IP + 4; ++i) {
 #pragma unroll
-            for (int v = 0; v < 16; v += 2) {
+            for (int v = 0; v < 4; v += 2) {
                 const int row = row0 + acc_row(i, v, lane);          // rows row and row + 1
                 const float4 ra = info[row < Mc ? row : Mc - 1];
                 const float4 rb = info[row + 1 < Mc ? row + 1 : Mc - 1];
                 // rows past the chunk hold zero logits: coefficient 0 and offset 0 keep their product finite
                 const float cfa = row < Mc ? ra.y : 0.f, cfb = row + 1 < Mc ? rb.y : 0.f;
                 const float la = row < Mc ? ra.x : 0.f, lb = row + 1 < Mc ? rb.x : 0.f;
-                float ga[C::TN], gb[C::TN];
+                float ga[C::TN16], gb[C::TN16];
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j) {
+                for (int j = 0; j < C::TN16; ++j) {
                     // z - lse first: exact where the logit is close to the log-normaliser (p close to 1)
                     ga[j] = cfa * __builtin_amdgcn_exp2f((acc[i][j][v] - la) * kLog2e);
                     gb[j] = cfb * __builtin_amdgcn_exp2f((acc[i][j][v + 1] - lb) * kLog2e);
                 }
-                const int xa = __float_as_int(ra.z) - lcol, xb = __float_as_int(rb.z) - lcol;   // 32 j at the target
-                const bool ha = (xa & 31) == 0 && (unsigned)xa < 32u * C::TN;
-                const bool hb = (xb & 31) == 0 && (unsigned)xb < 32u * C::TN;
+                const int xa = __float_as_int(ra.z) - lcol, xb = __float_as_int(rb.z) - lcol;   // 16 j at the target
+                const bool ha = (xa & 15) == 0 && (unsigned)xa < 16u * C::TN16;
+                const bool hb = (xb & 15) == 0 && (unsigned)xb < 16u * C::TN16;
                 if (ha || hb) {
 #pragma unroll
-                    for (int j = 0; j < C::TN; ++j) {
-                        if (ha && xa == 32 * j) ga[j] -= cfa;
-                        if (hb && xb == 32 * j) gb[j] -= cfb;
+                    for (int j = 0; j < C::TN16; ++j) {
+                        if (ha && xa == 16 * j) ga[j] -= cfa;
+                        if (hb && xb == 16 * j) gb[j] -= cfb;
                     }
                 }
                 if (ragged) {
 #pragma unroll
-                    for (int j = 0; j < C::TN; ++j)
-                        if (lcol + 32 * j >= V) { ga[j] = 0.f; gb[j] = 0.f; }
+                    for (int j = 0; j < C::TN16; ++j)
+                        if (lcol + 16 * j >= V) { ga[j] = 0.f; gb[j] = 0.f; }
                 }
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j) acc[i][j][v] = __uint_as_float(f32x2_to_bf16x2(ga[j], gb[j]));
+                for (int j = 0; j < C::TN16; ++j) acc[i][j][v] = __uint_as_float(f32x2_to_bf16x2(ga[j], gb[j]));
             }
             // keeps the per-row loads of the next block from being hoisted (they would spill registers)
             asm volatile("" ::: "memory");
