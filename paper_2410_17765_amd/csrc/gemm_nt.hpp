@@ -100,8 +100,12 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     constexpr int HA = TM / 2, HB = TN / 2;                  // A fragments per row half, B fragments per read half
     constexpr int NLOAD = Cfg::A_PASSES + Cfg::B_PASSES;
     constexpr int NM = HA * TN;                              // MFMAs per phase
-    constexpr int NEARLY = NLOAD / 2;
-    static_assert(BK == 64 && TM % 2 == 0 && TN % 2 == 0 && TN + HA <= NM, "schedule slots");
+    // loads of a tile per phase, from the phase after the barrier that frees its stage: phases 3, 0, 1, 2.
+    // Measured on the three large product shapes: 8/8/0/0 and 10/6/0/0 lead (the latter by about 1 %),
+    // 12/4 loses 3-5 %, 16/0 and any load in phases 1 or 2 (less time to land) lose 10-30 %.
+    constexpr int L3 = NLOAD * 5 / 8, L0 = NLOAD - L3, L1 = 0, L2 = 0;
+    constexpr int NEARLY = L3;
+    static_assert(BK == 64 && TM % 2 == 0 && TN % 2 == 0 && TN + HA <= NM && L2 >= 0, "schedule slots");
     typedef __attribute__((address_space(3))) void lds_void;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -212,9 +216,9 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
         const int cur = (KT_) & 1;                                                                 \
         const char *st = smem + cur * Cfg::STAGE_BYTES;                                            \
         const char *nx = smem + (cur ^ 1) * Cfg::STAGE_BYTES;                                      \
-        CPH_PHASE16(0, 0, 0, reads0, HA + HB, LOAD_NEXT, (KT_) + 1, cur ^ 1, NEARLY, NLOAD - NEARLY) \
-        CPH_PHASE16(1, 0, 1, reads1, HB + HA, false, 0, 0, 0, 0)                                   \
-        CPH_PHASE16(0, 1, 0, reads2, HA, false, 0, 0, 0, 0)                                        \
+        CPH_PHASE16(0, 0, 0, reads0, HA + HB, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3, L0)               \
+        CPH_PHASE16(1, 0, 1, reads1, HB + HA, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3 + L0, L1)          \
+        CPH_PHASE16(0, 1, 0, reads2, HA, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3 + L0 + L1, L2)          \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): tile kt+1 is complete in the other stage */ \
         __syncthreads();                                                                           \
         CPH_PHASE16(1, 1, 1, reads3, TN + HA, LOAD_AFTER, (KT_) + 2, cur, 0, NEARLY)               \
@@ -337,6 +341,7 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
                 *reinterpret_cast<u32x4_t *>(dst + (size_t)grow * ld + gcol) = val;
         }
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);              // conversions of the next pass stay behind this one's stores
     }
 }
 
@@ -390,6 +395,7 @@ __device__ __forceinline__ void store_tile_bf16_transposed(char *smem, int wave,
                 *reinterpret_cast<u32x4_t *>(dst + (size_t)gcol * ld + grow) = val;
         }
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -433,6 +439,7 @@ __device__ __forceinline__ void store_tile_f32(char *smem, int wave, int lane, i
             }
         }
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
