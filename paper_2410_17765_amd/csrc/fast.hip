@@ -1092,7 +1092,7 @@ int fast_fwd_rows(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     float2 *part = at<float2>(ws, f.part);
 
     launch_gate(ds, Hv, Gv, logw, w, st);                                                      // eq. 7
-    launch_gemm_nt<Cfg>("gemm_y", H, d, T, W, d, nrd, d, EpiStoreBf16{Y, Ylo, (long)nrd, T, nrd}, st);   // y = W_sa h
+    launch_gemm_nt<Cfg>("gemm_y", H, d, T, W, d, nrd, d, EpiStoreBf16{Y, Ylo, (long)nrd, T, nrd}, st, kGroupRowsNarrow);   // y = W_sa h
     launch_gemm_nt<Cfg>("gemm_z_stats", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);  // z = U y, statistics
     k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, ds.r, f.parts, part, Y, Ylo, U, X, lse, C);
     out->lse = lse; out->w = w; out->gamma = gamma; out->logw = logw; out->C = C; out->Y = Y;
@@ -1139,23 +1139,25 @@ int fast_bwd_from_dz(const cp_head_desc &ds, const void *Hv, const void *Wv, con
         // cover the padding columns V..Vp-1, which the epilogue zero-fills
         dz_launch(user, Yc, Mc, Mcp, m0, dZ, (long)Vp, dU ? dZt : nullptr, ldM, st);
         // dY = dz U   (contraction over the vocabulary)
-        launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st);
+        launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st,
+                            kGroupRowsNarrow);
         if (dU) {
             // dU += dz^T Y   (contraction over the rows of the chunk)
             transpose_bf16(Yc, d, Mc, d, Yt, ldM, Mcp, st);           // Yt[d, Mcp]
-            launch_gemm_nt<Cfg>("gemm_du", dZt, ldM, V, Yt, ldM, d, Mcp, EpiStoreF32{dU, (long)d, V, d, first ? 0 : 1}, st);
+            launch_gemm_nt<Cfg>("gemm_du", dZt, ldM, V, Yt, ldM, d, Mcp, EpiStoreF32{dU, (long)d, V, d, first ? 0 : 1}, st,
+                                kGroupRowsNarrow);
         }
         first = 0;
     }
     // dH = dY W + G^T dg   (contraction over (s, a, k))
     transpose_bf16(W, d, (int)nrd, d, Wt, ldN, (int)nrd, st);         // Wt[d, nrd]
-    launch_gemm_nt<Cfg>("gemm_dh", dY, (long)nrd, (int)T, Wt, ldN, d, (int)nrd, EpiStoreF32{dH, (long)d, (int)T, d, 0}, st);
+    launch_gemm_nt<Cfg>("gemm_dh", dY, (long)nrd, (int)T, Wt, ldN, d, (int)nrd, EpiStoreF32{dH, (long)d, (int)T, d, 0}, st, kGroupRowsNarrow);
     k_add_gate_to_dh<<<blocks_for(T * d, kBlock), kBlock, 0, st>>>(T, d, r, G, dg, dH);
     if (dW) {
         // dW_sa = dY_sa^T H   (contraction over positions)
         transpose_bf16(dY, (long)nrd, (int)T, (int)nrd, dYt, ldT, Tp, st);  // dYt[nrd, Tp]
         transpose_bf16(H, d, (int)T, d, Ht, ldT, Tp, st);                   // Ht[d, Tp]
-        launch_gemm_nt<Cfg>("gemm_dw", dYt, ldT, (int)nrd, Ht, ldT, d, Tp, EpiStoreF32{dW, (long)d, (int)nrd, d, 0}, st);
+        launch_gemm_nt<Cfg>("gemm_dw", dYt, ldT, (int)nrd, Ht, ldT, d, Tp, EpiStoreF32{dW, (long)d, (int)nrd, d, 0}, st, kGroupRowsNarrow);
     }
     if (dG) {
         float *part = at<float>(ws, b.dGpart);
@@ -1394,11 +1396,12 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Fv, c
             // dH += dz F_sa   (contraction over the vocabulary)
             transpose_bf16(Fsa, d, V, d, Ft, ldV, Vp, st);            // Ft[d, Vp]
             launch_gemm_nt<Cfg>("full_gemm_dh", dZ, Vp, Tc, Ft, ldV, d, Vp,
-                                EpiStoreF32{dH + t0 * d, (long)d, Tc, d, sa ? 1 : 0}, st);
+                                EpiStoreF32{dH + t0 * d, (long)d, Tc, d, sa ? 1 : 0}, st, kGroupRowsNarrow);
             // dF_sa += dz^T H   (contraction over the positions of the chunk)
             if (dF)
                 launch_gemm_nt<Cfg>("full_gemm_df", dZt, ldM, V, Ht + t0, ldT, d, Tcp,
-                                    EpiStoreF32{dF + (size_t)sa * V * d, (long)d, V, d, first_chunk ? 0 : 1}, st);
+                                    EpiStoreF32{dF + (size_t)sa * V * d, (long)d, V, d, first_chunk ? 0 : 1}, st,
+                                    kGroupRowsNarrow);
         }
         first_chunk = 0;
     }

@@ -32,6 +32,7 @@ struct GemmOperands {
     long lda, ldb;     // elements
     int M, N, K;       // K % 64 == 0
     int tiles_m, tiles_n;
+    int gm;            // tile rows per group of the workgroup -> tile walk
 };
 
 template <int BM_, int BN_, int WM_, int WN_>
@@ -56,14 +57,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, un
 }
 
 // Workgroup id -> output tile.  Consecutive workgroup ids go round-robin over the 8 XCDs, so the
-// id is first unrolled into a per-XCD contiguous range; inside it tiles are walked in groups of 8
+// id is first unrolled into a per-XCD contiguous range; inside it tiles are walked in groups of GM
 // rows of tiles so that the tiles in flight on one XCD share operand panels in its L2.
-__device__ __forceinline__ bool tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int &tm, int &tn)
+__device__ __forceinline__ bool tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int GM, int &tm, int &tn)
 {
     const int per_xcd = nblocks >> 3;
     const int lid = (bid & 7) * per_xcd + (bid >> 3);
     if (lid >= tiles_m * tiles_n) return false;
-    constexpr int GM = 8;     // 4, 16 and 32 tile rows per group were measured slower
     const int per_group = GM * tiles_n;
     const int group = lid / per_group;
     const int first_m = group * GM;
@@ -73,6 +73,10 @@ __device__ __forceinline__ bool tile_of_block(int bid, int nblocks, int tiles_m,
     tn = in / gsize;
     return true;
 }
+// Tile rows per group of that walk.  8 x 4 tiles in flight per XCD suit the vocabulary-wide products (125 or
+// more tile columns; 16 rows per group cost them 10-25 %); the products with a d-wide output (16 tile columns)
+// and y = W h run 2-5 % faster with 4 x 8, which re-reads their large A operand half as often.
+constexpr int kGroupRowsWide = 8, kGroupRowsNarrow = 4;
 inline int gemm_grid(int tiles_m, int tiles_n) { return (tiles_m * tiles_n + 7) / 8 * 8; }
 
 // The main loop, with direct global->LDS loads (no staging registers, no LDS write instructions) and
@@ -244,7 +248,7 @@ __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi ep
 {
     __shared__ __attribute__((aligned(16))) char smem[Cfg::LDS_BYTES];
     int tm, tn;
-    if (!tile_of_block(blockIdx.x, gridDim.x, g.tiles_m, g.tiles_n, tm, tn)) return;
+    if (!tile_of_block(blockIdx.x, gridDim.x, g.tiles_m, g.tiles_n, g.gm, tm, tn)) return;
     f32x4_t acc[Cfg::TM16][Cfg::TN16];
     gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -255,13 +259,14 @@ __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi ep
 
 template <class Cfg, class Epi>
 inline void launch_gemm_nt(const char *name, const bf16_t *A, long lda, int M, const bf16_t *B, long ldb, int N, int K,
-                           const Epi &epi, hipStream_t st)
+                           const Epi &epi, hipStream_t st, int gm = kGroupRowsWide)
 {
     ProfileScope prof(name, 2.0 * (double)M * (double)N * (double)K, st);
     GemmOperands g;
     g.A = A; g.B = B; g.lda = lda; g.ldb = ldb; g.M = M; g.N = N; g.K = K;
     g.tiles_m = (M + Cfg::BM - 1) / Cfg::BM;
     g.tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
+    g.gm = gm;
     k_gemm_nt<Cfg, Epi><<<gemm_grid(g.tiles_m, g.tiles_n), Cfg::THREADS, 0, st>>>(g, epi);
 }
 
