@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # there report null.
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
-    ("head_7b", "gemm_z_stats"): (204.961 + 1.273) * GIB,
+    ("head_7b", "gemm_z_stats"): (275.559 + 1.490) * GIB,
     ("head_7b", "gemm_z_dz"): (11.938 + 3.906) * GIB,
     # draft step: L2 fills of its kernels per step at B = 1, 8, 64 (profiles/draft_b8_kernel_stats.md)
     ("draft", 1): 1.9856 * GIB,
