@@ -32,13 +32,15 @@ struct EpiStoreBf16 {
     template <class C>
     __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
-        store_tile_bf16<C>(smem, wave, lane, row0, col0, M, N, hi, ldc,
-                           [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); });
         if (lo)
-            store_tile_bf16<C>(smem, wave, lane, row0, col0, M, N, lo, ldc, [&](int i, int j, int v, int, int) {
+            store_tile_bf16_pair<C>(smem, wave, lane, row0, col0, M, N, hi, lo, ldc, [&](int i, int j, int v) {
                 const float a = acc[i][j][v];
-                return f32_to_bf16(a - bf16_to_f32(f32_to_bf16(a)));
+                const bf16_t h = f32_to_bf16(a);
+                return (uint32_t)h | ((uint32_t)f32_to_bf16(a - bf16_to_f32(h)) << 16);
             });
+        else
+            store_tile_bf16<C>(smem, wave, lane, row0, col0, M, N, hi, ldc,
+                               [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); });
     }
 };
 

@@ -350,6 +350,54 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
     }
 }
 
+// Two bf16 outputs of the same shape from one pass over the accumulators: pair(i, j, v) yields both values
+// (first in the low half); one set of barriers and one staging round serve both.
+template <class Cfg, class F>
+__device__ __forceinline__ void store_tile_bf16_pair(char *smem, int wave, int lane, int row0, int col0, int row_limit,
+                                                     int col_limit /* multiple of 8 */, bf16_t *__restrict__ dst0,
+                                                     bf16_t *__restrict__ dst1, long ld, F pair)
+{
+    constexpr int RS = Cfg::WTN * 2 + 16;
+    constexpr int CPR = Cfg::WTN / 8;
+    constexpr int RPP = kWave / CPR;
+    constexpr int REGION = Cfg::WM * Cfg::WN * 32 * RS;  // staging of one output
+    static_assert(2 * REGION <= Cfg::LDS_BYTES, "staging fits");
+    char *stage = smem + wave * (32 * RS);
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < Cfg::WTM / 32; ++p) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii) {
+            const int i = 2 * p + ii;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int r = 16 * ii + 4 * (lane >> 4) + v;
+#pragma unroll
+                for (int j = 0; j < Cfg::TN16; ++j) {
+                    const int c = j * 16 + (lane & 15);
+                    const uint32_t both = pair(i, j, v);
+                    *reinterpret_cast<bf16_t *>(stage + r * RS + c * 2) = (bf16_t)(both & 0xFFFFu);
+                    *reinterpret_cast<bf16_t *>(stage + REGION + r * RS + c * 2) = (bf16_t)(both >> 16);
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 32 / RPP; ++q) {
+            const int r = q * RPP + lane / CPR, ch = lane % CPR;
+            const u32x4_t v0 = *reinterpret_cast<const u32x4_t *>(stage + r * RS + ch * 16);
+            const u32x4_t v1 = *reinterpret_cast<const u32x4_t *>(stage + REGION + r * RS + ch * 16);
+            const int grow = row0 + p * 32 + r, gcol = col0 + ch * 8;
+            if (grow < row_limit && gcol < col_limit) {
+                *reinterpret_cast<u32x4_t *>(dst0 + (size_t)grow * ld + gcol) = v0;
+                *reinterpret_cast<u32x4_t *>(dst1 + (size_t)grow * ld + gcol) = v1;
+            }
+        }
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // Transposed bf16 output: dst[col * ld + row] = value(i, j, v, row, col).  A lane owns four consecutive
 // rows of one column per accumulator block, so the sub-tile is laid out column-major in LDS (64 rows at
 // a time, 8-byte writes) and leaves as 16-byte pieces of 128-byte column segments.
