@@ -241,8 +241,9 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
 
 // Generic kernel: main loop + epilogue functor.  Epi::run receives the accumulators of one wavefront
 // together with the global row/column of its sub-tile's origin.
-// One workgroup per output tile.  (A persistent variant that walks several tiles per workgroup was
-// measured: the extra live state made the compiler spill accumulators and it ran slower.)
+// One workgroup per output tile.  (A persistent variant, one workgroup per compute unit walking a fixed share
+// of the tiles, was measured twice: it is no faster in isolation and slower inside the step, where a freshly
+// dispatched workgroup goes to whichever compute unit is free first.)
 template <class Cfg, class Epi>
 __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi epi)
 {
