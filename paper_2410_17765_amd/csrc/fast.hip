@@ -204,11 +204,51 @@ __global__ void __launch_bounds__(kBlock) k_transpose_bf16(const bf16_t *__restr
     }
 }
 
+// The same with 16-byte accesses on both sides, for C a multiple of 64 and lds_, ldd, Rp multiples of 8 (and
+// 16-byte aligned bases): a thread loads eight columns of a row at once, the tile crosses LDS, and a thread
+// gathers eight rows of one column for a 16-byte store; a wavefront store covers 8 output rows x 128 bytes.
+__global__ void __launch_bounds__(kBlock) k_transpose_bf16_wide(const bf16_t *__restrict__ src, long lds_, int R,
+                                                                bf16_t *__restrict__ dst, long ldd, int Rp, int tiles_c)
+{
+    __shared__ uint32_t tile[64][33];                   // 64 rows x 64 bf16, one dword of padding per row
+    const int tc = blockIdx.x % tiles_c, tr = blockIdx.x / tiles_c;
+    const int r0 = tr * 64, c0 = tc * 64;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int id = threadIdx.x + kBlock * p, row = id >> 3, ch = id & 7;
+        const int r = r0 + row;
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (r < R) v = *reinterpret_cast<const u32x4_t *>(src + (size_t)r * lds_ + c0 + ch * 8);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) tile[row][ch * 4 + w] = v[w];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int id = threadIdx.x + kBlock * p, col = id >> 3, rg = id & 7;     // source column, group of 8 rows
+        const int shift = (col & 1) * 16;
+        u32x4_t v;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t a = (tile[rg * 8 + 2 * w][col >> 1] >> shift) & 0xFFFFu;
+            const uint32_t b = (tile[rg * 8 + 2 * w + 1][col >> 1] >> shift) & 0xFFFFu;
+            v[w] = a | (b << 16);
+        }
+        const int r = r0 + rg * 8;
+        if (r < Rp) *reinterpret_cast<u32x4_t *>(dst + (size_t)(c0 + col) * ldd + r) = v;
+    }
+}
+
 void transpose_bf16(const bf16_t *src, long lds_, int R, int C, bf16_t *dst, long ldd, int Rp, hipStream_t st)
 {
     ProfileScope prof("transpose", 2.0 * ((double)R * C + (double)Rp * C), st);   // work = bytes moved
     const int tiles_c = (C + 63) / 64, tiles_r = (Rp + 63) / 64;
-    k_transpose_bf16<<<(unsigned)((size_t)tiles_c * tiles_r), kBlock, 0, st>>>(src, lds_, R, C, dst, ldd, Rp, tiles_c);
+    const bool wide = C % 64 == 0 && lds_ % 8 == 0 && ldd % 8 == 0 && Rp % 8 == 0 &&
+                      (reinterpret_cast<uintptr_t>(src) & 15u) == 0 && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+    if (wide)
+        k_transpose_bf16_wide<<<(unsigned)((size_t)tiles_c * tiles_r), kBlock, 0, st>>>(src, lds_, R, dst, ldd, Rp, tiles_c);
+    else
+        k_transpose_bf16<<<(unsigned)((size_t)tiles_c * tiles_r), kBlock, 0, st>>>(src, lds_, R, C, dst, ldd, Rp, tiles_c);
 }
 
 // Per head row: combine the per-tile statistics into the log-normaliser (eq. 5), take the
