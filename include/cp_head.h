@@ -55,7 +55,7 @@ enum {
                                    matrix-core path applies (a second opinion in tests) */
     CP_HEAD_MIN_WORKSPACE = 2   /* flags bit 1: the backward pass holds logit gradients for one
                                    tile of 256 head rows at a time (least workspace, slower)
-                                   instead of its default of 32768 rows or 2 GiB worth of them,
+                                   instead of its default of 32768 rows or 4 GiB worth of them,
                                    whichever is more, up to 8 GiB (0.5 GiB on the plain path) */
 };
 

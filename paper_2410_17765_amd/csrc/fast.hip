@@ -921,18 +921,18 @@ inline FwdWs fwd_ws(const cp_head_desc &ds)
     return f;
 }
 
-// Rows of logit gradients held at a time: about 2 GiB of bf16 at V = 32000, i.e. 32768 rows (4, 8 and
-// 16 GiB were measured there: the dU product gains from fewer accumulation passes, the dz and dY products
-// lose as much or more).  A larger vocabulary keeps the 32768 rows, up to 8 GiB of them: the rows of a
-// chunk are the contraction length of its dU product, and at 8192 rows (2 GiB at V = 128256) that product
-// ran at 1.08 PFLOP/s against 1.25 at 32768.  The count is a multiple of 16 tiles of 256 rows where
-// possible, so that the d-wide products of a chunk (16 tile columns at d = 4096) fill all 256 compute
-// units in whole rounds.
+// Rows of logit gradients held at a time: about 4 GiB of bf16 at V = 32000, i.e. 65536 rows.  Measured on the
+// headline step: 2 GiB 450.4 ms, 4 GiB 447.9, 8 GiB 448.3 (the dU product gains from fewer accumulation passes
+// over its fp32 output, the dz product loses about half of that).  A larger vocabulary keeps at least 32768
+// rows, up to 8 GiB of them: the rows of a chunk are the contraction length of its dU product, and at 8192 rows
+// (2 GiB at V = 128256) that product ran at 1.08 PFLOP/s against 1.25 at 32768.  The count is a multiple of 16
+// tiles of 256 rows where possible, so that the d-wide products of a chunk (16 tile columns at d = 4096) fill
+// all 256 compute units in whole rounds.
 inline size_t bwd_chunk_rows(const cp_head_desc &ds)
 {
     const size_t M = (size_t)ds.T * ds.n * ds.r;
     const size_t Vp = round_up((size_t)ds.V, 64);
-    size_t rows = ((size_t)1 << 31) / (Vp * 2);
+    size_t rows = ((size_t)1 << 32) / (Vp * 2);
     if (rows < 32768) {
         const size_t cap = ((size_t)1 << 33) / (Vp * 2);
         rows = cap < 32768 ? cap : 32768;
