@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0
 # there report null.
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
-    ("head_7b", "gemm_z_stats"): (275.559 + 1.490) * GIB,
-    ("head_7b", "gemm_z_dz"): (11.938 + 3.906) * GIB,
+    ("head_7b", "gemm_z_stats"): (249.304 + 1.358) * GIB,
+    ("head_7b", "gemm_z_dz"): (25.620 + 7.813) * GIB,
     # draft step: L2 fills of its kernels per step at B = 1, 8, 64 (profiles/draft_b8_kernel_stats.md)
     ("draft", 1): 1.9856 * GIB,
     ("draft", 8): (1.0006 + 1.0108 + 0.0020 + 0.0316 + 0.0022) * GIB,
