@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per thread for the loss, per two threads for the full heads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
+    ap.add_argument("--recompute-logits", action="store_true",
+                    help="loss workloads: the backward pass multiplies U y again instead of reading the logits the "
+                         "forward pass kept in HBM (CP_HEAD_KEEP_LOGITS off)")
     ap.add_argument("--no-modes", action="store_true", help="loss workloads: skip the forward-only and frozen-unembedding timings")
     ap.add_argument("--no-draft", action="store_true", help="loss workloads: skip the appended draft-step measurements")
     return ap.parse_args()
@@ -259,13 +262,16 @@ def bench_loss(args):
     t0 = time.time()
     inp = synth.make_inputs(cfg)
     print(f"[bench] inputs for {cfg.name} generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
-    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    keep = cfg.dtype == "bf16" and not args.recompute_logits
+    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype, flags=binding.KEEP_LOGITS if keep else 0)
     H = head.to_device(inp["H"], cfg.dtype)
     X = torch.from_numpy(inp["X"]).to(dev)
     ds = h.desc(cfg.T)
-    ctx = torch.empty(binding.cp_head_ctx_bytes(ds), dtype=torch.uint8, device=dev)
-    ws_bytes = max(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD),
-                   binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_BWD))
+    ctx_bytes = binding.cp_head_ctx_bytes(ds)
+    ctx = torch.empty(ctx_bytes, dtype=torch.uint8, device=dev)
+    ds_re = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, ds.dtype, 0)        # the recompute variant
+    ws_bytes = max(binding.cp_head_workspace_bytes(dsc, op) for dsc in (ds, ds_re)
+                   for op in (binding.OP_LOSS_FWD, binding.OP_LOSS_BWD))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     f32 = dict(dtype=torch.float32, device=dev)
     loss = torch.empty(cfg.T, **f32)
@@ -315,7 +321,9 @@ def bench_loss(args):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
-                   "frozen_u": bool(args.frozen_u), "token": "one position (n future tokens each)"},
+                   "frozen_u": bool(args.frozen_u), "token": "one position (n future tokens each)",
+                   "logits": "kept in HBM between forward and backward" if keep else "recomputed in the backward pass",
+                   "ctx_gib": ctx_bytes / GIB},
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "predicted_tokens_per_s": value * cfg.n,      # every position predicts n tokens
         "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
@@ -357,6 +365,14 @@ def bench_loss(args):
         out["frozen_u"] = {"ms_per_step": t_fr * 1e3, "tokens_per_s": cfg.T / t_fr,
                            "model_tflops": fr_flops / t_fr / 1e12,
                            "model_flop_frac_of_bf16_peak": fr_flops / t_fr / 1e12 / PEAK_BF16_TFLOPS}
+    if keep and not args.no_modes:
+        # the same step with the logits recomputed in the backward pass (least HBM: ctx holds y and per-row values only)
+        def recompute_step():
+            binding.cp_head_loss_fwd(ds_re, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
+            binding.cp_head_loss_bwd(ds_re, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, dU, dG, ws, stream)
+        t_re = timed(recompute_step)
+        out["recompute_logits"] = {"ms_per_step": t_re * 1e3, "tokens_per_s": cfg.T / t_re,
+                                   "ctx_gib": binding.cp_head_ctx_bytes(ds_re) / GIB}
     del ws, ctx, dW, dH, dU, H, h
     torch.cuda.empty_cache()
     if not args.no_draft:

@@ -53,10 +53,17 @@ enum {
 enum {
     CP_HEAD_FORCE_GENERIC = 1,  /* flags bit 0: use the plain fp32 path even where the
                                    matrix-core path applies (a second opinion in tests) */
-    CP_HEAD_MIN_WORKSPACE = 2   /* flags bit 1: the backward pass holds logit gradients for one
+    CP_HEAD_MIN_WORKSPACE = 2,  /* flags bit 1: the backward pass holds logit gradients for one
                                    tile of 256 head rows at a time (least workspace, slower)
                                    instead of its default of 32768 rows or 4 GiB worth of them,
                                    whichever is more, up to 8 GiB (0.5 GiB on the plain path) */
+    CP_HEAD_KEEP_LOGITS = 4     /* flags bit 2, matrix-core path of cp_head_loss_fwd / _bwd only (ignored
+                                   elsewhere): the forward pass keeps every logit in ctx as a 16-bit float
+                                   relative to the maximum of its row over a block of 128 columns
+                                   (T*n*r*roundup(V,64)*2 bytes plus 16 bytes per row and 256 columns), and
+                                   the backward pass reads them back instead of multiplying U y a second
+                                   time.  Trades HBM capacity for a quarter of the backward pass's matrix
+                                   work; set it in the desc of both calls or of neither. */
 };
 
 enum {
@@ -81,7 +88,7 @@ typedef struct cp_head_desc {
     int32_t n;        /* future tokens per position */
     int32_t r;        /* CP rank = number of experts */
     int32_t dtype;    /* CP_HEAD_FP32 or CP_HEAD_BF16 */
-    int32_t flags;    /* OR of CP_HEAD_FORCE_GENERIC, CP_HEAD_MIN_WORKSPACE, or 0 */
+    int32_t flags;    /* OR of CP_HEAD_FORCE_GENERIC, CP_HEAD_MIN_WORKSPACE, CP_HEAD_KEEP_LOGITS, or 0 */
 } cp_head_desc;
 
 /* Human-readable text for an error code (static storage). */
@@ -90,7 +97,8 @@ const char *cp_head_strerror(int code);
 /*
  * Bytes of `ctx` that cp_head_loss_fwd fills and cp_head_loss_bwd reads: the
  * log-normaliser of every factor (eq. 5), the gate weights (eq. 7), the
- * posterior over experts, and the projected states y = W_sa h.  Host-only.
+ * posterior over experts, and the projected states y = W_sa h; with
+ * CP_HEAD_KEEP_LOGITS also the logits.  Host-only.
  */
 int cp_head_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
 
@@ -98,7 +106,8 @@ int cp_head_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
  * Bytes of scratch `workspace` that operation `op` (CP_HEAD_OP_*) needs for
  * this shape.  Host-only.  The size is bounded in the number of positions for
  * the logit-sized buffers: logits and their gradients are only ever held for a
- * bounded chunk of rows, never for all T*n*r rows.
+ * bounded chunk of rows, never for all T*n*r rows (CP_HEAD_KEEP_LOGITS keeps
+ * the logits of all rows, but in ctx, not here).
  */
 int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes);
 

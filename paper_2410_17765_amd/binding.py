@@ -15,6 +15,7 @@ FP32 = 0
 BF16 = 1
 FORCE_GENERIC = 1
 MIN_WORKSPACE = 2
+KEEP_LOGITS = 4
 OP_LOSS_FWD, OP_LOSS_BWD, OP_DRAFT = 0, 1, 2
 OP_FIRST_TOKEN, OP_DRAFT_SEQUENTIAL, OP_AUX_BALANCE = 3, 4, 5
 OP_FULL_LOSS_FWD, OP_FULL_LOSS_BWD = 6, 7

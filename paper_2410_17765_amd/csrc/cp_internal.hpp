@@ -58,9 +58,14 @@ inline T *at(void *base, size_t off) { return reinterpret_cast<T *>(static_cast<
 template <typename T>
 inline const T *at(const void *base, size_t off) { return reinterpret_cast<const T *>(static_cast<const char *>(base) + off); }
 
-// Saved-for-backward buffer: [lse M f32][w T*r f32][gamma T*r f32][Y M*d].
+// Saved-for-backward buffer: [lse M f32][w T*r f32][gamma T*r f32][Y M*d], and on the matrix-core path with
+// CP_HEAD_KEEP_LOGITS also [zpart M*parts float2][zs M*Vp fp16]: the (maximum, sum of exponentials) of every
+// row over each block of 128 columns, and the logits relative to that maximum.
 struct CtxLayout {
-    size_t lse, w, gamma, Y, total;
+    size_t lse, w, gamma, Y, zpart, zs, total;
+    size_t Vp;      // row length of zs
+    int parts;      // blocks of 128 columns per row (two per 256-column tile)
+    bool keep;
 };
 // Y is fp32 on the generic path and bf16 on the matrix-core path.
 inline CtxLayout ctx_layout(const cp_head_desc &ds, bool fast)
@@ -72,6 +77,14 @@ inline CtxLayout ctx_layout(const cp_head_desc &ds, bool fast)
     c.w = off;     off = align_up(off + Tr * 4);
     c.gamma = off; off = align_up(off + Tr * 4);
     c.Y = off;     off = align_up(off + M * ds.d * (fast ? 2 : 4));
+    c.keep = fast && (ds.flags & CP_HEAD_KEEP_LOGITS);
+    c.Vp = round_up((size_t)ds.V, 64);
+    c.parts = ((ds.V + 255) / 256) * 2;
+    c.zpart = c.zs = off;
+    if (c.keep) {
+        c.zpart = off; off = align_up(off + M * c.parts * 8);
+        c.zs = off;    off = align_up(off + M * c.Vp * 2);
+    }
     c.total = off;
     return c;
 }

@@ -692,17 +692,26 @@ int plain_distill_bwd(const cp_head_desc &ds, const void *H, const void *W, cons
 
 }  // namespace
 
-size_t distill_ctx_bytes(const cp_head_desc &ds) { return distill_ctx(ds).total; }
-size_t distill_workspace_bytes(const cp_head_desc &ds, int op)
+// The fine-tuning loss recomputes its logits: the flag that keeps them belongs to the training loss alone.
+static cp_head_desc without_kept_logits(cp_head_desc ds)
 {
+    ds.flags &= ~CP_HEAD_KEEP_LOGITS;
+    return ds;
+}
+
+size_t distill_ctx_bytes(const cp_head_desc &ds) { return distill_ctx(without_kept_logits(ds)).total; }
+size_t distill_workspace_bytes(const cp_head_desc &ds_in, int op)
+{
+    const cp_head_desc ds = without_kept_logits(ds_in);
     if (on_matrix_cores(ds)) return op == CP_HEAD_OP_DISTILL_FWD ? distill_fwd_ws(ds).total : distill_bwd_ws(ds).total;
     return op == CP_HEAD_OP_DISTILL_FWD ? plain_fwd_ws(ds).total : plain_bwd_ws(ds).total;
 }
 
-int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+int distill_loss_fwd(const cp_head_desc &ds_in, const void *H, const void *W, const void *U, const void *G,
                      const int32_t *X, const void *TZ, float beta, float disc, float *loss, void *ctx, void *ws,
                      hipStream_t st)
 {
+    const cp_head_desc ds = without_kept_logits(ds_in);
     if (ds.T == 0) return CP_HEAD_OK;
     if (on_matrix_cores(ds)) return mfma_distill_fwd(ds, H, W, U, G, X, TZ, beta, disc, loss, ctx, ws, st);
     if (ds.dtype == CP_HEAD_FP32)
@@ -710,10 +719,11 @@ int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const
     return plain_distill_fwd<bf16_t>(ds, H, W, U, G, X, (const bf16_t *)TZ, beta, disc, loss, ctx, ws, st);
 }
 
-int distill_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+int distill_loss_bwd(const cp_head_desc &ds_in, const void *H, const void *W, const void *U, const void *G,
                      const int32_t *X, const void *TZ, const float *dloss, float scale, const void *ctx, float *dH,
                      float *dW, float *dU, float *dG, void *ws, hipStream_t st)
 {
+    const cp_head_desc ds = without_kept_logits(ds_in);
     if (ds.T == 0) {
         launch_fill_zero(dW, (size_t)ds.n * ds.r * ds.d * ds.d, st);
         launch_fill_zero(dU, (size_t)ds.V * ds.d, st);

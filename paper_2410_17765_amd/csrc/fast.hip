@@ -96,6 +96,64 @@ struct EpiRowStats {
     }
 };
 
+// 16-bit float (IEEE binary16) bit patterns of the kept logits; round to nearest even, overflow to -inf is
+// harmless (its exponential is the zero that the exact value rounds to as well)
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+
+// The statistics of EpiRowStats, and the logits kept for the backward pass: zs[m, v] = fp16(z - ref) with ref
+// the maximum of row m over the wavefront's 128 columns (the pair that goes to `part`).  Relative to that
+// maximum the large probabilities of a row, which carry its gradient, sit near zero where fp16 resolves
+// 2^-11 or better; a logit 16 below the maximum is kept to 2^-7, i.e. its probability to under one percent.
+struct EpiRowStatsKeep {
+    float2 *part;   // [M, parts]
+    int parts;
+    int M, V;
+    uint16_t *zs;   // [M, ldzs]
+    long ldzs;
+    int Vp;         // columns of zs that are written (V rounded up to 64; those from V on hold junk)
+    template <class C, int P>
+    __device__ __forceinline__ void pass(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave,
+                                         int slot, const bool (&valid)[C::TN16], char *smem) const
+    {
+#pragma unroll
+        for (int i = 2 * P; i < 2 * P + 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < C::TN16; ++j)
+                    if (valid[j]) mx = fmaxf(mx, acc[i][j][v]);
+                mx = row16_max(mx);
+                const float ref = (mx == -INFINITY) ? 0.f : mx;
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < C::TN16; ++j) {
+                    acc[i][j][v] -= ref;
+                    if (valid[j]) s += __expf(acc[i][j][v]);
+                }
+                s = row16_sum(s);
+                const int r = row0 + acc_row(i, v, lane);
+                if ((lane & 15) == 0 && r < M)
+                    part[(size_t)r * parts + slot] = make_float2(mx, (mx == -INFINITY) ? 0.f : s);
+            }
+        auto half = [&](int i, int j, int v, int, int) { return f32_to_f16_bits(acc[i][j][v]); };
+        store_tile_bf16<C, decltype(half), P, P + 1>(smem, wave, lane, row0, col0, M, Vp, zs, ldzs, half);
+    }
+    template <class C>
+    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int tn, char *smem) const
+    {
+        static_assert(C::WTM == 128 && C::WTN == 128, "blocks of 128 columns, four passes of 32 rows");
+        const int slot = tn * C::WN + (wave % C::WN);
+        bool valid[C::TN16];
+#pragma unroll
+        for (int j = 0; j < C::TN16; ++j) valid[j] = col0 + acc_col(j, lane) < V;
+        pass<C, 0>(acc, row0, col0, lane, wave, slot, valid, smem);
+        pass<C, 1>(acc, row0, col0, lane, wave, slot, valid, smem);
+        pass<C, 2>(acc, row0, col0, lane, wave, slot, valid, smem);
+        pass<C, 3>(acc, row0, col0, lane, wave, slot, valid, smem);
+    }
+};
+
 // Softmax gradient (derivative of eq. 8/9 with respect to the logits), written in bf16:
 //   dz[m, v] = coef[m] * (exp(z - lse[m]) - 1[v = x_m]),  zero in the padding columns V..Vp-1;
 // optionally also transposed (dzT[v, m], rows of the chunk padded with zeros up to Mcp), which is the
@@ -178,6 +236,82 @@ struct EpiDz {
         }
     }
 };
+
+// ------------------------------------------------------------------------------------------
+// logit gradients from kept logits
+// ------------------------------------------------------------------------------------------
+
+constexpr int kKeptTile = 128;      // rows and columns of a block's tile; its columns are one block of `part`
+
+// The gradient of EpiDz from the logits that EpiRowStatsKeep left behind instead of from a second product:
+//   dz[m, v] = coef[m] * (exp(zs[m, v] - (lse[m] - max[m, v / 128])) - 1[v = x_m]).
+// A block takes 128 rows x 128 columns.  A thread reads 8 consecutive logits of two consecutive rows (16 bytes
+// each), writes their gradients row-major (16 bytes each) and leaves them, one 32-bit word per column holding
+// the pair of rows, in a column-major LDS tile, from which the transposed copy leaves in 16-byte pieces of
+// 256-byte column segments.  The 16-byte pieces of an LDS column are stored at position (piece ^ column / 8):
+// the sixteen threads that write one pair of rows would otherwise all hit the same banks.
+// zs, part: rows of the chunk (already offset); rowinfo as for EpiDz.  dZt may be null.
+__global__ void __launch_bounds__(kBlock) k_dz_from_kept(const uint16_t *__restrict__ zs, long ldzs,
+                                                         const float2 *__restrict__ part, int parts,
+                                                         const float4 *__restrict__ rowinfo, int Mc, int Mcp, int V,
+                                                         int Vp, bf16_t *__restrict__ dZ, long ldz,
+                                                         bf16_t *__restrict__ dZt, long ldzt, int tiles_c)
+{
+    constexpr int CS = kKeptTile * 2 + 16;              // padded column stride in bytes
+    __shared__ __align__(16) char stage[kKeptTile * CS];
+    typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+    const int tc = blockIdx.x % tiles_c, tr = blockIdx.x / tiles_c;
+    const int t = threadIdx.x, cg = t & 15;
+    const int col = tc * kKeptTile + cg * 8;
+    const bool col_in = col < Vp;                        // Vp is a multiple of 8: all eight columns or none
+#pragma unroll
+    for (int pass = 0; pass < kKeptTile / 32; ++pass) {
+        const int rp = pass * 16 + (t >> 4);             // pair of rows inside the tile
+        const int row = tr * kKeptTile + 2 * rp;
+        float g[2][8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int m = row + h;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) g[h][k] = 0.f;
+            if (col_in && m < Mc) {
+                const float4 info = rowinfo[m];
+                const float off = info.x - part[(size_t)m * parts + tc].x;     // lse - reference of the block
+                const float cf = info.y;
+                const f16x8_t z = __builtin_bit_cast(
+                    f16x8_t, *reinterpret_cast<const u32x4_t *>(zs + (size_t)m * ldzs + col));
+                const int x = __float_as_int(info.z) - col;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    float v = cf * __builtin_amdgcn_exp2f(((float)z[k] - off) * kLog2e);
+                    if (x == k) v -= cf;
+                    g[h][k] = (col + k < V) ? v : 0.f;
+                }
+                u32x4_t out;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) out[k] = f32x2_to_bf16x2(g[h][2 * k], g[h][2 * k + 1]);
+                *reinterpret_cast<u32x4_t *>(dZ + (size_t)m * ldz + col) = out;
+            }
+        }
+        if (dZt) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                *reinterpret_cast<uint32_t *>(stage + (cg * 8 + k) * CS + 16 * ((rp >> 2) ^ cg) + 4 * (rp & 3)) =
+                    f32x2_to_bf16x2(g[0][k], g[1][k]);
+        }
+    }
+    if (!dZt) return;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kKeptTile * 16 / kBlock; ++q) {
+        const int idx = q * kBlock + t;
+        const int c = idx >> 4, pos = idx & 15;
+        const int piece = pos ^ (c >> 3);                // rows 8 piece .. 8 piece + 7 of the tile
+        const u32x4_t val = *reinterpret_cast<const u32x4_t *>(stage + c * CS + pos * 16);
+        const int grow = tr * kKeptTile + piece * 8, gcol = tc * kKeptTile + c;
+        if (grow < Mcp && gcol < V) *reinterpret_cast<u32x4_t *>(dZt + (size_t)gcol * ldzt + grow) = val;
+    }
+}
 
 // ------------------------------------------------------------------------------------------
 // small kernels around the GEMMs
@@ -916,7 +1050,8 @@ inline FwdWs fwd_ws(const cp_head_desc &ds)
     f.logw = take((size_t)ds.T * ds.r * 4);
     f.C = take(M * 4);
     f.Ylo = take(M * ds.d * 2);
-    f.part = take(M * f.parts * sizeof(float2));
+    // with kept logits the statistics live in ctx: the backward pass needs the maxima again
+    f.part = (ds.flags & CP_HEAD_KEEP_LOGITS) ? off : take(M * f.parts * sizeof(float2));
     f.total = off;
     return f;
 }
@@ -1131,11 +1266,16 @@ int fast_fwd_rows(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     bf16_t *Y = at<bf16_t>(ctx, cl.Y);
     float *logw = at<float>(ws, f.logw), *C = at<float>(ws, f.C);
     bf16_t *Ylo = at<bf16_t>(ws, f.Ylo);
-    float2 *part = at<float2>(ws, f.part);
+    float2 *part = cl.keep ? at<float2>(ctx, cl.zpart) : at<float2>(ws, f.part);
+    if (cl.keep && (cl.parts != f.parts || kKeptTile != Cfg::WTN)) return CP_HEAD_ERR_UNSUPPORTED;
 
     launch_gate(ds, Hv, Gv, logw, w, st);                                                      // eq. 7
     launch_gemm_nt<Cfg>("gemm_y", H, d, T, W, d, nrd, d, EpiStoreBf16{Y, Ylo, (long)nrd, T, nrd}, st, kGroupRowsNarrow);   // y = W_sa h
-    launch_gemm_nt<Cfg>("gemm_z_stats", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);  // z = U y, statistics
+    if (cl.keep)                                                                               // z = U y, statistics, z kept
+        launch_gemm_nt<Cfg>("gemm_z_stats_keep", Y, d, (int)M, U, d, V, d,
+                            EpiRowStatsKeep{part, f.parts, (int)M, V, at<uint16_t>(ctx, cl.zs), (long)cl.Vp, (int)cl.Vp}, st);
+    else
+        launch_gemm_nt<Cfg>("gemm_z_stats", Y, d, (int)M, U, d, V, d, EpiRowStats{part, f.parts, (int)M, V}, st);  // z = U y, statistics
     k_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, d, ds.r, f.parts, part, Y, Ylo, U, X, lse, C);
     out->lse = lse; out->w = w; out->gamma = gamma; out->logw = logw; out->C = C; out->Y = Y;
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
@@ -1226,6 +1366,27 @@ void loss_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf
     launch_gemm_nt<Cfg>("gemm_z_dz", Yc, a->d, Mc, a->U, a->d, a->V, a->d,
                         EpiDz{dZ, ldz, dZt, ldzt, a->rowinfo + m0, Mc, Mcp, a->V, (int)ldz}, st);
 }
+
+struct KeptDzArgs {
+    const uint16_t *zs;      // [M, Vp]
+    const float2 *part;      // [M, parts]
+    const float4 *rowinfo;
+    size_t Vp;
+    int parts, V;
+};
+// the same dz from the logits kept by the forward pass
+void kept_dz_launch(void *user, const bf16_t *, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt, long ldzt,
+                    hipStream_t st)
+{
+    const KeptDzArgs *a = static_cast<const KeptDzArgs *>(user);
+    const int tiles_c = (int)((a->Vp + kKeptTile - 1) / kKeptTile);
+    const size_t tiles_r = ((size_t)Mcp + kKeptTile - 1) / kKeptTile;
+    // algorithmic traffic: the logits read once, the gradients written once or twice
+    ProfileScope scope("dz_from_kept", (double)Mc * a->Vp * 2.0 * (dZt ? 3.0 : 2.0), st);
+    k_dz_from_kept<<<(unsigned)(tiles_r * tiles_c), kBlock, 0, st>>>(a->zs + m0 * a->Vp, (long)a->Vp, a->part + m0 * a->parts,
+                                                                       a->parts, a->rowinfo + m0, Mc, Mcp, a->V, (int)ldz,
+                                                                       dZ, ldz, dZt, ldzt, tiles_c);
+}
 }  // namespace
 
 int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
@@ -1248,6 +1409,10 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     float4 *rowinfo = at<float4>(ws, b.coef);
     float *dg = at<float>(ws, b.dg);
     k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, lse, dloss, scale, X, rowinfo, dg);
+    if (cl.keep) {
+        KeptDzArgs kept{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), rowinfo, cl.Vp, cl.parts, V};
+        return fast_bwd_from_dz(ds, Hv, Wv, Uv, Gv, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, kept_dz_launch, &kept, st);
+    }
     LossDzArgs args{(const bf16_t *)Uv, rowinfo, d, V};
     return fast_bwd_from_dz(ds, Hv, Wv, Uv, Gv, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, loss_dz_launch, &args, st);
 }

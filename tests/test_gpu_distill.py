@@ -124,6 +124,18 @@ def test_matches_training_loss_without_teacher_term(gpu):
         assert rel_fro(g1[k], g2[k]) <= 5e-3, k
 
 
+def test_flag_for_kept_logits_is_ignored(gpu):
+    """CP_HEAD_KEEP_LOGITS (4) belongs to the training loss: here it changes neither sizes nor results."""
+    cfg = synth.HeadConfig("distill_keep_flag", T=150, d=128, V=1000, n=2, r=4)
+    inp = synth.make_inputs(cfg)
+    TZ = synth.teacher_logits(cfg)
+    l0, g0 = run(gpu, cfg, inp, TZ, 0.9, 0.8)
+    l1, g1 = run(gpu, cfg, inp, TZ, 0.9, 0.8, flags=4)
+    np.testing.assert_array_equal(l0, l1)
+    for k in g0:
+        np.testing.assert_array_equal(g0[k], g1[k])
+
+
 def test_frozen_unembedding_and_empty_batch(gpu):
     import torch
     cfg = synth.HeadConfig("distill_opts", T=130, d=64, V=300, n=2, r=2)

@@ -44,6 +44,18 @@ CASES = [
 ]
 
 
+_ORACLE_RESULTS = {}
+
+
+def oracle_results(oracle, cfg, inp, dloss):
+    """The oracle's loss and gradients of a case; the cases with kept logits use the same inputs again."""
+    if cfg.name not in _ORACLE_RESULTS:
+        ref = oracle.loss_fwd(inp["H"], inp["W"], inp["U"], inp["G"], inp["X"])
+        gref = oracle.loss_bwd(inp["H"], inp["W"], inp["U"], inp["G"], inp["X"], dloss)
+        _ORACLE_RESULTS[cfg.name] = (ref, gref)
+    return _ORACLE_RESULTS[cfg.name]
+
+
 @pytest.mark.parametrize("cfg,flags", CASES, ids=lambda c: c.name if hasattr(c, "name") else str(c))
 def test_loss_and_gradients(gpu, oracle, cfg, flags):
     print(f"case {cfg} flags={flags}", flush=True)
@@ -51,11 +63,10 @@ def test_loss_and_gradients(gpu, oracle, cfg, flags):
     inp["X"][::7, 0] = -1                       # a few dropped factors
     dloss = synth.upstream_grad(cfg.T)
     loss, grads = run_loss(gpu, cfg, inp, dloss, flags=flags)
-    ref = oracle.loss_fwd(inp["H"], inp["W"], inp["U"], inp["G"], inp["X"])
+    ref, gref = oracle_results(oracle, cfg, inp, dloss)
     err = np.abs(loss - ref).max()
     print(f"  loss max abs err {err:.3e}", flush=True)
     assert err <= loss_atol_bf16(cfg)          # 2e-3 at the workloads' shapes; see the helper for the others
-    gref = oracle.loss_bwd(inp["H"], inp["W"], inp["U"], inp["G"], inp["X"], dloss)
     for k, v in gref.items():
         if k == "dG" and cfg.r == 1:
             # one expert: the gate weight is the constant 1 and its gradient vanishes identically
@@ -89,14 +100,46 @@ def test_loss_and_gradients_random_shapes(gpu, oracle, cfg, flags):
     test_loss_and_gradients(gpu, oracle, cfg, flags)
 
 
-def test_single_token_vocabulary(gpu):
+KEEP_LOGITS = 4      # CP_HEAD_KEEP_LOGITS: the backward pass reads the forward pass's logits instead of recomputing them
+
+
+@pytest.mark.parametrize("cfg,flags", [(c, f | KEEP_LOGITS) for c, f in CASES + random_shapes()],
+                         ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_loss_and_gradients_with_kept_logits(gpu, oracle, cfg, flags):
+    test_loss_and_gradients(gpu, oracle, cfg, flags)
+
+
+def test_kept_logits_change_nothing_in_the_forward_pass(gpu):
+    """The kept logits are an extra output of the same kernel: losses are bit-identical, and the gradients of
+    the two backward passes agree far inside the tolerance against the oracle."""
+    cfg = synth.HeadConfig("mfma_keep_vs_recompute", T=700, d=128, V=1500, n=2, r=3)
+    inp = synth.make_inputs(cfg)
+    inp["X"][::5, 1] = -1
+    dloss = synth.upstream_grad(cfg.T)
+    l0, g0 = run_loss(gpu, cfg, inp, dloss, flags=0)
+    for flags in (KEEP_LOGITS, KEEP_LOGITS | 2):
+        l1, g1 = run_loss(gpu, cfg, inp, dloss, flags=flags)
+        np.testing.assert_array_equal(l0, l1)
+        for k in g0:
+            e = rel_fro(g1[k], g0[k])
+            print(f"  flags={flags} {k}: kept vs recomputed rel fro {e:.3e}", flush=True)
+            assert e <= 3e-3, (k, e)
+    _, g2 = run_loss(gpu, cfg, inp, dloss, flags=KEEP_LOGITS, want_dU=False)     # frozen unembedding: no transposed dz
+    _, g3 = run_loss(gpu, cfg, inp, dloss, flags=KEEP_LOGITS)
+    assert "dU" not in g2
+    for k in g2:
+        np.testing.assert_array_equal(g2[k], g3[k])
+
+
+@pytest.mark.parametrize("flags", [0, KEEP_LOGITS])
+def test_single_token_vocabulary(gpu, flags):
     """V = 1: every factor is the constant 1, so the loss is zero and the heads have no gradient.  The
     target logit (fp32 from y = hi + lo) and the log-normaliser (the same single logit from bf16 y) differ by
     the rounding of y, so the loss is zero to the tiny-vocabulary bound of the test above and the gate sees a
     gradient of that size."""
     cfg = synth.HeadConfig("mfma_v1", T=70, d=64, V=1, n=2, r=3, targets="uniform")
     inp = synth.make_inputs(cfg)
-    loss, grads = run_loss(gpu, cfg, inp)
+    loss, grads = run_loss(gpu, cfg, inp, flags=flags)
     assert np.abs(loss).max() <= 1e-2
     assert np.abs(grads["dW"]).max() == 0.0 and np.abs(grads["dU"]).max() == 0.0
     assert np.abs(grads["dH"]).max() <= 2e-2 and np.abs(grads["dG"]).max() <= 2e-1
@@ -186,14 +229,15 @@ def test_draft_boundaries(gpu):
     assert (a.cpu().numpy() == cfg.r - 1).all() and (tok.cpu().numpy() == cfg.V - 1).all()
 
 
-def test_loss_step_replays_from_a_hip_graph(gpu):
+@pytest.mark.parametrize("flags", [2, 2 | KEEP_LOGITS])
+def test_loss_step_replays_from_a_hip_graph(gpu, flags):
     """The calls only enqueue kernels on the stream they are given (no allocation, no memset nodes), so a
     training step can be captured once and replayed: every replay must reproduce the eager result."""
     import torch
     from paper_2410_17765_amd import binding
     cfg = synth.HeadConfig("mfma_graph", T=520, d=128, V=1000, n=2, r=4)
     inp = synth.make_inputs(cfg)
-    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=2)        # several chunks in the backward pass
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype="bf16", flags=flags)    # several chunks in the backward pass
     H = gpu.to_device(inp["H"], "bf16")
     X = torch.from_numpy(inp["X"]).cuda()
     ds = h.desc(cfg.T)

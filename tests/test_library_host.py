@@ -149,6 +149,31 @@ def test_new_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cp_head_aux_balance(ctypes.byref(bf), p, p, None, p, p, 256, None) == -1
 
 
+def test_kept_logits_are_sized_into_ctx_on_the_matrix_core_path_only(lib):
+    T, d, V, n, r = 1000, 128, 1000, 2, 3
+    plain = binding.make_desc(T, d, V, n, r, binding.BF16, 0)
+    keep = binding.make_desc(T, d, V, n, r, binding.BF16, binding.KEEP_LOGITS)
+    rows, Vp, blocks = T * n * r, 1024, 8                    # V rounded up to 64; blocks of 128 columns
+    extra = binding.cp_head_ctx_bytes(keep) - binding.cp_head_ctx_bytes(plain)
+    assert rows * (Vp * 2 + blocks * 8) <= extra <= rows * (Vp * 2 + blocks * 8) + 512
+    # the statistics move from the forward workspace into ctx; the backward workspace is the same
+    assert (binding.cp_head_workspace_bytes(plain, binding.OP_LOSS_FWD)
+            - binding.cp_head_workspace_bytes(keep, binding.OP_LOSS_FWD)) >= rows * blocks * 8
+    assert (binding.cp_head_workspace_bytes(plain, binding.OP_LOSS_BWD)
+            == binding.cp_head_workspace_bytes(keep, binding.OP_LOSS_BWD))
+    # ignored on the plain path and by the fine-tuning loss
+    for dtype, flags in ((binding.FP32, 0), (binding.BF16, binding.FORCE_GENERIC)):
+        a = binding.make_desc(T, d, V, n, r, dtype, flags)
+        b = binding.make_desc(T, d, V, n, r, dtype, flags | binding.KEEP_LOGITS)
+        assert binding.cp_head_ctx_bytes(a) == binding.cp_head_ctx_bytes(b)
+    out_a, out_b = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert lib.cp_head_distill_ctx_bytes(ctypes.byref(plain), ctypes.byref(out_a)) == 0
+    assert lib.cp_head_distill_ctx_bytes(ctypes.byref(keep), ctypes.byref(out_b)) == 0
+    assert out_a.value == out_b.value
+    for op in (binding.OP_DISTILL_FWD, binding.OP_DISTILL_BWD):
+        assert binding.cp_head_workspace_bytes(plain, op) == binding.cp_head_workspace_bytes(keep, op)
+
+
 def test_full_head_workspace_is_bounded_in_positions(lib):
     a = binding.make_desc(1 << 16, 4096, 32000, 4, 8, binding.BF16)
     b = binding.make_desc(1 << 17, 4096, 32000, 4, 8, binding.BF16)
