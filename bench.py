@@ -106,7 +106,8 @@ def bench_full(args):
         F, G = head.to_device(inp["F"], cfg.dtype), head.to_device(inp["G"], cfg.dtype)
         H = head.to_device(inp["H"], cfg.dtype)
         X = torch.from_numpy(inp["X"]).to(dev)
-    ds = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, binding.BF16, 0)
+    keep = not args.recompute_logits
+    ds = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, binding.BF16, binding.KEEP_LOGITS if keep else 0)
     ctx = torch.empty(binding.cp_head_full_ctx_bytes(ds), dtype=torch.uint8, device=dev)
     ws = torch.empty(max(binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_FWD),
                          binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_BWD)), dtype=torch.uint8, device=dev)
@@ -148,7 +149,9 @@ def bench_full(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic (head weights drawn on the device)" if on_device else "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
-                   "token": "one position (n future tokens each)"},
+                   "token": "one position (n future tokens each)",
+                   "logits": "kept in HBM between forward and backward" if keep else "recomputed in the backward pass",
+                   "ctx_gib": ctx.numel() / GIB},
         "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
         "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "mean_loss": float(loss.mean()),

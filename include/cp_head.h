@@ -57,8 +57,9 @@ enum {
                                    tile of 256 head rows at a time (least workspace, slower)
                                    instead of its default of 32768 rows or 4 GiB worth of them,
                                    whichever is more, up to 8 GiB (0.5 GiB on the plain path) */
-    CP_HEAD_KEEP_LOGITS = 4     /* flags bit 2, matrix-core path of cp_head_loss_fwd / _bwd only (ignored
-                                   elsewhere): the forward pass keeps every logit in ctx as a 16-bit float
+    CP_HEAD_KEEP_LOGITS = 4     /* flags bit 2, matrix-core path of cp_head_loss_fwd / _bwd and of
+                                   cp_head_full_loss_fwd / _bwd only (ignored elsewhere, the fine-tuning loss
+                                   included): the forward pass keeps every logit in ctx as a 16-bit float
                                    relative to the maximum of its row over a block of 128 columns
                                    (T*n*r*roundup(V,64)*2 bytes plus 16 bytes per row and 256 columns), and
                                    the backward pass reads them back instead of multiplying U y a second
@@ -210,7 +211,7 @@ int cp_head_aux_balance(const cp_head_desc *desc, const void *H, const void *G,
  * Forward: loss[T] fp32, overwritten.  Backward: gradients of sum_t dloss[t] * loss[t] (dloss and
  * scale as in cp_head_loss_bwd); dH[T,d] (required), dF[n,r,V,d] and dG[r,d] (either may be NULL)
  * are fp32 and overwritten.  Logits are recomputed head by head for a bounded chunk of positions;
- * nothing of size T*n*r*V is ever stored.
+ * nothing of size T*n*r*V is ever stored, unless CP_HEAD_KEEP_LOGITS asks for it (then ctx holds them).
  */
 int cp_head_full_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
 int cp_head_full_loss_fwd(const cp_head_desc *desc,

@@ -1111,7 +1111,10 @@ inline BwdWs bwd_ws(const cp_head_desc &ds)
 
 // Saved-for-backward buffer of the full-head calls: [lse nr*T f32, head-major][w T*r][gamma T*r]
 struct FullCtx {
-    size_t lse, w, gamma, total;
+    size_t lse, w, gamma, zpart, zs, total;
+    size_t Vp;
+    int parts;
+    bool keep;      // CP_HEAD_KEEP_LOGITS: statistics and logits of all rows (head-major, like lse) stay in ctx
 };
 inline FullCtx full_ctx(const cp_head_desc &ds)
 {
@@ -1122,6 +1125,14 @@ inline FullCtx full_ctx(const cp_head_desc &ds)
     c.lse = take(M * 4);
     c.w = take(Tr * 4);
     c.gamma = take(Tr * 4);
+    c.keep = (ds.flags & CP_HEAD_KEEP_LOGITS) != 0 && use_fast_path(ds);
+    c.Vp = round_up((size_t)ds.V, 64);
+    c.parts = ((ds.V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+    c.zpart = c.zs = off;
+    if (c.keep) {
+        c.zpart = take(M * c.parts * sizeof(float2));
+        c.zs = take(M * c.Vp * 2);
+    }
     c.total = off;
     return c;
 }
@@ -1139,7 +1150,7 @@ inline FullFwdWs full_fwd_ws(const cp_head_desc &ds)
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     f.logw = take((size_t)ds.T * ds.r * 4);
     f.C = take(M * 4);
-    f.part = take(M * f.parts * sizeof(float2));
+    f.part = (ds.flags & CP_HEAD_KEEP_LOGITS) ? off : take(M * f.parts * sizeof(float2));   // else in ctx
     f.total = off;
     return f;
 }
@@ -1554,11 +1565,18 @@ int fast_full_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Fv, c
     const size_t M = (size_t)T * nr;
     float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
     float *logw = at<float>(ws, f.logw), *C = at<float>(ws, f.C);
-    float2 *part = at<float2>(ws, f.part);
+    float2 *part = cl.keep ? at<float2>(ctx, cl.zpart) : at<float2>(ws, f.part);
+    uint16_t *zs = at<uint16_t>(ctx, cl.zs);
     launch_gate(ds, Hv, Gv, logw, w, st);                                                       // eq. 7
-    for (int sa = 0; sa < nr; ++sa)                                                             // z_sa = F_sa h (eq. 6), statistics
-        launch_gemm_nt<Cfg>("full_gemm_z_stats", H, d, T, F + (size_t)sa * V * d, d, V, d,
-                            EpiRowStats{part + (size_t)sa * T * f.parts, f.parts, T, V}, st);
+    for (int sa = 0; sa < nr; ++sa) {                                                           // z_sa = F_sa h (eq. 6), statistics
+        if (cl.keep)
+            launch_gemm_nt<Cfg>("full_gemm_z_stats_keep", H, d, T, F + (size_t)sa * V * d, d, V, d,
+                                EpiRowStatsKeep{part + (size_t)sa * T * f.parts, f.parts, T, V,
+                                                zs + (size_t)sa * T * cl.Vp, (long)cl.Vp, (int)cl.Vp}, st);
+        else
+            launch_gemm_nt<Cfg>("full_gemm_z_stats", H, d, T, F + (size_t)sa * V * d, d, V, d,
+                                EpiRowStats{part + (size_t)sa * T * f.parts, f.parts, T, V}, st);
+    }
     k_full_row_finish<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>((size_t)T, d, V, ds.n, ds.r, f.parts, part, H, F, X,
                                                                         lse, C);             // eq. 5, 8
     launch_mixture(ds, logw, C, loss, gamma, -1.f, st);                                         // eq. 9
@@ -1597,9 +1615,14 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Fv, c
         const bf16_t *Hc = H + t0 * d;
         for (int sa = 0; sa < nr; ++sa) {
             const bf16_t *Fsa = F + (size_t)sa * V * d;
-            // recompute z_sa for these positions; the epilogue turns it into dz (bf16), also transposed
-            launch_gemm_nt<Cfg>("full_gemm_z_dz", Hc, d, Tc, Fsa, d, V, d,
-                                EpiDz{dZ, (long)Vp, dF ? dZt : nullptr, ldM, rowinfo + (size_t)sa * T + t0, Tc, Tcp, V, Vp}, st);
+            // dz (bf16), also transposed, from the kept logits of these positions, or from z_sa recomputed
+            if (cl.keep) {
+                KeptDzArgs kept{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), rowinfo, cl.Vp, cl.parts, V};
+                kept_dz_launch(&kept, nullptr, Tc, Tcp, (size_t)sa * T + t0, dZ, (long)Vp, dF ? dZt : nullptr, ldM, st);
+            } else {
+                launch_gemm_nt<Cfg>("full_gemm_z_dz", Hc, d, Tc, Fsa, d, V, d,
+                                    EpiDz{dZ, (long)Vp, dF ? dZt : nullptr, ldM, rowinfo + (size_t)sa * T + t0, Tc, Tcp, V, Vp}, st);
+            }
             // dH += dz F_sa   (contraction over the vocabulary)
             transpose_bf16(Fsa, d, V, d, Ft, ldV, Vp, st);            // Ft[d, Vp]
             launch_gemm_nt<Cfg>("full_gemm_dh", dZ, Vp, Tc, Ft, ldV, d, Vp,

@@ -35,6 +35,8 @@ def run(head, cfg, inp, dloss=None, flags=0, want_dF=True, scale=1.0):
     return loss.cpu().numpy(), grads
 
 
+_ORACLE_RESULTS = {}     # per case name: the cases with kept logits use the same inputs again
+
 CASES = [
     (synth.HeadConfig("full_small", T=300, d=128, V=1000, n=2, r=3, u_scale=2.0), 0),
     (synth.HeadConfig("full_ragged", T=523, d=192, V=777, n=3, r=2, u_scale=3.0), 0),
@@ -56,11 +58,13 @@ def test_loss_and_gradients(gpu, oracle, cfg, flags):
         inp["X"][5, :] = -1                       # a position with no targets at all
     dloss = synth.upstream_grad(cfg.T).astype(np.float32)
     loss, g = run(gpu, cfg, inp, dloss, flags=flags)
-    ref = oracle.full_loss_fwd(inp["H"], inp["F"], inp["G"], inp["X"])
+    if cfg.name not in _ORACLE_RESULTS:
+        _ORACLE_RESULTS[cfg.name] = (oracle.full_loss_fwd(inp["H"], inp["F"], inp["G"], inp["X"]),
+                                     oracle.full_loss_bwd(inp["H"], inp["F"], inp["G"], inp["X"], dloss.astype(np.float64)))
+    ref, rg = _ORACLE_RESULTS[cfg.name]
     err = np.abs(loss - ref).max()
     print(f"  loss max abs err {err:.3e}", flush=True)
     assert err <= LOSS_ATOL
-    rg = oracle.full_loss_bwd(inp["H"], inp["F"], inp["G"], inp["X"], dloss.astype(np.float64))
     for k in ("dH", "dF", "dG"):
         e = rel_fro(g[k], rg[k])
         print(f"  {k} rel fro {e:.3e}", flush=True)
@@ -88,6 +92,17 @@ def random_shapes(count=8, seed=20241022, budget=4e8):
 
 @pytest.mark.parametrize("cfg,flags", random_shapes(), ids=lambda c: c.name if hasattr(c, "name") else str(c))
 def test_loss_and_gradients_random_shapes(gpu, oracle, cfg, flags):
+    test_loss_and_gradients(gpu, oracle, cfg, flags)
+
+
+KEEP_LOGITS = 4      # CP_HEAD_KEEP_LOGITS: the backward pass reads the forward pass's logits instead of recomputing them
+
+
+@pytest.mark.parametrize("cfg,flags", [(c, f | KEEP_LOGITS) for c, f in CASES + random_shapes()],
+                         ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_loss_and_gradients_with_kept_logits(gpu, oracle, cfg, flags):
+    """On the plain path (fp32 storage, or flag 1) the flag is ignored; on the matrix-core path it swaps the
+    recomputation for a read of the kept logits."""
     test_loss_and_gradients(gpu, oracle, cfg, flags)
 
 
@@ -129,7 +144,7 @@ def full():
     cfg = synth.CONFIGS["full_heads"]
     print(f"[full heads] generating {cfg}", flush=True)
     inp = make(cfg)
-    h = head.CpFullHead(inp["F"], inp["G"], dtype=cfg.dtype)
+    h = head.CpFullHead(inp["F"], inp["G"], dtype=cfg.dtype, flags=KEEP_LOGITS)     # as bench.py times it
     H = head.to_device(inp["H"], cfg.dtype)
     X = torch.from_numpy(inp["X"]).cuda()
     scale = 1.0 / cfg.T
