@@ -26,6 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # there report null.
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
+    ("head_7b", "gemm_z_stats_keep"): (223.494 + 32.562) * GIB,
     ("head_7b", "gemm_z_stats"): (249.304 + 1.358) * GIB,
     ("head_7b", "gemm_z_dz"): (25.620 + 7.813) * GIB,
     # draft step: L2 fills of its kernels per step at B = 1, 8, 64 (profiles/draft_b8_kernel_stats.md)
@@ -352,10 +353,12 @@ def bench_loss(args):
 
     fwd_flops = 2.0 * cfg.n * cfg.r * cfg.d * (cfg.d + cfg.V) * cfg.T
     if not args.no_modes:
-        t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
+        # evaluation keeps no logits: the forward call alone runs without CP_HEAD_KEEP_LOGITS
+        t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds_re, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
         out["forward_only"] = {"ms_per_step": t_fwd * 1e3, "tokens_per_s": cfg.T / t_fwd,
                                "model_tflops": fwd_flops / t_fwd / 1e12}
-        # backward alone, on the ctx the last forward call left
+        # backward alone, on the ctx of a forward call of the timed step's kind
+        binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
         t_bwd = timed(lambda: binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, dU, dG, ws,
                                                        stream))
         out["backward_only"] = {"ms_per_step": t_bwd * 1e3, "model_tflops": (model_flops - fwd_flops) / t_bwd / 1e12}
