@@ -190,7 +190,8 @@ def bench_distill(args):
     torch.cuda.set_device(dev)
     cfg = synth.CONFIGS["head_7b"]
     inp = synth.make_inputs(cfg)
-    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    keep = not args.recompute_logits
+    h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype, flags=binding.KEEP_LOGITS if keep else 0)
     H = head.to_device(inp["H"], cfg.dtype)
     X = torch.from_numpy(inp["X"]).to(dev)
     gen = torch.Generator(device=dev)
@@ -233,15 +234,17 @@ def bench_distill(args):
     gemms = [k for k in kernels if "gemm_" in k[0]]
     dom = max(gemms, key=lambda k: k[2])
     achieved = dom[3] / (dom[2] * 1e-3) / 1e12
-    # algorithmic products: y, z (log-normalisers), z again (mixture over the experts), dY, dH, dW
-    model_flops = (2.0 * cfg.n * cfg.r * cfg.d * (3 * cfg.d + 3 * cfg.V)) * cfg.T
+    # algorithmic products: y, z, dY, dH, dW (without kept logits the hardware multiplies U y twice more)
+    model_flops = (2.0 * cfg.n * cfg.r * cfg.d * (3 * cfg.d + 2 * cfg.V)) * cfg.T
     return {
         "metric": "CP-head fine-tuning loss fwd+bwd tokens/s", "value": cfg.T * args.steps / dt, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic (teacher logits drawn on the device)",
         "config": {"workload": "distill_7b", "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
-                   "beta": 0.9, "discount": 0.8, "frozen_u": True, "token": "one position (n future tokens each)"},
+                   "beta": 0.9, "discount": 0.8, "frozen_u": True, "token": "one position (n future tokens each)",
+                   "logits": "kept in HBM between forward and backward" if keep else "recomputed twice",
+                   "ctx_gib": ctx.numel() / GIB},
         "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
         "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "mean_loss": float(loss.mean()),

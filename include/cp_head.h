@@ -57,9 +57,9 @@ enum {
                                    tile of 256 head rows at a time (least workspace, slower)
                                    instead of its default of 32768 rows or 4 GiB worth of them,
                                    whichever is more, up to 8 GiB (0.5 GiB on the plain path) */
-    CP_HEAD_KEEP_LOGITS = 4     /* flags bit 2, matrix-core path of cp_head_loss_fwd / _bwd and of
-                                   cp_head_full_loss_fwd / _bwd only (ignored elsewhere, the fine-tuning loss
-                                   included): the forward pass keeps every logit in ctx as a 16-bit float
+    CP_HEAD_KEEP_LOGITS = 4     /* flags bit 2, matrix-core path of the three loss call pairs (cp_head_loss_,
+                                   cp_head_full_loss_, cp_head_distill_loss_ fwd / bwd; ignored on the plain
+                                   path and by the other calls): the forward pass keeps every logit in ctx as a 16-bit float
                                    relative to the maximum of its row over a block of 128 columns
                                    (T*n*r*roundup(V,64)*2 bytes plus 16 bytes per row and 256 columns), and
                                    the backward pass reads them back instead of multiplying U y a second
@@ -244,8 +244,9 @@ int cp_head_full_loss_bwd(const cp_head_desc *desc,
  * (dU = NULL for the frozen unembedding of fine tuning).  Every entry of TZ must be finite, also in the
  * rows of dropped tokens.  For bf16 storage with d a multiple of 64 and r in {1, 2, 4, 8} no logits are
  * stored: the mixture over the experts is formed inside the tiles of two further vocabulary-sized
- * products on the matrix cores.  Every other shape and fp32 storage run on the plain fp32 path, which
- * keeps the fp32 logits of one chunk of rows at a time in the workspace.
+ * products on the matrix cores (with CP_HEAD_KEEP_LOGITS: the first product keeps its logits in ctx
+ * and the two further ones become memory-bound passes over them).  Every other shape and fp32 storage
+ * run on the plain fp32 path, which keeps the fp32 logits of one chunk of rows at a time in the workspace.
  */
 int cp_head_distill_ctx_bytes(const cp_head_desc *desc, size_t *bytes);
 int cp_head_distill_loss_fwd(const cp_head_desc *desc,

@@ -18,7 +18,10 @@
 //           coefficients of the backward pass.
 // Backward: a third product whose epilogue writes dz = c1 P - c3 p^c rho + c2 1[v = x] in bf16; everything
 //           below dz is the training loss's backward pass.
+// With CP_HEAD_KEEP_LOGITS the first product keeps its logits (kept_logits.hpp) and the second and third
+// products become HBM-bound passes over them: k_distill_kl_kept and k_dz_from_kept<DistillDzRule>.
 #include "gemm_nt.hpp"
+#include "kept_logits.hpp"
 
 #include <math.h>
 
@@ -354,6 +357,135 @@ struct EpiDzDistill {
 };
 
 // ------------------------------------------------------------------------------------------
+// the same two passes over kept logits
+// ------------------------------------------------------------------------------------------
+
+// teacher logits of 8 consecutive columns; columns from V on read as the last valid one (and are not used)
+__device__ __forceinline__ void load_teacher8(const bf16_t *__restrict__ trow, int col, int V, float (&tz)[8])
+{
+    const bf16_t *p = trow + col;
+    if (col + 8 <= V && (reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+        const u32x4_t raw = *reinterpret_cast<const u32x4_t *>(p);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            tz[2 * k] = __uint_as_float(raw[k] << 16);
+            tz[2 * k + 1] = __uint_as_float(raw[k] & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) tz[k] = bf16_to_f32(trow[col + k < V ? col + k : V - 1]);
+    }
+}
+
+template <int R>
+__device__ __forceinline__ float log_mixture(const float (&l)[R])
+{
+    float mx = l[0];
+#pragma unroll
+    for (int a = 1; a < R; ++a) mx = fmaxf(mx, l[a]);
+    float s = 0.f;
+#pragma unroll
+    for (int a = 0; a < R; ++a) s += __expf(l[a] - mx);
+    return mx + __logf(s);
+}
+
+// What EpiDistillStats accumulates, from the kept logits: one workgroup per token g, a thread takes 8 columns
+// of the token's R rows at a time; SK[g R + a] = {S_a, KL}.
+template <int R>
+__global__ void __launch_bounds__(kBlock) k_distill_kl_kept(KeptLogits kept, int V, int Vp, const float2 *__restrict__ rowa,
+                                                            const bf16_t *__restrict__ TZ, const float *__restrict__ tlse,
+                                                            float2 *__restrict__ SK)
+{
+    __shared__ float red[kBlock / kWave][R + 1];
+    const size_t g = blockIdx.x;
+    float lse_[R], lq_[R], S[R];
+#pragma unroll
+    for (int a = 0; a < R; ++a) {
+        const float2 ra = rowa[g * R + a];
+        lse_[a] = ra.x;
+        lq_[a] = ra.y;
+        S[a] = 0.f;
+    }
+    const float tl = tlse[g];
+    const bf16_t *trow = TZ + g * (size_t)V;
+    float kl = 0.f;
+    for (int col = (int)threadIdx.x * 8; col < Vp && col < V; col += kBlock * 8) {
+        float lp[R][8], tz[8];
+#pragma unroll
+        for (int a = 0; a < R; ++a) kept_log_probs(kept, g * R + a, col, lse_[a], lp[a]);
+        load_teacher8(trow, col, V, tz);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (col + k >= V) continue;
+            float l[R];
+#pragma unroll
+            for (int a = 0; a < R; ++a) l[a] = lp[a][k] + lq_[a];
+            const float lm = log_mixture<R>(l);
+            const float lpc = tz[k] - tl;
+            const float pc = __expf(lpc);
+            kl += pc * (lpc - lm);
+#pragma unroll
+            for (int a = 0; a < R; ++a) S[a] += pc * __expf(l[a] - lm);
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    kl = wave_sum(kl);
+#pragma unroll
+    for (int a = 0; a < R; ++a) S[a] = wave_sum(S[a]);
+    if (lane == 0) {
+#pragma unroll
+        for (int a = 0; a < R; ++a) red[wave][a] = S[a];
+        red[wave][R] = kl;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < R) {
+        float s = 0.f, k = 0.f;
+        for (int w = 0; w < kBlock / kWave; ++w) {
+            s += red[w][threadIdx.x];
+            k += red[w][R];
+        }
+        SK[g * R + threadIdx.x] = make_float2(s, k);
+    }
+}
+
+// The gradient of EpiDzDistill for a thread's rows of k_dz_from_kept: whole tokens (R rows each; a chunk starts
+// and ends on a token).  rowinfo {lse, log qhat, c1, c2}; grp and TZ chunk-relative as for EpiDzDistill.
+template <int R>
+struct DistillDzRule {
+    static constexpr int RT = R < 2 ? 2 : R;
+    const float4 *grp;
+    const bf16_t *TZ;
+    __device__ __forceinline__ void operator()(int row, int nrows, int col, int V, const float4 (&info)[RT],
+                                               const float (&lp)[RT][8], float (&g)[RT][8]) const
+    {
+#pragma unroll
+        for (int gi = 0; gi < RT / R; ++gi) {
+            if (gi * R >= nrows) continue;
+            const size_t tok = (size_t)(row / R + gi);
+            const float4 gv = grp[tok];
+            const float tl = gv.x, c3 = gv.y;
+            const int x = __float_as_int(gv.z) - col;
+            float tz[8];
+            load_teacher8(TZ + tok * (size_t)V, col, V, tz);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (col + k >= V) continue;
+                float l[R];
+#pragma unroll
+                for (int e = 0; e < R; ++e) l[e] = lp[gi * R + e][k] + info[gi * R + e].y;
+                const float lm = log_mixture<R>(l);
+                const float lpc = tz[k] - tl;
+#pragma unroll
+                for (int e = 0; e < R; ++e) {
+                    const int h = gi * R + e;
+                    g[h][k] = info[h].z * __expf(lp[h][k]) - c3 * __expf(lpc + l[e] - lm) + (x == k ? info[h].w : 0.f);
+                }
+            }
+        }
+    }
+};
+
+// ------------------------------------------------------------------------------------------
 // buffers
 // ------------------------------------------------------------------------------------------
 
@@ -397,7 +529,7 @@ DistillFwdWs distill_fwd_ws(const cp_head_desc &ds)
     f.rhox = take(M * 4);
     f.ce = take(Tn * 4);
     f.SK = take(M * 8);
-    f.part = take(M * f.parts * sizeof(float2));
+    f.part = (ds.flags & CP_HEAD_KEEP_LOGITS) ? off : take(M * f.parts * sizeof(float2));   // no second product then
     f.total = off;
     return f;
 }
@@ -444,6 +576,31 @@ void distill_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0,
                         st);
 }
 
+template <int R>
+void launch_kl_kept(const cp_head_desc &ds, const KeptLogits &kept, const float2 *rowa, const bf16_t *TZ, const float *tlse,
+                    float2 *SK, hipStream_t st)
+{
+    const size_t Tn = (size_t)ds.T * ds.n;
+    // algorithmic traffic: kept logits and teacher logits read once
+    ProfileScope scope("distill_kl_kept", ((double)Tn * R * kept.ld + (double)Tn * ds.V) * 2.0, st);
+    k_distill_kl_kept<R><<<(unsigned)Tn, kBlock, 0, st>>>(kept, ds.V, (int)kept.ld, rowa, TZ, tlse, SK);
+}
+
+struct DistillKeptArgs {
+    KeptLogits kept;
+    const bf16_t *TZ;
+    const float4 *rowinfo, *grp;
+    int V;
+};
+template <int R>
+void distill_kept_dz_launch(void *user, const bf16_t *, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt,
+                            long ldzt, hipStream_t st)
+{
+    const DistillKeptArgs *a = static_cast<const DistillKeptArgs *>(user);
+    launch_dz_from_kept(a->kept, m0, a->rowinfo + m0, DistillDzRule<R>{a->grp + m0 / R, a->TZ + (m0 / R) * a->V}, Mc, Mcp,
+                        a->V, dZ, ldz, dZt, ldzt, st);
+}
+
 int mfma_distill_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,
                      const int32_t *X, const void *TZv, float beta, float disc, float *loss, void *ctx, void *ws,
                      hipStream_t st)
@@ -464,13 +621,24 @@ int mfma_distill_fwd(const cp_head_desc &ds, const void *H, const void *W, const
 
     k_teacher_lse<bf16_t><<<(unsigned)Tn, kBlock, 0, st>>>(ds.V, TZ, tlse);
     k_distill_weights<8><<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, fb.logw, fb.C, fb.lse, X, rowa, rhox, ce);
-    switch (ds.r) {
-    case 1: launch_stats<1>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
-    case 2: launch_stats<2>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
-    case 4: launch_stats<4>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
-    default: launch_stats<8>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+    const CtxLayout cl = ctx_layout(ds, true);
+    if (cl.keep) {
+        const KeptLogits kept{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), (long)cl.Vp, cl.parts};
+        switch (ds.r) {
+        case 1: launch_kl_kept<1>(ds, kept, rowa, TZ, tlse, SK, st); break;
+        case 2: launch_kl_kept<2>(ds, kept, rowa, TZ, tlse, SK, st); break;
+        case 4: launch_kl_kept<4>(ds, kept, rowa, TZ, tlse, SK, st); break;
+        default: launch_kl_kept<8>(ds, kept, rowa, TZ, tlse, SK, st); break;
+        }
+    } else {
+        switch (ds.r) {
+        case 1: launch_stats<1>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+        case 2: launch_stats<2>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+        case 4: launch_stats<4>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+        default: launch_stats<8>(ds, fb.Y, U, part, f.parts, rowa, TZ, tlse, st); break;
+        }
+        k_sum_parts<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, f.parts, part, SK);
     }
-    k_sum_parts<<<blocks_for(M, kBlock / kWave), kBlock, 0, st>>>(M, f.parts, part, SK);
     k_distill_finish<8><<<blocks_for(T, kBlock), kBlock, 0, st>>>(T, ds.n, ds.r, beta, disc, X, rowa, rhox, ce, SK, loss, c1,
                                                                   c2, c3, dgsum);
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
@@ -499,6 +667,13 @@ int mfma_distill_bwd(const cp_head_desc &ds, const void *H, const void *W, const
     float *dg = at<float>(ws, b.dg);
     k_distill_bwd_rows<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, ds.n, ds.r, rowa, c1, c2, c3, tlse, dgsum, dloss, scale, X,
                                                                  rowinfo, grp, dg);
+    if (cl.keep) {
+        DistillKeptArgs kargs{KeptLogits{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), (long)cl.Vp, cl.parts},
+                              (const bf16_t *)TZv, rowinfo, grp, ds.V};
+        FastDzLaunch kfn = ds.r == 1 ? distill_kept_dz_launch<1> : ds.r == 2 ? distill_kept_dz_launch<2>
+                         : ds.r == 4 ? distill_kept_dz_launch<4> : distill_kept_dz_launch<8>;
+        return fast_bwd_from_dz(ds, H, W, Uv, G, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, kfn, &kargs, st);
+    }
     DistillDzArgs args{(const bf16_t *)Uv, (const bf16_t *)TZv, rowinfo, grp, ds.d, ds.V, ds.r};
     FastDzLaunch fn = ds.r == 1 ? distill_dz_launch<1> : ds.r == 2 ? distill_dz_launch<2>
                     : ds.r == 4 ? distill_dz_launch<4> : distill_dz_launch<8>;
@@ -692,10 +867,10 @@ int plain_distill_bwd(const cp_head_desc &ds, const void *H, const void *W, cons
 
 }  // namespace
 
-// The fine-tuning loss recomputes its logits: the flag that keeps them belongs to the training loss alone.
+// The plain path keeps no logits: there the flag is dropped before any layout is computed.
 static cp_head_desc without_kept_logits(cp_head_desc ds)
 {
-    ds.flags &= ~CP_HEAD_KEEP_LOGITS;
+    if (!on_matrix_cores(ds)) ds.flags &= ~CP_HEAD_KEEP_LOGITS;
     return ds;
 }
 

@@ -7,6 +7,7 @@
 // All products run through the one NT main loop of gemm_nt.hpp; operands that are not
 // K-contiguous are transposed first (HBM-bound passes that cost a few percent of the GEMM time).
 #include "gemm_nt.hpp"
+#include "kept_logits.hpp"
 
 #include <math.h>
 
@@ -95,10 +96,6 @@ struct EpiRowStats {
             }
     }
 };
-
-// 16-bit float (IEEE binary16) bit patterns of the kept logits; round to nearest even, overflow to -inf is
-// harmless (its exponential is the zero that the exact value rounds to as well)
-__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 
 // The statistics of EpiRowStats, and the logits kept for the backward pass: zs[m, v] = fp16(z - ref) with ref
 // the maximum of row m over the wavefront's 128 columns (the pair that goes to `part`).  Relative to that
@@ -241,77 +238,27 @@ struct EpiDz {
 // logit gradients from kept logits
 // ------------------------------------------------------------------------------------------
 
-constexpr int kKeptTile = 128;      // rows and columns of a block's tile; its columns are one block of `part`
-
 // The gradient of EpiDz from the logits that EpiRowStatsKeep left behind instead of from a second product:
-//   dz[m, v] = coef[m] * (exp(zs[m, v] - (lse[m] - max[m, v / 128])) - 1[v = x_m]).
-// A block takes 128 rows x 128 columns.  A thread reads 8 consecutive logits of two consecutive rows (16 bytes
-// each), writes their gradients row-major (16 bytes each) and leaves them, one 32-bit word per column holding
-// the pair of rows, in a column-major LDS tile, from which the transposed copy leaves in 16-byte pieces of
-// 256-byte column segments.  The 16-byte pieces of an LDS column are stored at position (piece ^ column / 8):
-// the sixteen threads that write one pair of rows would otherwise all hit the same banks.
-// zs, part: rows of the chunk (already offset); rowinfo as for EpiDz.  dZt may be null.
-__global__ void __launch_bounds__(kBlock) k_dz_from_kept(const uint16_t *__restrict__ zs, long ldzs,
-                                                         const float2 *__restrict__ part, int parts,
-                                                         const float4 *__restrict__ rowinfo, int Mc, int Mcp, int V,
-                                                         int Vp, bf16_t *__restrict__ dZ, long ldz,
-                                                         bf16_t *__restrict__ dZt, long ldzt, int tiles_c)
-{
-    constexpr int CS = kKeptTile * 2 + 16;              // padded column stride in bytes
-    __shared__ __align__(16) char stage[kKeptTile * CS];
-    typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
-    const int tc = blockIdx.x % tiles_c, tr = blockIdx.x / tiles_c;
-    const int t = threadIdx.x, cg = t & 15;
-    const int col = tc * kKeptTile + cg * 8;
-    const bool col_in = col < Vp;                        // Vp is a multiple of 8: all eight columns or none
+//   dz[m, v] = coef[m] * (exp(log P[m, v]) - 1[v = x_m]),  rowinfo as for EpiDz.
+struct LossDzRule {
+    static constexpr int RT = 2;
+    __device__ __forceinline__ void operator()(int, int nrows, int col, int V, const float4 (&info)[2],
+                                               const float (&lp)[2][8], float (&g)[2][8]) const
+    {
 #pragma unroll
-    for (int pass = 0; pass < kKeptTile / 32; ++pass) {
-        const int rp = pass * 16 + (t >> 4);             // pair of rows inside the tile
-        const int row = tr * kKeptTile + 2 * rp;
-        float g[2][8];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int m = row + h;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) g[h][k] = 0.f;
-            if (col_in && m < Mc) {
-                const float4 info = rowinfo[m];
-                const float off = info.x - part[(size_t)m * parts + tc].x;     // lse - reference of the block
-                const float cf = info.y;
-                const f16x8_t z = __builtin_bit_cast(
-                    f16x8_t, *reinterpret_cast<const u32x4_t *>(zs + (size_t)m * ldzs + col));
-                const int x = __float_as_int(info.z) - col;
+        for (int h = 0; h < 2; ++h)
+            if (h < nrows) {
+                const float cf = info[h].y;
+                const int x = __float_as_int(info[h].z) - col;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    float v = cf * __builtin_amdgcn_exp2f(((float)z[k] - off) * kLog2e);
+                    float v = cf * __builtin_amdgcn_exp2f(lp[h][k] * kLog2e);
                     if (x == k) v -= cf;
                     g[h][k] = (col + k < V) ? v : 0.f;
                 }
-                u32x4_t out;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) out[k] = f32x2_to_bf16x2(g[h][2 * k], g[h][2 * k + 1]);
-                *reinterpret_cast<u32x4_t *>(dZ + (size_t)m * ldz + col) = out;
             }
-        }
-        if (dZt) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                *reinterpret_cast<uint32_t *>(stage + (cg * 8 + k) * CS + 16 * ((rp >> 2) ^ cg) + 4 * (rp & 3)) =
-                    f32x2_to_bf16x2(g[0][k], g[1][k]);
-        }
     }
-    if (!dZt) return;
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < kKeptTile * 16 / kBlock; ++q) {
-        const int idx = q * kBlock + t;
-        const int c = idx >> 4, pos = idx & 15;
-        const int piece = pos ^ (c >> 3);                // rows 8 piece .. 8 piece + 7 of the tile
-        const u32x4_t val = *reinterpret_cast<const u32x4_t *>(stage + c * CS + pos * 16);
-        const int grow = tr * kKeptTile + piece * 8, gcol = tc * kKeptTile + c;
-        if (grow < Mcp && gcol < V) *reinterpret_cast<u32x4_t *>(dZt + (size_t)gcol * ldzt + grow) = val;
-    }
-}
+};
 
 // ------------------------------------------------------------------------------------------
 // small kernels around the GEMMs
@@ -1379,24 +1326,16 @@ void loss_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf
 }
 
 struct KeptDzArgs {
-    const uint16_t *zs;      // [M, Vp]
-    const float2 *part;      // [M, parts]
+    KeptLogits kept;         // zs [M, Vp], part [M, parts]
     const float4 *rowinfo;
-    size_t Vp;
-    int parts, V;
+    int V;
 };
 // the same dz from the logits kept by the forward pass
 void kept_dz_launch(void *user, const bf16_t *, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt, long ldzt,
                     hipStream_t st)
 {
     const KeptDzArgs *a = static_cast<const KeptDzArgs *>(user);
-    const int tiles_c = (int)((a->Vp + kKeptTile - 1) / kKeptTile);
-    const size_t tiles_r = ((size_t)Mcp + kKeptTile - 1) / kKeptTile;
-    // algorithmic traffic: the logits read once, the gradients written once or twice
-    ProfileScope scope("dz_from_kept", (double)Mc * a->Vp * 2.0 * (dZt ? 3.0 : 2.0), st);
-    k_dz_from_kept<<<(unsigned)(tiles_r * tiles_c), kBlock, 0, st>>>(a->zs + m0 * a->Vp, (long)a->Vp, a->part + m0 * a->parts,
-                                                                       a->parts, a->rowinfo + m0, Mc, Mcp, a->V, (int)ldz,
-                                                                       dZ, ldz, dZt, ldzt, tiles_c);
+    launch_dz_from_kept(a->kept, m0, a->rowinfo + m0, LossDzRule{}, Mc, Mcp, a->V, dZ, ldz, dZt, ldzt, st);
 }
 }  // namespace
 
@@ -1421,7 +1360,7 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     float *dg = at<float>(ws, b.dg);
     k_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(M, n, r, w, gamma, lse, dloss, scale, X, rowinfo, dg);
     if (cl.keep) {
-        KeptDzArgs kept{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), rowinfo, cl.Vp, cl.parts, V};
+        KeptDzArgs kept{KeptLogits{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), (long)cl.Vp, cl.parts}, rowinfo, V};
         return fast_bwd_from_dz(ds, Hv, Wv, Uv, Gv, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, kept_dz_launch, &kept, st);
     }
     LossDzArgs args{(const bf16_t *)Uv, rowinfo, d, V};
@@ -1617,7 +1556,7 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Fv, c
             const bf16_t *Fsa = F + (size_t)sa * V * d;
             // dz (bf16), also transposed, from the kept logits of these positions, or from z_sa recomputed
             if (cl.keep) {
-                KeptDzArgs kept{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), rowinfo, cl.Vp, cl.parts, V};
+                KeptDzArgs kept{KeptLogits{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), (long)cl.Vp, cl.parts}, rowinfo, V};
                 kept_dz_launch(&kept, nullptr, Tc, Tcp, (size_t)sa * T + t0, dZ, (long)Vp, dF ? dZt : nullptr, ldM, st);
             } else {
                 launch_gemm_nt<Cfg>("full_gemm_z_dz", Hc, d, Tc, Fsa, d, V, d,

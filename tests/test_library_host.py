@@ -166,12 +166,20 @@ def test_kept_logits_are_sized_into_ctx_on_the_matrix_core_path_only(lib):
         a = binding.make_desc(T, d, V, n, r, dtype, flags)
         b = binding.make_desc(T, d, V, n, r, dtype, flags | binding.KEEP_LOGITS)
         assert binding.cp_head_ctx_bytes(a) == binding.cp_head_ctx_bytes(b)
+    # the fine-tuning loss: ignored at r = 3 (its plain path), honoured at r = 4
     out_a, out_b = ctypes.c_size_t(0), ctypes.c_size_t(0)
     assert lib.cp_head_distill_ctx_bytes(ctypes.byref(plain), ctypes.byref(out_a)) == 0
     assert lib.cp_head_distill_ctx_bytes(ctypes.byref(keep), ctypes.byref(out_b)) == 0
     assert out_a.value == out_b.value
     for op in (binding.OP_DISTILL_FWD, binding.OP_DISTILL_BWD):
         assert binding.cp_head_workspace_bytes(plain, op) == binding.cp_head_workspace_bytes(keep, op)
+    plain4 = binding.make_desc(T, d, V, n, 4, binding.BF16, 0)
+    keep4 = binding.make_desc(T, d, V, n, 4, binding.BF16, binding.KEEP_LOGITS)
+    assert lib.cp_head_distill_ctx_bytes(ctypes.byref(plain4), ctypes.byref(out_a)) == 0
+    assert lib.cp_head_distill_ctx_bytes(ctypes.byref(keep4), ctypes.byref(out_b)) == 0
+    assert out_b.value - out_a.value >= T * n * 4 * Vp * 2
+    assert (binding.cp_head_workspace_bytes(keep4, binding.OP_DISTILL_FWD)
+            < binding.cp_head_workspace_bytes(plain4, binding.OP_DISTILL_FWD))
 
 
 def test_full_head_workspace_is_bounded_in_positions(lib):
