@@ -46,9 +46,11 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per thread for the loss, per two threads for the full heads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
-    ap.add_argument("--recompute-logits", action="store_true",
-                    help="loss workloads: the backward pass multiplies U y again instead of reading the logits the "
-                         "forward pass kept in HBM (CP_HEAD_KEEP_LOGITS off)")
+    ap.add_argument("--keep-logits", action="store_true",
+                    help="loss workloads: time the step with CP_HEAD_KEEP_LOGITS (the forward pass keeps the logits in "
+                         "HBM as 16-bit floats, the backward pass reads them instead of multiplying U y again).  The "
+                         "default is the path with no materialised logits; the default run of a shared-unembedding "
+                         "workload reports the other variant as an extra mode")
     ap.add_argument("--no-modes", action="store_true", help="loss workloads: skip the forward-only and frozen-unembedding timings")
     ap.add_argument("--no-draft", action="store_true", help="loss workloads: skip the appended draft-step measurements")
     return ap.parse_args()
@@ -107,7 +109,7 @@ def bench_full(args):
         F, G = head.to_device(inp["F"], cfg.dtype), head.to_device(inp["G"], cfg.dtype)
         H = head.to_device(inp["H"], cfg.dtype)
         X = torch.from_numpy(inp["X"]).to(dev)
-    keep = not args.recompute_logits
+    keep = bool(args.keep_logits)
     ds = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, binding.BF16, binding.KEEP_LOGITS if keep else 0)
     ctx = torch.empty(binding.cp_head_full_ctx_bytes(ds), dtype=torch.uint8, device=dev)
     ws = torch.empty(max(binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_FWD),
@@ -151,7 +153,7 @@ def bench_full(args):
         "data": "synthetic (head weights drawn on the device)" if on_device else "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
                    "token": "one position (n future tokens each)",
-                   "logits": "kept in HBM between forward and backward" if keep else "recomputed in the backward pass",
+                   "logits": "kept in HBM between forward and backward" if keep else "never stored (recomputed in the backward pass)",
                    "ctx_gib": ctx.numel() / GIB},
         "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
         "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -190,7 +192,7 @@ def bench_distill(args):
     torch.cuda.set_device(dev)
     cfg = synth.CONFIGS["head_7b"]
     inp = synth.make_inputs(cfg)
-    keep = not args.recompute_logits
+    keep = bool(args.keep_logits)
     h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype, flags=binding.KEEP_LOGITS if keep else 0)
     H = head.to_device(inp["H"], cfg.dtype)
     X = torch.from_numpy(inp["X"]).to(dev)
@@ -243,7 +245,7 @@ def bench_distill(args):
         "data": "synthetic (teacher logits drawn on the device)",
         "config": {"workload": "distill_7b", "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
                    "beta": 0.9, "discount": 0.8, "frozen_u": True, "token": "one position (n future tokens each)",
-                   "logits": "kept in HBM between forward and backward" if keep else "recomputed twice",
+                   "logits": "kept in HBM between forward and backward" if keep else "never stored (recomputed twice)",
                    "ctx_gib": ctx.numel() / GIB},
         "model_tflops": model_flops / (ms_per_step * 1e-3) / 1e12,
         "model_flop_frac_of_bf16_peak": model_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -269,15 +271,17 @@ def bench_loss(args):
     t0 = time.time()
     inp = synth.make_inputs(cfg)
     print(f"[bench] inputs for {cfg.name} generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
-    keep = cfg.dtype == "bf16" and not args.recompute_logits
+    keep = cfg.dtype == "bf16" and bool(args.keep_logits)
     h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype, flags=binding.KEEP_LOGITS if keep else 0)
     H = head.to_device(inp["H"], cfg.dtype)
     X = torch.from_numpy(inp["X"]).to(dev)
-    ds = h.desc(cfg.T)
+    ds = h.desc(cfg.T)                                                                  # the timed step's variant
+    ds_plain = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, ds.dtype, 0)         # no materialised logits
+    ds_keep = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, ds.dtype, binding.KEEP_LOGITS)
+    both = cfg.dtype == "bf16" and not args.no_modes                                    # the other variant as a mode
     ctx_bytes = binding.cp_head_ctx_bytes(ds)
-    ctx = torch.empty(ctx_bytes, dtype=torch.uint8, device=dev)
-    ds_re = binding.make_desc(cfg.T, cfg.d, cfg.V, cfg.n, cfg.r, ds.dtype, 0)        # the recompute variant
-    ws_bytes = max(binding.cp_head_workspace_bytes(dsc, op) for dsc in (ds, ds_re)
+    ctx = torch.empty(max(ctx_bytes, binding.cp_head_ctx_bytes(ds_keep) if both else 0), dtype=torch.uint8, device=dev)
+    ws_bytes = max(binding.cp_head_workspace_bytes(dsc, op) for dsc in (ds_plain, ds_keep)
                    for op in (binding.OP_LOSS_FWD, binding.OP_LOSS_BWD))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     f32 = dict(dtype=torch.float32, device=dev)
@@ -329,7 +333,7 @@ def bench_loss(args):
         "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
                    "frozen_u": bool(args.frozen_u), "token": "one position (n future tokens each)",
-                   "logits": "kept in HBM between forward and backward" if keep else "recomputed in the backward pass",
+                   "logits": "kept in HBM between forward and backward" if keep else "never stored (recomputed in the backward pass)",
                    "ctx_gib": ctx_bytes / GIB},
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "predicted_tokens_per_s": value * cfg.n,      # every position predicts n tokens
@@ -357,7 +361,7 @@ def bench_loss(args):
     fwd_flops = 2.0 * cfg.n * cfg.r * cfg.d * (cfg.d + cfg.V) * cfg.T
     if not args.no_modes:
         # evaluation keeps no logits: the forward call alone runs without CP_HEAD_KEEP_LOGITS
-        t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds_re, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
+        t_fwd = timed(lambda: binding.cp_head_loss_fwd(ds_plain, H, h.W, h.U, h.G, X, loss, ctx, ws, stream))
         out["forward_only"] = {"ms_per_step": t_fwd * 1e3, "tokens_per_s": cfg.T / t_fwd,
                                "model_tflops": fwd_flops / t_fwd / 1e12}
         # backward alone, on the ctx of a forward call of the timed step's kind
@@ -374,14 +378,19 @@ def bench_loss(args):
         out["frozen_u"] = {"ms_per_step": t_fr * 1e3, "tokens_per_s": cfg.T / t_fr,
                            "model_tflops": fr_flops / t_fr / 1e12,
                            "model_flop_frac_of_bf16_peak": fr_flops / t_fr / 1e12 / PEAK_BF16_TFLOPS}
-    if keep and not args.no_modes:
-        # the same step with the logits recomputed in the backward pass (least HBM: ctx holds y and per-row values only)
-        def recompute_step():
-            binding.cp_head_loss_fwd(ds_re, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
-            binding.cp_head_loss_bwd(ds_re, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, dU, dG, ws, stream)
-        t_re = timed(recompute_step)
-        out["recompute_logits"] = {"ms_per_step": t_re * 1e3, "tokens_per_s": cfg.T / t_re,
-                                   "ctx_gib": binding.cp_head_ctx_bytes(ds_re) / GIB}
+    if both:
+        # the same step in the other variant: logits kept in HBM as 16-bit floats for the backward pass (an opt-in
+        # trade of HBM capacity for the recompute product; it materialises the logits, so it is not the headline),
+        # or, under --keep-logits, the default with no materialised logits
+        ds_other = ds_plain if keep else ds_keep
+
+        def other_step():
+            binding.cp_head_loss_fwd(ds_other, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
+            binding.cp_head_loss_bwd(ds_other, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, dU, dG, ws, stream)
+        t_o = timed(other_step)
+        out["recompute_logits" if keep else "kept_logits"] = {
+            "ms_per_step": t_o * 1e3, "tokens_per_s": cfg.T / t_o, "ctx_gib": binding.cp_head_ctx_bytes(ds_other) / GIB,
+            "model_flop_frac_of_bf16_peak": model_flops / t_o / 1e12 / PEAK_BF16_TFLOPS}
     del ws, ctx, dW, dH, dU, H, h
     torch.cuda.empty_cache()
     if not args.no_draft:

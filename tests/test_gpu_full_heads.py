@@ -136,15 +136,15 @@ def test_empty_batch(gpu):
 SUBSET = 8
 
 
-@pytest.fixture(scope="module")
-def full():
+@pytest.fixture(scope="module", params=[0, KEEP_LOGITS], ids=["no_logits_stored", "kept_logits"])
+def full(request):
     import gc
     import torch
     from paper_2410_17765_amd import head
     cfg = synth.CONFIGS["full_heads"]
     print(f"[full heads] generating {cfg}", flush=True)
     inp = make(cfg)
-    h = head.CpFullHead(inp["F"], inp["G"], dtype=cfg.dtype, flags=KEEP_LOGITS)     # as bench.py times it
+    h = head.CpFullHead(inp["F"], inp["G"], dtype=cfg.dtype, flags=request.param)   # 0: as bench.py times it
     H = head.to_device(inp["H"], cfg.dtype)
     X = torch.from_numpy(inp["X"]).cuda()
     scale = 1.0 / cfg.T
@@ -162,11 +162,14 @@ def test_benchmark_size_sampled_positions(oracle, full):
     cfg, inp, torch, head = full["cfg"], full["inp"], full["torch"], full["head"]
     sel = synth.position_subset(cfg.T, SUBSET)
     print(f"[full heads] oracle on positions {sel.tolist()}", flush=True)
-    ref = oracle.full_loss_fwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel])
+    if "benchmark_size" not in _ORACLE_RESULTS:       # shared by the two variants of the fixture
+        _ORACLE_RESULTS["benchmark_size"] = (
+            oracle.full_loss_fwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel]),
+            oracle.full_loss_bwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel], np.full(len(sel), full["scale"])))
+    ref, rg = _ORACLE_RESULTS["benchmark_size"]
     err = np.abs(full["loss"].cpu().numpy()[sel] - ref).max()
     print(f"  loss max abs err {err:.3e} (mean loss {ref.mean():.3f})", flush=True)
     assert err <= LOSS_ATOL
-    rg = oracle.full_loss_bwd(inp["H"][sel], inp["F"], inp["G"], inp["X"][sel], np.full(len(sel), full["scale"]))
     e = rel_fro(full["grads"]["dH"][torch.from_numpy(sel).cuda()].cpu().numpy(), rg["dH"])
     print(f"  dH rows rel fro {e:.3e}", flush=True)
     assert e <= GRAD_REL_FRO
