@@ -22,13 +22,13 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy) from the rocprofv3 --pmc
-# runs summarised in profiles/loss_head_7b_kernel_stats.md; kernels whose counters were not separated
+# runs summarised in profiles/loss_head_7b_kernel_stats.md (and ..._kept_logits_...); kernels whose counters were not separated
 # there report null.
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
-    ("head_7b", "gemm_z_stats_keep"): (223.494 + 32.562) * GIB,
-    ("head_7b", "gemm_z_stats"): (249.304 + 1.358) * GIB,
-    ("head_7b", "gemm_z_dz"): (25.620 + 7.813) * GIB,
+    ("head_7b", "gemm_z_stats_keep"): (217.507 + 32.541) * GIB,
+    ("head_7b", "gemm_z_stats"): (201.371 + 1.312) * GIB,
+    ("head_7b", "gemm_z_dz"): (25.589 + 7.813) * GIB,
     # draft step: L2 fills of its kernels per step at B = 1, 8, 64 (profiles/draft_b8_kernel_stats.md)
     ("draft", 1): 1.9856 * GIB,
     ("draft", 8): (1.0006 + 1.0108 + 0.0020 + 0.0316 + 0.0022) * GIB,
