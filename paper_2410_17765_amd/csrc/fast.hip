@@ -4,6 +4,8 @@
 //            (logits never stored) -> per-row log-normaliser and fp32 target logit -> mixture.
 // Backward:  per bounded chunk of head rows: recompute z, epilogue writes dz in bf16 ->
 //            dY = dz U and dU += dz^T Y; then dW = dY^T H, dH = dY W + G^T dg, dG = dg^T H.
+// With CP_HEAD_KEEP_LOGITS the forward epilogue also keeps the logits as 16-bit floats and the backward
+// pass reads them back instead of recomputing z (kept_logits.hpp).
 // All products run through the one NT main loop of gemm_nt.hpp; operands that are not
 // K-contiguous are transposed first (HBM-bound passes that cost a few percent of the GEMM time).
 #include "gemm_nt.hpp"
