@@ -20,6 +20,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
+PEAK_FP32_VECTOR_TFLOPS = 157.3   # 256 compute units x 128 fp32 FMA lanes x 2 x 2.4 GHz
 
 # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy) from the rocprofv3 --pmc
 # runs summarised in profiles/loss_head_7b_kernel_stats.md (and ..._kept_logits_...); kernels whose counters were not separated
@@ -317,15 +318,23 @@ def bench_loss(args):
     mean_loss = float(loss.mean())
 
     # roofline of the dominant matrix-product kernel: algorithmic FLOPs of its launches / their summed duration
-    gemms = [k for k in kernels if k[0].startswith("gemm_")]
-    dom = max(gemms, key=lambda k: k[2])
-    achieved = dom[3] / (dom[2] * 1e-3) / 1e12
-    roof = {"bound": "mfma", "kernel": dom[0], "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get((cfg.name, dom[0])),
-            "traffic_unit": "bytes per launch", "launches": dom[1], "avg_ms": dom[2] / dom[1]}
     model_flops = 6.0 * cfg.n * cfg.r * cfg.d * (cfg.d + cfg.V) * cfg.T
     if args.frozen_u:
         model_flops = 2.0 * cfg.n * cfg.r * cfg.d * (3 * cfg.d + 2 * cfg.V) * cfg.T
+    gemms = [k for k in kernels if k[0].startswith("gemm_")]
+    if gemms:
+        dom = max(gemms, key=lambda k: k[2])
+        achieved = dom[3] / (dom[2] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": dom[0], "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get((cfg.name, dom[0])),
+                "traffic_unit": "bytes per launch", "launches": dom[1], "avg_ms": dom[2] / dom[1]}
+    else:
+        # the plain fp32 path (fp32 storage or shapes off the matrix-core path: the small parity workloads): plain
+        # vector arithmetic, the whole step against the fp32 vector peak
+        achieved = model_flops / (ms_per_step * 1e-3) / 1e12
+        roof = {"bound": "alu", "kernel": "plain fp32 path, whole step", "achieved": achieved, "peak": PEAK_FP32_VECTOR_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": None,
+                "traffic_unit": "bytes per launch", "launches": args.steps, "avg_ms": ms_per_step}
     out = {
         "metric": "CP-head fwd+bwd tokens/s", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
