@@ -215,23 +215,36 @@ struct EpiDistillStats {
     const float *tlse;       // [M / R]
     int M, V;
     template <class C>
-    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int tn, char *) const
+    __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int tn, char *smem) const
     {
         const int slot = tn * C::WN + (wave % C::WN);
+        // {lse, log qhat, teacher log-normaliser} of the tile's BM rows: one coalesced load, one row per thread, parked
+        // in LDS (the operand stages are free by now); loaded per block they were a chain of exposed cache misses
+        static_assert(C::THREADS >= C::BM, "one row per thread");
+        float4 *linfo = reinterpret_cast<float4 *>(smem);
+        {
+            const int trow = min(row0 - (wave / C::WN) * C::WTM + (int)threadIdx.x, M - 1);
+            const float2 ra = rowa[trow];
+            const float tl = tlse[trow / R];
+            __syncthreads();                                // every wavefront is done reading operand tiles
+            if ((int)threadIdx.x < C::BM) linfo[threadIdx.x] = make_float4(ra.x, ra.y, tl, 0.f);
+            __syncthreads();
+        }
+        const float4 *winfo = linfo + (wave / C::WN) * C::WTM;
 #pragma unroll
         for (int i = 0; i < C::TM16; ++i) {
-            const int rbase = row0 + 16 * i + 4 * (lane >> 4);
+            const int lbase = 16 * i + 4 * (lane >> 4);
+            const int rbase = row0 + lbase;
             float lse_[4], lq_[4], tl_[4];
             size_t trow_[4];
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const int rc = min(rbase + jj, M - 1);
-                const float2 ra = rowa[rc];
-                lse_[jj] = ra.x;
-                lq_[jj] = ra.y;
-                const int g = rc / R;
-                tl_[jj] = tlse[g];
-                trow_[jj] = (size_t)g * V;
+                const float4 ri = winfo[lbase + jj];
+                lse_[jj] = ri.x;
+                lq_[jj] = ri.y;
+                tl_[jj] = ri.z;
+                trow_[jj] = (size_t)(rc / R) * V;
             }
             float S[4] = {0.f, 0.f, 0.f, 0.f}, KL[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -285,13 +298,31 @@ struct EpiDzDistill {
         constexpr int RG = R < 4 ? R : 4;        // rows of one token among the four registers of a block
         constexpr int NG = 4 / RG;               // tokens among them
         auto dz = [&](int i, int j, int v, int, int) { return f32_to_bf16(acc[i][j][v]); };
+        // The row values of the tile's BM rows and the token values of each row's token come in with one coalesced
+        // load each, one row per thread, and are parked in the last BM * 32 bytes of the LDS buffer, beyond every
+        // staging area of the stores below: loaded where they are used, they were a chain of exposed cache misses.
+        static_assert(C::THREADS >= C::BM, "one row per thread");
+        static_assert(C::WM * C::WN * C::WTN * (64 * 2 + 16) <= C::LDS_BYTES - C::BM * 32, "row values beyond the staging areas");
+        float4 *linfo = reinterpret_cast<float4 *>(smem + C::LDS_BYTES - C::BM * 32), *lgrp = linfo + C::BM;
+        {
+            const int trow = row0 - (wave / C::WN) * C::WTM + (int)threadIdx.x;   // this thread's row of the tile
+            const int crow = trow < Mc ? trow : Mc - 1;
+            const float4 mine = rowinfo[crow], gmine = grp[crow / R];
+            __syncthreads();                                // every wavefront is done reading operand tiles
+            if ((int)threadIdx.x < C::BM) {
+                linfo[threadIdx.x] = mine;
+                lgrp[threadIdx.x] = gmine;
+            }
+            __syncthreads();
+        }
+        const float4 *winfo = linfo + (wave / C::WN) * C::WTM, *wgrp = lgrp + (wave / C::WN) * C::WTM;
         // 64 rows at a time: turn their logits into gradients and write them out at once, so that the
         // finished values do not stay in registers
-        convert<C, RG, NG, 0>(acc, row0, col0, lane);
+        convert<C, RG, NG, 0>(acc, row0, col0, lane, winfo, wgrp);
         store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
         if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         if (C::WTM > 64) {
-            convert<C, RG, NG, 1>(acc, row0, col0, lane);
+            convert<C, RG, NG, 1>(acc, row0, col0, lane, winfo, wgrp);
             store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
             if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         }
@@ -299,19 +330,19 @@ struct EpiDzDistill {
 
     // logits -> gradients, in place, for the 16-row blocks 4 IP .. 4 IP + 3
     template <class C, int RG, int NG, int IP>
-    __device__ __forceinline__ void convert(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane) const
+    __device__ __forceinline__ void convert(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane,
+                                            const float4 *winfo, const float4 *wgrp) const
     {
-        const float4 *__restrict__ rinfo = rowinfo;
-        const float4 *__restrict__ ginfo = grp;
         const bf16_t *__restrict__ tz = TZ;
 #pragma unroll
         for (int i = 4 * IP; i < 4 * IP + 4; ++i) {
-            const int rbase = row0 + 16 * i + 4 * (lane >> 4);
+            const int lbase = 16 * i + 4 * (lane >> 4);      // first of the lane's four rows, in the sub-tile
+            const int rbase = row0 + lbase;
             float lse_[4], lq_[4], c1_[4], c2_[4];
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const int row = rbase + jj;
-                const float4 ri = rinfo[min(row, Mc - 1)];
+                const float4 ri = winfo[lbase + jj];         // rows past the chunk hold the last row's values
                 lse_[jj] = ri.x;
                 lq_[jj] = ri.y;
                 c1_[jj] = row < Mc ? ri.z : 0.f;
@@ -323,7 +354,7 @@ struct EpiDzDistill {
             for (int gi = 0; gi < NG; ++gi) {
                 const int row = rbase + gi * RG;
                 const int g = min(row, Mc - 1) / R;
-                const float4 gv = ginfo[g];
+                const float4 gv = wgrp[lbase + gi * RG];
                 tl_[gi] = gv.x;
                 c3_[gi] = row < Mc ? gv.y : 0.f;
                 x_[gi] = __float_as_int(gv.z);

@@ -168,6 +168,18 @@ struct EpiDz {
     __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
         static_assert(C::WTM == 64 || C::WTM == 128, "sub-tiles of 64 or 128 rows");
+        static_assert(C::WM * C::WN * C::WTN * (64 * 2 + 16) <= C::LDS_BYTES - C::BM * 16, "row values beyond the staging areas");
+        // The row values of the tile's BM rows come in with one coalesced load, one row per thread, and are parked
+        // in the last BM * 16 bytes of the LDS buffer, beyond every staging area of the stores below: loaded where
+        // they are used, they were a chain of sixteen exposed cache misses per tile.
+        static_assert(C::THREADS >= C::BM, "one row per thread");
+        float4 *linfo = reinterpret_cast<float4 *>(smem + C::LDS_BYTES - C::BM * 16);
+        const int trow = row0 - (wave / C::WN) * C::WTM + (int)threadIdx.x;       // this thread's row of the tile
+        const float4 mine = rowinfo[trow < Mc ? trow : Mc - 1];
+        __syncthreads();                                    // every wavefront is done reading operand tiles
+        if ((int)threadIdx.x < C::BM) linfo[threadIdx.x] = mine;
+        __syncthreads();
+        const float4 *winfo = linfo + (wave / C::WN) * C::WTM;     // the rows of this wavefront's sub-tile
         // after convert() the even accumulator of a pair of rows holds both gradients as two bf16
         auto dz = [&](int i, int j, int v, int, int) {
             const uint32_t pk = __float_as_uint(acc[i][j][v & ~1]);
@@ -175,11 +187,11 @@ struct EpiDz {
         };
         // 64 rows at a time: turn their logits into gradients in place and write them out at once, so that
         // the finished values do not stay in registers
-        convert<C, 0>(acc, row0, col0, lane);
+        convert<C, 0>(acc, row0, col0, lane, winfo);
         store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
         if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         if (C::WTM > 64) {
-            convert<C, 1>(acc, row0, col0, lane);
+            convert<C, 1>(acc, row0, col0, lane, winfo);
             store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
             if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         }
@@ -190,18 +202,19 @@ struct EpiDz {
     // one element of a row, so it is a branch that a wavefront takes only where a target falls into its
     // columns.
     template <class C, int IP>
-    __device__ __forceinline__ void convert(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane) const
+    __device__ __forceinline__ void convert(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane,
+                                            const float4 *winfo) const
     {
-        const float4 *__restrict__ info = rowinfo;
         const int lcol = col0 + (lane & 15);
         const bool ragged = col0 + 16 * C::TN16 > V;     // the same for the whole wavefront
 #pragma unroll
         for (int i = 4 * IP; i < 4 * IP + 4; ++i) {
 #pragma unroll
             for (int v = 0; v < 4; v += 2) {
-                const int row = row0 + acc_row(i, v, lane);          // rows row and row + 1
-                const float4 ra = info[row < Mc ? row : Mc - 1];
-                const float4 rb = info[row + 1 < Mc ? row + 1 : Mc - 1];
+                const int lrow = acc_row(i, v, lane);                // rows lrow and lrow + 1 of the sub-tile
+                const int row = row0 + lrow;
+                const float4 ra = winfo[lrow];                       // rows past the chunk hold the last row's values
+                const float4 rb = winfo[lrow + 1];
                 // rows past the chunk hold zero logits: coefficient 0 and offset 0 keep their product finite
                 const float cfa = row < Mc ? ra.y : 0.f, cfb = row + 1 < Mc ? rb.y : 0.f;
                 const float la = row < Mc ? ra.x : 0.f, lb = row + 1 < Mc ? rb.x : 0.f;
