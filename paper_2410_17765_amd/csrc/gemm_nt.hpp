@@ -243,16 +243,10 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
 // One workgroup per output tile.  (A persistent variant, one workgroup per compute unit walking a fixed share
 // of the tiles, was measured twice: it is no faster in isolation and slower inside the step, where a freshly
 // dispatched workgroup goes to whichever compute unit is free first.)
-// An epilogue that needs per-row values from global memory declares a type Pre and a member
-//   template <class C> Pre prefetch(int tile_row0, int tid) const
-// whose loads are issued before the main loop and therefore cost no latency after it; run() then receives the
-// Pre as a last argument.  (Loaded inside the epilogue, such values are a chain of exposed cache misses per tile
-// while the matrix cores idle.)
-template <class Epi, class = void>
-struct epi_has_prefetch { static constexpr bool value = false; };
-template <class Epi>
-struct epi_has_prefetch<Epi, decltype((void)sizeof(typename Epi::Pre))> { static constexpr bool value = true; };
-
+// An epilogue that needs per-row values from global memory fetches them for the whole tile with one coalesced load
+// at its start and parks them in LDS.  (Loaded where they are used they are a chain of exposed cache misses per
+// tile while the matrix cores idle; requested before the main loop they cost the main loop 9 %: the registers
+// they occupy across it change its schedule.)
 template <class Cfg, class Epi>
 __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi epi)
 {
@@ -260,17 +254,11 @@ __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi ep
     int tm, tn;
     if (!tile_of_block(blockIdx.x, gridDim.x, g.tiles_m, g.tiles_n, g.gm, tm, tn)) return;
     f32x4_t acc[Cfg::TM16][Cfg::TN16];
+    gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int row0 = tm * Cfg::BM + (wave / Cfg::WN) * Cfg::WTM;
     const int col0 = tn * Cfg::BN + (wave % Cfg::WN) * Cfg::WTN;
-    if constexpr (epi_has_prefetch<Epi>::value) {
-        const typename Epi::Pre pre = epi.template prefetch<Cfg>(tm * Cfg::BM, (int)threadIdx.x);
-        gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
-        epi.template run<Cfg>(acc, row0, col0, lane, wave, tn, smem, pre);
-    } else {
-        gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
-        epi.template run<Cfg>(acc, row0, col0, lane, wave, tn, smem);
-    }
+    epi.template run<Cfg>(acc, row0, col0, lane, wave, tn, smem);
 }
 
 template <class Cfg, class Epi>
