@@ -57,14 +57,16 @@ enum {
                                    tile of 256 head rows at a time (least workspace, slower)
                                    instead of its default of 32768 rows or 4 GiB worth of them,
                                    whichever is more, up to 8 GiB (0.5 GiB on the plain path) */
-    CP_HEAD_KEEP_LOGITS = 4     /* flags bit 2, matrix-core path of the three loss call pairs (cp_head_loss_,
-                                   cp_head_full_loss_, cp_head_distill_loss_ fwd / bwd; ignored on the plain
-                                   path and by the other calls): the forward pass keeps every logit in ctx as a 16-bit float
-                                   relative to the maximum of its row over a block of 128 columns
-                                   (T*n*r*roundup(V,64)*2 bytes plus 16 bytes per row and 256 columns), and
-                                   the backward pass reads them back instead of multiplying U y a second
-                                   time.  Trades HBM capacity for a quarter of the backward pass's matrix
-                                   work; set it in the desc of both calls or of neither. */
+    CP_HEAD_KEEP_LOGITS = 4     /* flags bit 2, off by default (by default no logit is ever stored).
+                                   Matrix-core path of the three loss call pairs only (cp_head_loss_,
+                                   cp_head_full_loss_, cp_head_distill_loss_ fwd / bwd; ignored on the
+                                   plain path and by the other calls): the forward pass keeps every logit
+                                   in ctx as a 16-bit float relative to the maximum of its row over a
+                                   block of 128 columns (T*n*r*roundup(V,64)*2 bytes plus 16 bytes per row
+                                   and 256 columns), and the backward pass reads them back instead of
+                                   multiplying U y a second time.  Trades HBM capacity for a quarter of
+                                   the backward pass's matrix work; set it in the desc of both calls of a
+                                   pair or of neither. */
 };
 
 enum {
