@@ -149,6 +149,20 @@ def test_new_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cp_head_aux_balance(ctypes.byref(bf), p, p, None, p, p, 256, None) == -1
 
 
+def test_binding_constants_match_the_header():
+    """The Python binding restates the header's enumerators: flags, storage types, error codes, operations."""
+    text = open(os.path.join(ROOT, "include", "cp_head.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    values = {name: int(val) for name, val in re.findall(r"\b(CP_HEAD_[A-Z0-9_]+)\s*=\s*(-?\d+)", text)}
+    assert values["CP_HEAD_FORCE_GENERIC"] == binding.FORCE_GENERIC
+    assert values["CP_HEAD_MIN_WORKSPACE"] == binding.MIN_WORKSPACE
+    assert values["CP_HEAD_KEEP_LOGITS"] == binding.KEEP_LOGITS
+    assert values["CP_HEAD_FP32"] == binding.FP32 and values["CP_HEAD_BF16"] == binding.BF16
+    for name in ("LOSS_FWD", "LOSS_BWD", "DRAFT", "FIRST_TOKEN", "DRAFT_SEQUENTIAL", "AUX_BALANCE", "FULL_LOSS_FWD",
+                 "FULL_LOSS_BWD", "DISTILL_FWD", "DISTILL_BWD"):
+        assert values["CP_HEAD_OP_" + name] == getattr(binding, "OP_" + name), name
+
+
 def test_kept_logits_are_sized_into_ctx_on_the_matrix_core_path_only(lib):
     T, d, V, n, r = 1000, 128, 1000, 2, 3
     plain = binding.make_desc(T, d, V, n, r, binding.BF16, 0)
