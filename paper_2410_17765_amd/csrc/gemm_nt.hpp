@@ -324,6 +324,10 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
     constexpr int RPP = kWave / CPR;                    // rows per store pass
     static_assert(Cfg::WM * Cfg::WN * 32 * RS <= Cfg::LDS_BYTES, "staging fits");
     char *stage = smem + wave * (32 * RS);
+    // a lane's first output address; every later one is a compile-time multiple of the (uniform) row stride away,
+    // which keeps 64-bit multiplies per store out of the vector unit
+    bf16_t *out = dst + (size_t)(row0 + P0 * 32 + lane / CPR) * ld + (col0 + (lane % CPR) * 8);
+    const size_t step = (size_t)RPP * ld;
     __syncthreads();                                    // every wavefront is done reading operand tiles
 #pragma unroll
     for (int p = P0; p < P1; ++p) {
@@ -347,7 +351,8 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
             const u32x4_t val = *reinterpret_cast<const u32x4_t *>(stage + r * RS + ch * 16);
             const int grow = row0 + p * 32 + r, gcol = col0 + ch * 8;
             if (grow < row_limit && gcol < col_limit)
-                *reinterpret_cast<u32x4_t *>(dst + (size_t)grow * ld + gcol) = val;
+                *reinterpret_cast<u32x4_t *>(out) = val;
+            out += step;
         }
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);              // conversions of the next pass stay behind this one's stores
@@ -367,6 +372,8 @@ __device__ __forceinline__ void store_tile_bf16_pair(char *smem, int wave, int l
     constexpr int REGION = Cfg::WM * Cfg::WN * 32 * RS;  // staging of one output
     static_assert(2 * REGION <= Cfg::LDS_BYTES, "staging fits");
     char *stage = smem + wave * (32 * RS);
+    size_t off = (size_t)(row0 + lane / CPR) * ld + (col0 + (lane % CPR) * 8);            // as in store_tile_bf16
+    const size_t step = (size_t)RPP * ld;
     __syncthreads();
 #pragma unroll
     for (int p = 0; p < Cfg::WTM / 32; ++p) {
@@ -393,9 +400,10 @@ __device__ __forceinline__ void store_tile_bf16_pair(char *smem, int wave, int l
             const u32x4_t v1 = *reinterpret_cast<const u32x4_t *>(stage + REGION + r * RS + ch * 16);
             const int grow = row0 + p * 32 + r, gcol = col0 + ch * 8;
             if (grow < row_limit && gcol < col_limit) {
-                *reinterpret_cast<u32x4_t *>(dst0 + (size_t)grow * ld + gcol) = v0;
-                *reinterpret_cast<u32x4_t *>(dst1 + (size_t)grow * ld + gcol) = v1;
+                *reinterpret_cast<u32x4_t *>(dst0 + off) = v0;
+                *reinterpret_cast<u32x4_t *>(dst1 + off) = v1;
             }
+            off += step;
         }
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
@@ -416,6 +424,8 @@ __device__ __forceinline__ void store_tile_bf16_transposed(char *smem, int wave,
     constexpr int CS = 64 * 2 + 16;                     // padded column stride in bytes (64 rows)
     static_assert(Cfg::WM * Cfg::WN * Cfg::WTN * CS <= Cfg::LDS_BYTES, "staging fits");
     char *stage = smem + wave * (Cfg::WTN * CS);
+    bf16_t *const out0 = dst + (size_t)(col0 + (lane >> 3)) * ld + (row0 + (lane & 7) * 8);         // as in store_tile_bf16
+    const size_t step = (size_t)8 * ld;
     __syncthreads();
 #pragma unroll
     for (int ip = IP0; ip < IP1; ++ip) {
@@ -443,13 +453,15 @@ __device__ __forceinline__ void store_tile_bf16_transposed(char *smem, int wave,
             }
         }
         __syncthreads();
+        bf16_t *out = out0 + ip * 64;
 #pragma unroll
         for (int p = 0; p < Cfg::WTN / 8; ++p) {
             const int c = p * 8 + (lane >> 3), ch = lane & 7;
             const u32x4_t val = *reinterpret_cast<const u32x4_t *>(stage + c * CS + ch * 16);
             const int grow = row0 + ip * 64 + ch * 8, gcol = col0 + c;
             if (grow < row_limit && gcol < col_limit)
-                *reinterpret_cast<u32x4_t *>(dst + (size_t)gcol * ld + grow) = val;
+                *reinterpret_cast<u32x4_t *>(out) = val;
+            out += step;
         }
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
@@ -467,6 +479,8 @@ __device__ __forceinline__ void store_tile_f32(char *smem, int wave, int lane, i
     constexpr int RPP = kWave / CPR;
     static_assert(Cfg::WM * Cfg::WN * 32 * RS <= Cfg::LDS_BYTES, "staging fits");
     char *stage = smem + wave * (32 * RS);
+    float *out = dst + (size_t)(row0 + lane / CPR) * ld + (col0 + (lane % CPR) * 4);          // as in store_tile_bf16
+    const size_t step = (size_t)RPP * ld;
     __syncthreads();
 #pragma unroll
     for (int p = 0; p < Cfg::WTM / 32; ++p) {
@@ -490,10 +504,11 @@ __device__ __forceinline__ void store_tile_f32(char *smem, int wave, int lane, i
             f32x4_t val = *reinterpret_cast<const f32x4_t *>(stage + r * RS + ch * 16);
             const int grow = row0 + p * 32 + r, gcol = col0 + ch * 4;
             if (grow < row_limit && gcol < col_limit) {
-                f32x4_t *o = reinterpret_cast<f32x4_t *>(dst + (size_t)grow * ld + gcol);
+                f32x4_t *o = reinterpret_cast<f32x4_t *>(out);
                 if (accumulate) val += *o;
                 *o = val;
             }
+            out += step;
         }
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
