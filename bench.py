@@ -27,9 +27,9 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3   # 256 compute units x 128 fp32 FMA lanes x 2 x
 # there report null.
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
-    ("head_7b", "gemm_z_stats_keep"): (213.827 + 32.530) * GIB,
-    ("head_7b", "gemm_z_stats"): (230.669 + 1.266) * GIB,
-    ("head_7b", "gemm_z_dz"): (25.861 + 7.812) * GIB,
+    ("head_7b", "gemm_z_stats_keep"): (212.209 + 32.555) * GIB,
+    ("head_7b", "gemm_z_stats"): (220.394 + 1.311) * GIB,
+    ("head_7b", "gemm_z_dz"): (25.780 + 7.812) * GIB,
     # draft step: L2 fills of its kernels per step at B = 1, 8, 64 (profiles/draft_b8_kernel_stats.md)
     ("draft", 1): 1.9856 * GIB,
     ("draft", 8): (1.0006 + 1.0108 + 0.0020 + 0.0316 + 0.0022) * GIB,
