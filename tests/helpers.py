@@ -26,6 +26,22 @@ def loss_atol_bf16(cfg) -> float:
     return tol * max(1.0, cfg.n / 4) * max(1.0, (256.0 / cfg.d) ** 0.5)
 
 
+def distill_loss_atol_bf16(cfg) -> float:
+    """Loss bound of the fine-tuning loss (eq. 14) on the matrix-core path.  Its KL term weights the error of every
+    single logit by the teacher's probability: with dz_v = U_v . dy (dy the bf16 rounding of y, relative rms
+    2^-9 / sqrt(3) = 1.1e-3),
+        d KL_k = (U^T (p^d - p^c)) . dy,   rms = 1.1e-3 u_scale sqrt(sum_v p^c_v^2 + sum_v p^d_v^2),
+    independent of d.  For the synthetic teacher (logits N(0, 1.5^2)) and student (about N(0, 1)) the two sums are
+    e^2.25 / V and e / V, together 12 / V: negligible at a language model's vocabulary (1.4e-5 at V = 32000), but
+    3e-4 per token at V = 131, where single positions with a peaked teacher row reach five to six times the rms
+    of a batch.  The bound is the training loss's, or ten times that rms over the n tokens of a position,
+    whichever is larger; it scales with the logits (u_scale)."""
+    base = loss_atol_bf16(cfg)
+    if cfg.dtype == "fp32":
+        return base * cfg.u_scale
+    return max(base, 10 * 1.1e-3 * (12.0 * cfg.n / cfg.V) ** 0.5) * cfg.u_scale
+
+
 def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2410_17765_amd import synth
-from tests.helpers import GRAD_REL_FRO, LOSS_ATOL, loss_atol_bf16, rel_fro
+from tests.helpers import distill_loss_atol_bf16, GRAD_REL_FRO, LOSS_ATOL, loss_atol_bf16, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -75,8 +75,9 @@ def test_loss_and_gradients(gpu, oracle, cfg, flags, beta, disc):
     # The logits behind the log-normalisers and the mixture come from y rounded to bf16 (the matrix-core
     # operand): each carries an error of about |U_v| rms(y) 2^-9 / sqrt(3) = 1.1e-3 u_scale, which the
     # probability-weighted sums average down.  The bound is the loss tolerance at the prescribed
-    # initialisation and scales with the logits otherwise.
-    assert err <= loss_atol_bf16(cfg) * cfg.u_scale
+    # initialisation, scales with the logits otherwise, and grows where a small vocabulary leaves the teacher's
+    # probabilities little to average over (see the helper).
+    assert err <= distill_loss_atol_bf16(cfg)
     for k in ("dH", "dW", "dU", "dG"):
         if k == "dG" and cfg.r == 1:
             # one expert: the gate weight is the constant 1 and its gradient vanishes identically
