@@ -204,11 +204,13 @@ int CPO(joint_prob_naive)(const cpo_shape *sh, const in_t *H, const in_t *W, con
         for (int al = 0; al < r; ++al) {
             double term = g[al] / gsum;                                /* w_a, eq. 7 */
             for (int s = 0; s < n; ++s) {
+                const int x = X[(size_t)t * n + s];
+                if (x < 0) continue;                                   /* a dropped factor, as in loss_fwd */
                 head_y(sh, h, W, s, al, y);
                 head_z(sh, U, y, z);
                 double zsum = 0.0;
                 for (int v = 0; v < V; ++v) zsum += exp(z[v]);
-                term *= exp(z[X[(size_t)t * n + s]]) / zsum;           /* eq. 6 */
+                term *= exp(z[x]) / zsum;                              /* eq. 6 */
             }
             total += term;                                             /* eq. 2 */
         }

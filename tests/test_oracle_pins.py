@@ -11,7 +11,11 @@ transposed operand) fails at least one of them:
 * mixture invariants: identical experts, expert permutation, Jensen;
 * backward: central finite differences for every input, zero-sum invariants;
 * sampling: chain of conditionals (eq. 11-13) multiplies to the joint, tuple
-  frequencies follow the joint, boundary cases of the inverse CDF.
+  frequencies follow the joint, boundary cases of the inverse CDF;
+* the rounded-y mode that defines the draft calls (y -> bfloat16 before U y): every
+  routine that takes it against a library composition with an independently written
+  rounding, identity on representable y, and the hooks for rounding ties (exact y,
+  zero nudge, a nudge across one midpoint = one ulp of one element).
 """
 import itertools
 
@@ -159,6 +163,8 @@ def test_negative_target_drops_factor(oracle):
     l_drop = oracle.loss_fwd(H, W, U, G, Xd)
     l_short = oracle.loss_fwd(H, W[:2].copy(), U, G, X[:, :2].copy())
     np.testing.assert_allclose(l_drop, l_short, rtol=1e-13)
+    # the probability-space routine drops the same factors
+    np.testing.assert_allclose(oracle.joint_prob_naive(H, W, U, G, Xd), np.exp(-l_short), rtol=1e-12)
     g_drop = oracle.loss_bwd(H, W, U, G, Xd)
     g_short = oracle.loss_bwd(H, W[:2].copy(), U, G, X[:, :2].copy())
     np.testing.assert_allclose(g_drop["dW"][:2], g_short["dW"], rtol=1e-9, atol=1e-14)
@@ -359,6 +365,216 @@ def test_rounded_y_changes_loss_by_the_expected_amount(oracle):
     diff = np.abs(l0 - l1)
     # bf16 rounding of y perturbs each target logit by about 2^-9 |z|: visible, but small
     assert 1e-5 < diff.max() < 3e-2
+
+
+# ---------------------------------------------------------------------------
+# the rounded-y mode (y -> bfloat16 before z = U y) and the hooks for rounding ties.
+# The draft calls are defined with this rounding, so where it is applied is part of the definition:
+# each routine that takes round_y is compared with a numpy/scipy composition that rounds W_sa h, and
+# nothing else, with a rounding routine written independently of the oracle's (integer arithmetic on
+# the fp64 bit pattern instead of frexp/nearbyint).
+# ---------------------------------------------------------------------------
+
+def bf16_nearest_even(x):
+    """fp64 -> nearest value with 8 significant bits, ties to even, on the bit pattern: 45 of the 52
+    fraction bits are dropped, a carry out of the fraction rightly bumps the exponent."""
+    bits = np.ascontiguousarray(x, dtype=np.float64).view(np.uint64)
+    drop = np.uint64(45)
+    keep_lsb = (bits >> drop) & np.uint64(1)
+    bits = ((bits + np.uint64((1 << 44) - 1) + keep_lsb) >> drop) << drop
+    return bits.view(np.float64)
+
+
+def composed_log_factors(H, W, U, G, round_y, y_override=None):
+    """(logw[B,r], logP[B,n,r,V], y[B,n,r,d] before rounding) from library routines; the rounding, if any,
+    is applied to y = W_sa h only.  y_override replaces the (rounded) y that enters U y."""
+    logw = sps.log_softmax(H @ G.T, axis=-1)
+    Y = np.einsum("sakj,bj->bsak", W, H)
+    Yin = bf16_nearest_even(Y) if round_y else Y
+    if y_override is not None:
+        Yin = y_override
+    Z = np.einsum("vk,bsak->bsav", U, Yin)
+    return logw, sps.log_softmax(Z, axis=-1), Y
+
+
+def rounding_problem(B=5, seed=61, **kw):
+    H, W, U, G, _ = small_problem(T=B, seed=seed, **kw)
+    return H, W, U * 3.0, G            # peaked enough that one bf16 ulp of y is far above 1e-12
+
+
+def test_bit_pattern_rounding_agrees_with_the_oracles_helper(oracle):
+    rng = np.random.default_rng(60)
+    vals = np.concatenate([rng.standard_normal(3000) * np.exp(rng.uniform(-20, 20, 3000)),
+                           [1.00390625, 1.01171875, 1.998046875, -1.998046875, 255.5, 0.0]])
+    got = np.array([oracle.round_to_bf16(float(v)) for v in vals])
+    np.testing.assert_array_equal(got, bf16_nearest_even(vals))
+    # every result has 8 significant bits: it survives float32 -> bfloat16 truncation unchanged
+    as_f32 = got.astype(np.float32)
+    assert (as_f32.astype(np.float64) == got).all()
+    assert ((as_f32.view(np.uint32) & 0xFFFF) == 0).all()
+
+
+def test_rounded_y_loss_is_the_composition_with_y_rounded(oracle):
+    H, W, U, G = rounding_problem(B=6)
+    X = np.random.default_rng(62).integers(0, U.shape[0], size=(6, W.shape[0])).astype(np.int32)
+    logw, logP, _ = composed_log_factors(H, W, U, G, True)
+    C = np.take_along_axis(logP, X[:, :, None, None].astype(np.int64).repeat(W.shape[1], axis=2), axis=3)[..., 0]
+    ref = -sps.logsumexp(logw + C.sum(axis=1), axis=-1)
+    got = oracle.loss_fwd(H, W, U, G, X, round_y=True)
+    np.testing.assert_allclose(got, ref, rtol=1e-12)
+    # and the rounding matters at this size: the unrounded loss is measurably another number
+    assert np.abs(got - oracle.loss_fwd(H, W, U, G, X)).max() > 1e-5
+    for t in range(2):
+        cond = oracle.sequential_conditional(H, W, U, G, t, [int(X[t, 0])], round_y=True)
+        q = sps.softmax(logw[t] + logP[t, 0, :, X[t, 0]])
+        np.testing.assert_allclose(cond, q @ np.exp(logP[t, 1]), rtol=1e-11)
+
+
+def test_rounded_y_draft_is_the_composition_with_y_rounded(oracle):
+    H, W, U, G = rounding_problem()
+    B, n, r = H.shape[0], W.shape[0], W.shape[1]
+    u = synth.uniforms(B, n, seed=63).astype(np.float64)
+    logw, logP, Y = composed_log_factors(H, W, U, G, True)
+    a, tok, logq, cdf_w, cdf_tok, y_exact = oracle.draft_sample(H, W, U, G, u, round_y=True, want_cdf=True, want_y=True)
+    np.testing.assert_allclose(cdf_w, np.cumsum(np.exp(logw), axis=1), rtol=1e-12)
+    np.testing.assert_allclose(y_exact, Y, rtol=1e-13, atol=1e-15)            # y before rounding, nothing added
+    for b in range(B):
+        assert a[b] == min(int(np.searchsorted(cdf_w[b], u[b, 0], side="right")), r - 1)
+        for s in range(n):
+            ref = np.cumsum(np.exp(logP[b, s, a[b]]))
+            np.testing.assert_allclose(cdf_tok[b, s], ref, rtol=1e-12)
+            assert tok[b, s] == min(int(np.searchsorted(cdf_tok[b, s], u[b, 1 + s], side="right")), U.shape[0] - 1)
+        lq = sps.logsumexp(logw[b] + sum(logP[b, s, :, tok[b, s]] for s in range(n)))
+        np.testing.assert_allclose(logq[b], lq, rtol=1e-12)
+    # teeth: neither "no rounding" nor "rounding somewhere else" reproduces these running sums
+    _, logP_plain, _ = composed_log_factors(H, W, U, G, False)
+    assert max(np.abs(np.cumsum(np.exp(logP_plain[b, s, a[b]])) - cdf_tok[b, s]).max()
+               for b in range(B) for s in range(n)) > 1e-6
+    Zr = bf16_nearest_even(np.einsum("vk,bsak->bsav", U, Y))                   # rounding z instead of y
+    logP_z = sps.log_softmax(Zr, axis=-1)
+    assert max(np.abs(np.cumsum(np.exp(logP_z[b, s, a[b]])) - cdf_tok[b, s]).max()
+               for b in range(B) for s in range(n)) > 1e-6
+
+
+def test_rounded_y_first_token_and_sequential_are_the_composition(oracle):
+    H, W, U, G = rounding_problem(seed=64)
+    B, n, V = H.shape[0], W.shape[0], U.shape[0]
+    logw, logP, _ = composed_log_factors(H, W, U, G, True)
+    lp = oracle.first_token_logprob(H, W, U, G, round_y=True)
+    np.testing.assert_allclose(lp, sps.logsumexp(logw[:, :, None] + logP[:, 0], axis=1), rtol=1e-12, atol=1e-13)
+    assert np.abs(lp - oracle.first_token_logprob(H, W, U, G, round_y=False)).max() > 1e-6
+    u = np.random.default_rng(65).random((B, n))
+    tok, logq, cdf = oracle.draft_sample_sequential(H, W, U, G, u, round_y=True, want_cdf=True)
+    for b in range(B):
+        q = logw[b].copy()
+        for s in range(n):
+            ref = np.cumsum(sps.softmax(q) @ np.exp(logP[b, s]))
+            np.testing.assert_allclose(cdf[b, s], ref, rtol=1e-11)
+            assert tok[b, s] == min(int(np.searchsorted(cdf[b, s], u[b, s], side="right")), V - 1)
+            q = q + logP[b, s, :, tok[b, s]]
+        np.testing.assert_allclose(logq[b], sps.logsumexp(q), rtol=1e-12)
+
+
+def test_rounding_is_the_identity_on_representable_y(oracle):
+    # small integer W and h: every y is an integer below 256, exactly a bfloat16, so the rounded mode must
+    # return the unrounded mode's results bit for bit (rounding anything else, e.g. z, would not)
+    rng = np.random.default_rng(66)
+    B, d, V, n, r = 4, 8, 11, 3, 3
+    H = rng.integers(-2, 3, size=(B, d)).astype(np.float64)
+    W = rng.integers(-1, 2, size=(n, r, d, d)).astype(np.float64)
+    U = rng.standard_normal((V, d)) * 0.2
+    G = rng.standard_normal((r, d)) * 0.3
+    X = rng.integers(0, V, size=(B, n)).astype(np.int32)
+    u = synth.uniforms(B, n, seed=67).astype(np.float64)
+    assert np.abs(np.einsum("sakj,bj->bsak", W, H)).max() <= 256
+    for x, y in zip(oracle.draft_sample(H, W, U, G, u, round_y=True, want_cdf=True),
+                    oracle.draft_sample(H, W, U, G, u, round_y=False, want_cdf=True)):
+        np.testing.assert_array_equal(x, y)
+    np.testing.assert_array_equal(oracle.first_token_logprob(H, W, U, G, round_y=True),
+                                  oracle.first_token_logprob(H, W, U, G, round_y=False))
+    for x, y in zip(oracle.draft_sample_sequential(H, W, U, G, u[:, 1:], round_y=True, want_cdf=True),
+                    oracle.draft_sample_sequential(H, W, U, G, u[:, 1:], round_y=False, want_cdf=True)):
+        np.testing.assert_array_equal(x, y)
+    np.testing.assert_array_equal(oracle.loss_fwd(H, W, U, G, X, round_y=True), oracle.loss_fwd(H, W, U, G, X))
+
+
+def _nudge_across_midpoint(y):
+    """For one exact value y: (nudge, other) with y + nudge just across the rounding midpoint on the side of
+    the bfloat16 neighbour `other` that y does not round to."""
+    near = float(bf16_nearest_even(np.array([y]))[0])
+    ulp = 2.0 ** (np.floor(np.log2(abs(y))) - 7)
+    other = near + ulp if y > near else near - ulp
+    mid = 0.5 * (near + other)
+    nudge = (mid - y) + np.sign(other - near) * 1e-3 * ulp
+    assert float(bf16_nearest_even(np.array([y + nudge]))[0]) == other and abs(other - near) == ulp
+    return nudge, other
+
+
+def test_tie_hooks_of_the_draft_routines(oracle):
+    """y_exact is the value before the nudge and before rounding; a zero nudge is the identity; a nudge that takes one
+    element across its rounding midpoint moves exactly that element of the rounded y by one bfloat16 ulp."""
+    H, W, U, G = rounding_problem(seed=68)
+    B, n, r, d = H.shape[0], W.shape[0], W.shape[1], H.shape[1]
+    u = synth.uniforms(B, n, seed=69).astype(np.float64)
+    logw, logP, Y = composed_log_factors(H, W, U, G, True)
+    forced = np.array([1, 0, 2, 1, 3], dtype=np.int32)[:B] % r
+    base = oracle.draft_sample(H, W, U, G, u, round_y=True, alpha_in=forced, want_cdf=True, want_y=True)
+    zero = oracle.draft_sample(H, W, U, G, u, round_y=True, alpha_in=forced, want_cdf=True, want_y=True,
+                               y_nudge=np.zeros((B, n, r, d)))
+    for x, y in zip(base, zero):
+        np.testing.assert_array_equal(x, y)
+    np.testing.assert_array_equal(oracle.first_token_logprob(H, W, U, G, round_y=True, y_nudge=np.zeros((B, r, d))),
+                                  oracle.first_token_logprob(H, W, U, G, round_y=True))
+    for x, y in zip(oracle.draft_sample_sequential(H, W, U, G, u[:, 1:], round_y=True, want_cdf=True,
+                                                   y_nudge=np.zeros((B, n, r, d))),
+                    oracle.draft_sample_sequential(H, W, U, G, u[:, 1:], round_y=True, want_cdf=True)):
+        np.testing.assert_array_equal(x, y)
+
+    b, s, k = 2, 1, 5
+    a = int(forced[b])
+    nudge, other = _nudge_across_midpoint(Y[b, s, a, k])
+    nd = np.zeros((B, n, r, d))
+    nd[b, s, a, k] = nudge
+    Yr = bf16_nearest_even(Y)
+    ulp = abs(other - Yr[b, s, a, k])
+    Yr[b, s, a, k] = other
+    _, logP2, _ = composed_log_factors(H, W, U, G, True, y_override=Yr)
+    got = oracle.draft_sample(H, W, U, G, u, round_y=True, alpha_in=forced, want_cdf=True, want_y=True, y_nudge=nd)
+    np.testing.assert_array_equal(got[5], base[5])                      # y_exact does not see the nudge
+    np.testing.assert_allclose(got[5], Y, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(got[4][b, s], np.cumsum(np.exp(logP2[b, s, a])), rtol=1e-12)
+    moved = np.abs(got[4][b, s] - base[4][b, s]).max()
+    assert moved > 1e-9, "one ulp of one element must be visible in the running sums"
+    # one ulp exactly: the running sums are those of the other neighbour, not of any value in between
+    Yhalf = bf16_nearest_even(Y)
+    Yhalf[b, s, a, k] += 0.5 * np.sign(other - Yhalf[b, s, a, k]) * ulp
+    _, logPh, _ = composed_log_factors(H, W, U, G, True, y_override=Yhalf)
+    assert np.abs(got[4][b, s] - np.cumsum(np.exp(logPh[b, s, a]))).max() > 0.2 * moved
+    # nothing else moved: every other row's running sums are bit-identical
+    mask = np.ones((B, n), bool)
+    mask[b, s] = False
+    np.testing.assert_array_equal(got[4][mask], base[4][mask])
+    keep = np.arange(B) != b
+    np.testing.assert_array_equal(got[2][keep], base[2][keep])
+    lq = sps.logsumexp(logw[b] + sum(logP2[b, t, :, got[1][b, t]] for t in range(n)))
+    np.testing.assert_allclose(got[2][b], lq, rtol=1e-12)
+
+    # the same nudge through the other two routines
+    tok, logq, cdf = oracle.draft_sample_sequential(H, W, U, G, u[:, 1:], round_y=True, want_cdf=True, y_nudge=nd)
+    q = logw[b].copy()
+    for t in range(n):
+        np.testing.assert_allclose(cdf[b, t], np.cumsum(sps.softmax(q) @ np.exp(logP2[b, t])), rtol=1e-11)
+        q = q + logP2[b, t, :, tok[b, t]]
+    np.testing.assert_allclose(logq[b], sps.logsumexp(q), rtol=1e-12)
+    nudge0, other0 = _nudge_across_midpoint(Y[b, 0, a, k])
+    nd0 = np.zeros((B, r, d))
+    nd0[b, a, k] = nudge0
+    Yr0 = bf16_nearest_even(Y)
+    Yr0[b, 0, a, k] = other0
+    _, logP0, _ = composed_log_factors(H, W, U, G, True, y_override=Yr0)
+    lp = oracle.first_token_logprob(H, W, U, G, round_y=True, y_nudge=nd0)
+    np.testing.assert_allclose(lp, sps.logsumexp(logw[:, :, None] + logP0[:, 0], axis=1), rtol=1e-12, atol=1e-13)
+    assert np.abs(lp[b] - oracle.first_token_logprob(H, W, U, G, round_y=True)[b]).max() > 1e-9
 
 
 # ---------------------------------------------------------------------------

@@ -79,6 +79,27 @@ MUTANTS = [
     ("distill_backward_discount", "for (int k = 0; k < n; ++k, weight *= disc) {",
      "for (int k = 0; k < n; ++k, weight *= 1.0) {", 1,
      [("test_distill_gradients_match_central_differences", "H"), ("test_distill_gradients_match_central_differences", "W")]),
+    # the rounded-y mode and its hooks for rounding ties (several sites at once: old is a list of edits, new is None)
+    ("rounding_applied_to_z_not_y",
+     [("y[k] = sh->round_y ? round_to_bf16(acc) : acc;", "y[k] = acc;", None),
+      ("        z[v] = acc;\n", "        z[v] = sh->round_y ? round_to_bf16(acc) : acc;\n", 0)], None, None,
+     ["test_rounded_y_draft_is_the_composition_with_y_rounded", "test_rounding_is_the_identity_on_representable_y",
+      "test_rounded_y_first_token_and_sequential_are_the_composition"]),
+    ("nudge_added_after_rounding",
+     [("        if (nudge) acc += nudge[k];\n", "", None),
+      ("y[k] = sh->round_y ? round_to_bf16(acc) : acc;",
+       "y[k] = (sh->round_y ? round_to_bf16(acc) : acc) + (nudge ? nudge[k] : 0.0);", None)], None, None,
+     ["test_tie_hooks_of_the_draft_routines"]),
+    ("y_exact_taken_after_the_nudge",
+     [("        if (y_exact) y_exact[k] = acc;\n        if (nudge) acc += nudge[k];\n",
+       "        if (nudge) acc += nudge[k];\n        if (y_exact) y_exact[k] = acc;\n", None)], None, None,
+     ["test_tie_hooks_of_the_draft_routines"]),
+    ("rounded_mode_ignored_by_first_token", "head_y_ex(sh, h, W, 0, al, y_nudge ? y_nudge + ((size_t)b * r + al) * d : NULL, NULL, y);",
+     "head_y(&(cpo_shape){sh->T, sh->d, sh->V, sh->n, sh->r, 0}, h, W, 0, al, y);", None,
+     ["test_rounded_y_first_token_and_sequential_are_the_composition"]),
+    ("nudge_of_the_wrong_row_in_sequential", "y_nudge ? y_nudge + (((size_t)b * n + s) * r + al) * d : NULL, NULL, y);",
+     "y_nudge ? y_nudge + (((size_t)b * r + al) * n + s) * d : NULL, NULL, y);", None,
+     ["test_tie_hooks_of_the_draft_routines"]),
 ]
 
 
@@ -87,15 +108,17 @@ def mutated_oracle(tmp_path, old, new, occurrence):
     d = os.path.join(str(tmp_path), "oracle_mutant")
     os.makedirs(d, exist_ok=True)
     src = open(os.path.join(ORACLE_DIR, "cp_oracle.c")).read()
-    count = src.count(old)
-    assert count >= 1, f"mutation site not found: {old!r}"
-    if occurrence is None:
-        assert count == 1, f"mutation site is not unique ({count}): {old!r}"
-        src = src.replace(old, new)
-    else:
-        parts = src.split(old)
-        assert occurrence < len(parts) - 1
-        src = old.join(parts[:occurrence + 1]) + new + old.join(parts[occurrence + 1:])
+    edits = [(old, new, occurrence)] if isinstance(old, str) else old
+    for old, new, occurrence in edits:
+        count = src.count(old)
+        assert count >= 1, f"mutation site not found: {old!r}"
+        if occurrence is None:
+            assert count == 1, f"mutation site is not unique ({count}): {old!r}"
+            src = src.replace(old, new)
+        else:
+            parts = src.split(old)
+            assert occurrence < len(parts) - 1
+            src = old.join(parts[:occurrence + 1]) + new + old.join(parts[occurrence + 1:])
     with open(os.path.join(d, "cp_oracle.c"), "w") as f:
         f.write(src)
     shutil.copy(os.path.join(ORACLE_DIR, "cp_oracle.py"), os.path.join(d, "cp_oracle.py"))
