@@ -119,6 +119,14 @@ int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes);
  *     C_sa    = z_sa[X[t,s]] - logsumexp_v z_sa[v],   z_sa = U (W_sa h_t)
  *     loss[t] = -logsumexp_a( log w_a + sum_s C_sa )          (nats, no reduction)
  * loss[T] is fp32, overwritten.  ctx receives what the backward pass needs.
+ * Precision on the matrix-core path (bf16 storage): the log-normalisers are formed from logits of y
+ * rounded to bf16 (a matrix-core operand), the target logit z_sa[X[t,s]] from y kept to about fp32
+ * (bf16 value plus bf16 residual).  exp(-loss) is therefore the joint of eq. 2 only up to that
+ * mixed rounding: within 2e-3 of the unrounded value at the workloads' shapes.  -logq that
+ * cp_head_draft_sample reports for the same tokens takes every term from the rounded y and
+ * differs from loss by the rounding of the n target logits: rms about 1.1e-3 sqrt(n) for logits
+ * of unit scale, below 1e-2 at n = 4.  The backward pass differentiates the function with the
+ * rounded y throughout.
  */
 int cp_head_loss_fwd(const cp_head_desc *desc,
                      const void *H, const void *W, const void *U, const void *G,
@@ -155,7 +163,9 @@ int cp_head_loss_bwd(const cp_head_desc *desc,
  * rounded to bf16 (nearest-even) before z = U y: that rounding is part of the
  * sampled distribution's definition.
  * Outputs: alpha[B] int32, tokens[B,n] int32, logq[B] fp32 (may be NULL) =
- * log of eq. 2 at the drawn tuple, summed over all experts.
+ * log of eq. 2 at the drawn tuple, summed over all experts, every logit taken from the
+ * rounded y (so -logq and cp_head_loss_fwd at the same tokens differ by the rounding of
+ * the n target logits: see cp_head_loss_fwd).
  */
 int cp_head_draft_sample(const cp_head_desc *desc,
                          const void *H, const void *W, const void *U, const void *G,

@@ -21,18 +21,33 @@ std::vector<ProfileRecord> g_profile;
 }  // namespace
 
 namespace cph {
-void profile_begin(const char *name, double work, hipStream_t st)
+// Returns whether a record was pushed: only then may profile_end record its stop event.
+bool profile_begin(const char *name, double work, hipStream_t st)
 {
-    if (!g_profile_on) return;
+    if (!g_profile_on) return false;
     ProfileRecord rec{name, work, nullptr, nullptr};
-    if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) return;
-    (void)hipEventRecord(rec.start, st);
+    if (hipEventCreate(&rec.start) != hipSuccess) return false;
+    if (hipEventCreate(&rec.stop) != hipSuccess) {
+        (void)hipEventDestroy(rec.start);
+        return false;
+    }
+    if (hipEventRecord(rec.start, st) != hipSuccess) {
+        (void)hipEventDestroy(rec.start);
+        (void)hipEventDestroy(rec.stop);
+        return false;
+    }
     g_profile.push_back(rec);
+    return true;
 }
 void profile_end(hipStream_t st)
 {
-    if (!g_profile_on || g_profile.empty()) return;
-    (void)hipEventRecord(g_profile.back().stop, st);
+    if (g_profile.empty()) return;
+    ProfileRecord &rec = g_profile.back();
+    if (hipEventRecord(rec.stop, st) != hipSuccess) {          // a record without a stop event is dropped
+        (void)hipEventDestroy(rec.start);
+        (void)hipEventDestroy(rec.stop);
+        g_profile.pop_back();
+    }
 }
 }  // namespace cph
 
@@ -55,6 +70,13 @@ int check_desc(const cp_head_desc *ds)
     return CP_HEAD_OK;
 }
 
+// The fine-tuning loss runs ranks other than 1, 2, 4, 8 on the plain path even where the training loss would use
+// the matrix cores, so the plain path's limit on d applies to it by its own path selector.
+bool distill_shape_supported(const cp_head_desc &ds)
+{
+    return distill_on_matrix_cores(ds) || ds.d <= kMaxGenericD;
+}
+
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) != 0; }
 
 size_t workspace_need(const cp_head_desc &ds, int op)
@@ -69,6 +91,7 @@ size_t workspace_need(const cp_head_desc &ds, int op)
     if (op == CP_HEAD_OP_DRAFT_SEQUENTIAL) return generic_workspace_bytes(ds, CP_HEAD_OP_DRAFT);   // same buffers
     return generic_workspace_bytes(ds, op);
 }
+
 
 }  // namespace
 
@@ -99,10 +122,11 @@ int cp_head_profile_read(cp_head_kernel_time *out, int max_entries, int *count)
     std::vector<cp_head_kernel_time> rows;
     for (ProfileRecord &rec : g_profile) {
         float ms = 0.f;
-        (void)hipEventSynchronize(rec.stop);
-        (void)hipEventElapsedTime(&ms, rec.start, rec.stop);
+        const bool timed = hipEventSynchronize(rec.stop) == hipSuccess &&
+                           hipEventElapsedTime(&ms, rec.start, rec.stop) == hipSuccess;
         (void)hipEventDestroy(rec.start);
         (void)hipEventDestroy(rec.stop);
+        if (!timed) continue;                                    // never fold an unmeasured launch into the averages
         size_t i = 0;
         for (; i < rows.size(); ++i)
             if (std::string(rows[i].name) == rec.name) break;
@@ -136,6 +160,8 @@ int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes)
     const int rc = check_desc(desc);
     if (rc != CP_HEAD_OK) return rc;
     if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_DISTILL_BWD) return CP_HEAD_ERR_INVALID_ARG;
+    if ((op == CP_HEAD_OP_DISTILL_FWD || op == CP_HEAD_OP_DISTILL_BWD) && !distill_shape_supported(*desc))
+        return CP_HEAD_ERR_UNSUPPORTED;
     *bytes = workspace_need(*desc, op);
     return CP_HEAD_OK;
 }
@@ -278,6 +304,7 @@ int cp_head_distill_ctx_bytes(const cp_head_desc *desc, size_t *bytes)
     if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
     const int rc = check_desc(desc);
     if (rc != CP_HEAD_OK) return rc;
+    if (!distill_shape_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     *bytes = distill_ctx_bytes(*desc);
     return CP_HEAD_OK;
 }
@@ -292,6 +319,7 @@ int cp_head_distill_loss_fwd(const cp_head_desc *desc, const void *H, const void
     if (desc->T > 0 && (!H || !X || !TZ || !loss)) return CP_HEAD_ERR_INVALID_ARG;
     if (!(beta >= 0.f && beta <= 1.f) || !(discount >= 0.f)) return CP_HEAD_ERR_INVALID_ARG;
     if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!distill_shape_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DISTILL_FWD)) return CP_HEAD_ERR_WORKSPACE;
     return distill_loss_fwd(*desc, H, W, U, G, X, TZ, beta, discount, loss, ctx, workspace,
                             static_cast<hipStream_t>(stream));
@@ -307,6 +335,7 @@ int cp_head_distill_loss_bwd(const cp_head_desc *desc, const void *H, const void
     if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
     if (desc->T > 0 && (!H || !X || !TZ || !dH)) return CP_HEAD_ERR_INVALID_ARG;
     if (!ctx || !workspace || misaligned(ctx) || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!distill_shape_supported(*desc)) return CP_HEAD_ERR_UNSUPPORTED;
     if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_DISTILL_BWD)) return CP_HEAD_ERR_WORKSPACE;
     return distill_loss_bwd(*desc, H, W, U, G, X, TZ, dloss, scale, ctx, dH, dW, dU, dG, workspace,
                             static_cast<hipStream_t>(stream));

@@ -150,12 +150,13 @@ void launch_pick_alpha(const cp_head_desc &ds, const float *w, const float *unif
 // ---------------------------------------------------------------- optional per-kernel timing
 // While profiling is switched on (cp_head_profile_enable), a ProfileScope brackets a launch with a
 // pair of events on the launch stream and remembers the work it stands for.
-void profile_begin(const char *name, double work, hipStream_t st);
+bool profile_begin(const char *name, double work, hipStream_t st);   // whether a record was opened
 void profile_end(hipStream_t st);
 struct ProfileScope {
     hipStream_t st;
-    ProfileScope(const char *name, double work, hipStream_t s) : st(s) { profile_begin(name, work, s); }
-    ~ProfileScope() { profile_end(st); }
+    bool open;
+    ProfileScope(const char *name, double work, hipStream_t s) : st(s), open(profile_begin(name, work, s)) {}
+    ~ProfileScope() { if (open) profile_end(st); }
 };
 
 // ---------------------------------------------------------------- matrix-core path
@@ -198,6 +199,7 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *H, const void *F, con
 
 // ---------------------------------------------------------------- fine-tuning (distillation) loss
 // matrix-core path for bf16, d % 64 == 0, r in {1, 2, 4, 8}; the plain path otherwise
+bool distill_on_matrix_cores(const cp_head_desc &ds);   // the fine-tuning loss's own path selector
 size_t distill_ctx_bytes(const cp_head_desc &ds);
 size_t distill_workspace_bytes(const cp_head_desc &ds, int op);
 int distill_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,

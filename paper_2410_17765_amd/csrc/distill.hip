@@ -528,6 +528,9 @@ bool on_matrix_cores(const cp_head_desc &ds)
 {
     return use_fast_path(ds) && (ds.r == 1 || ds.r == 2 || ds.r == 4 || ds.r == 8);
 }
+}  // namespace
+bool distill_on_matrix_cores(const cp_head_desc &ds) { return on_matrix_cores(ds); }
+namespace {
 DistillCtx distill_ctx(const cp_head_desc &ds)
 {
     DistillCtx c;

@@ -2,6 +2,11 @@
 
 Only memory management lives here (torch tensors on ``cuda:0`` for inputs,
 outputs, ctx and workspace); every computation is a call through ``binding``.
+
+Every method launches on torch's current stream and allocates its buffers there, so the
+caching allocator's stream-ordered reuse of a released workspace is safe; to run on a side
+stream, call the methods under ``with torch.cuda.stream(side):``.  (The C ABI itself takes
+any stream; a caller that passes one to ``binding`` directly owns the lifetime of the buffers.)
 """
 from __future__ import annotations
 
@@ -61,19 +66,19 @@ class CpHead:
                                  binding.BF16 if self.dtype == "bf16" else binding.FP32, self.flags)
 
     # ------------------------------------------------------------------ loss
-    def loss_fwd(self, H: torch.Tensor, X: torch.Tensor, stream=None) -> torch.Tensor:
+    def loss_fwd(self, H: torch.Tensor, X: torch.Tensor) -> torch.Tensor:
         """H[T,d] (storage dtype), X[T,n] int32 on the device -> loss[T] fp32 (device).  Keeps ctx for loss_bwd."""
         T = H.shape[0]
         ds = self.desc(T)
         self._ctx = _scratch(binding.cp_head_ctx_bytes(ds), self.device)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD), self.device)
         loss = torch.empty(T, dtype=torch.float32, device=self.device)
-        binding.cp_head_loss_fwd(ds, H, self.W, self.U, self.G, X, loss, self._ctx, ws, stream)
+        binding.cp_head_loss_fwd(ds, H, self.W, self.U, self.G, X, loss, self._ctx, ws)
         self._desc = ds
         return loss
 
     def loss_bwd(self, H: torch.Tensor, X: torch.Tensor, dloss: Optional[torch.Tensor] = None, scale: float = 1.0,
-                 want_dU: bool = True, stream=None) -> Dict[str, torch.Tensor]:
+                 want_dU: bool = True) -> Dict[str, torch.Tensor]:
         assert self._ctx is not None, "call loss_fwd first"
         T = H.shape[0]
         ds = self.desc(T)
@@ -86,25 +91,23 @@ class CpHead:
             "dG": torch.empty((self.r, self.d), **f32),
         }
         binding.cp_head_loss_bwd(ds, H, self.W, self.U, self.G, X, dloss, scale, self._ctx,
-                                 out["dH"], out["dW"], out["dU"], out["dG"], ws, stream)
+                                 out["dH"], out["dW"], out["dU"], out["dG"], ws)
         return {k: v for k, v in out.items() if v is not None}
 
     # ------------------------------------------------------------------ fine-tuning (distillation) loss
     def distill_loss_fwd(self, H: torch.Tensor, X: torch.Tensor, TZ: torch.Tensor, beta: float = 0.9,
-                         discount: float = 1.0, stream=None) -> torch.Tensor:
+                         discount: float = 1.0) -> torch.Tensor:
         """TZ[T,n,V] teacher logits (storage dtype) -> loss[T] fp32.  Keeps ctx for distill_loss_bwd."""
         T = H.shape[0]
         ds = self.desc(T)
         self._dctx = _scratch(binding.cp_head_distill_ctx_bytes(ds), self.device)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DISTILL_FWD), self.device)
         loss = torch.empty(T, dtype=torch.float32, device=self.device)
-        binding.cp_head_distill_loss_fwd(ds, H, self.W, self.U, self.G, X, TZ, beta, discount, loss, self._dctx, ws,
-                                         stream)
+        binding.cp_head_distill_loss_fwd(ds, H, self.W, self.U, self.G, X, TZ, beta, discount, loss, self._dctx, ws)
         return loss
 
     def distill_loss_bwd(self, H: torch.Tensor, X: torch.Tensor, TZ: torch.Tensor,
-                         dloss: Optional[torch.Tensor] = None, scale: float = 1.0, want_dU: bool = False,
-                         stream=None) -> Dict[str, torch.Tensor]:
+                         dloss: Optional[torch.Tensor] = None, scale: float = 1.0, want_dU: bool = False) -> Dict[str, torch.Tensor]:
         T = H.shape[0]
         ds = self.desc(T)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DISTILL_BWD), self.device)
@@ -116,45 +119,45 @@ class CpHead:
             "dG": torch.empty((self.r, self.d), **f32),
         }
         binding.cp_head_distill_loss_bwd(ds, H, self.W, self.U, self.G, X, TZ, dloss, scale, self._dctx,
-                                         out["dH"], out["dW"], out["dU"], out["dG"], ws, stream)
+                                         out["dH"], out["dW"], out["dU"], out["dG"], ws)
         return {k: v for k, v in out.items() if v is not None}
 
     # ------------------------------------------------------------------ draft
-    def draft_sample(self, H: torch.Tensor, uniforms: torch.Tensor, stream=None):
+    def draft_sample(self, H: torch.Tensor, uniforms: torch.Tensor):
         B = H.shape[0]
         ds = self.desc(B)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT), self.device)
         alpha = torch.empty(B, dtype=torch.int32, device=self.device)
         tokens = torch.empty((B, self.n), dtype=torch.int32, device=self.device)
         logq = torch.empty(B, dtype=torch.float32, device=self.device)
-        binding.cp_head_draft_sample(ds, H, self.W, self.U, self.G, uniforms, alpha, tokens, logq, ws, stream)
+        binding.cp_head_draft_sample(ds, H, self.W, self.U, self.G, uniforms, alpha, tokens, logq, ws)
         return alpha, tokens, logq
 
     # ------------------------------------------------------------------ next-token distribution, paper-form sampler
-    def first_token_logprob(self, H: torch.Tensor, stream=None) -> torch.Tensor:
+    def first_token_logprob(self, H: torch.Tensor) -> torch.Tensor:
         B = H.shape[0]
         ds = self.desc(B)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_FIRST_TOKEN), self.device)
         logp = torch.empty((B, self.V), dtype=torch.float32, device=self.device)
-        binding.cp_head_first_token_logprob(ds, H, self.W, self.U, self.G, logp, ws, stream)
+        binding.cp_head_first_token_logprob(ds, H, self.W, self.U, self.G, logp, ws)
         return logp
 
-    def draft_sample_sequential(self, H: torch.Tensor, uniforms: torch.Tensor, stream=None):
+    def draft_sample_sequential(self, H: torch.Tensor, uniforms: torch.Tensor):
         B = H.shape[0]
         ds = self.desc(B)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_DRAFT_SEQUENTIAL), self.device)
         tokens = torch.empty((B, self.n), dtype=torch.int32, device=self.device)
         logq = torch.empty(B, dtype=torch.float32, device=self.device)
-        binding.cp_head_draft_sample_sequential(ds, H, self.W, self.U, self.G, uniforms, tokens, logq, ws, stream)
+        binding.cp_head_draft_sample_sequential(ds, H, self.W, self.U, self.G, uniforms, tokens, logq, ws)
         return tokens, logq
 
-    def aux_balance(self, H: torch.Tensor, stream=None):
+    def aux_balance(self, H: torch.Tensor):
         T = H.shape[0]
         ds = self.desc(T)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_AUX_BALANCE), self.device)
         counts = torch.empty(self.r, dtype=torch.int64, device=self.device)
         laux = torch.empty(1, dtype=torch.float32, device=self.device)
-        binding.cp_head_aux_balance(ds, H, self.G, counts, laux, ws, stream)
+        binding.cp_head_aux_balance(ds, H, self.G, counts, laux, ws)
         return counts, laux
 
 
@@ -174,17 +177,17 @@ class CpFullHead:
         return binding.make_desc(T, self.d, self.V, self.n, self.r,
                                  binding.BF16 if self.dtype == "bf16" else binding.FP32, self.flags)
 
-    def loss_fwd(self, H: torch.Tensor, X: torch.Tensor, stream=None) -> torch.Tensor:
+    def loss_fwd(self, H: torch.Tensor, X: torch.Tensor) -> torch.Tensor:
         T = H.shape[0]
         ds = self.desc(T)
         self._ctx = _scratch(binding.cp_head_full_ctx_bytes(ds), self.device)
         ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_FULL_LOSS_FWD), self.device)
         loss = torch.empty(T, dtype=torch.float32, device=self.device)
-        binding.cp_head_full_loss_fwd(ds, H, self.F, self.G, X, loss, self._ctx, ws, stream)
+        binding.cp_head_full_loss_fwd(ds, H, self.F, self.G, X, loss, self._ctx, ws)
         return loss
 
     def loss_bwd(self, H: torch.Tensor, X: torch.Tensor, dloss: Optional[torch.Tensor] = None, scale: float = 1.0,
-                 want_dF: bool = True, stream=None) -> Dict[str, torch.Tensor]:
+                 want_dF: bool = True) -> Dict[str, torch.Tensor]:
         assert self._ctx is not None, "call loss_fwd first"
         T = H.shape[0]
         ds = self.desc(T)
@@ -196,5 +199,5 @@ class CpFullHead:
             "dG": torch.empty((self.r, self.d), **f32),
         }
         binding.cp_head_full_loss_bwd(ds, H, self.F, self.G, X, dloss, scale, self._ctx,
-                                      out["dH"], out["dF"], out["dG"], ws, stream)
+                                      out["dH"], out["dF"], out["dG"], ws)
         return {k: v for k, v in out.items() if v is not None}

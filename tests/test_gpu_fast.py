@@ -103,7 +103,7 @@ def test_loss_and_gradients_random_shapes(gpu, oracle, cfg, flags):
 KEEP_LOGITS = 4      # CP_HEAD_KEEP_LOGITS: the backward pass reads the forward pass's logits instead of recomputing them
 
 
-@pytest.mark.parametrize("cfg,flags", [(c, f | KEEP_LOGITS) for c, f in CASES + random_shapes()],
+@pytest.mark.parametrize("cfg,flags", [(c, f | KEEP_LOGITS) for c, f in CASES + random_shapes()[:3]],
                          ids=lambda c: c.name if hasattr(c, "name") else str(c))
 def test_loss_and_gradients_with_kept_logits(gpu, oracle, cfg, flags):
     test_loss_and_gradients(gpu, oracle, cfg, flags)
@@ -193,6 +193,31 @@ def test_draft_sampling(gpu, oracle, cfg):
     assert stats["tokens_exact"] + stats["tie_draws"] + stats["band_draws"] == stats["tokens_total"]
     assert stats["tie_draws"] <= 2 and stats["tie_logq_rows"] <= 2
     assert stats["band_draws"] <= max(1, stats["tokens_total"] // 20)
+
+
+def test_draft_logq_against_the_loss_at_the_drawn_tokens(gpu, oracle):
+    """The two calls round differently (the loss takes its target logits from y kept to about fp32, logq from
+    bf16 y), so -logq and the loss at the drawn tokens agree to the rounding of n target logits, as the header
+    states: rms about 1.1e-3 sqrt(n), below 1e-2 at n = 4; the oracle shows the same gap between its two modes."""
+    import torch
+    cfg = synth.HeadConfig("draft_vs_loss", T=48, d=256, V=4000, n=4, r=4, targets="uniform")
+    inp = synth.make_inputs(cfg)
+    u = synth.uniforms(cfg.T, cfg.n)
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    H = gpu.to_device(inp["H"], cfg.dtype)
+    _, tokens, logq = h.draft_sample(H, torch.from_numpy(u).cuda())
+    loss = h.loss_fwd(H, tokens.contiguous())
+    torch.cuda.synchronize()
+    gap = (logq + loss).abs().cpu().numpy()
+    tok = tokens.cpu().numpy()
+    exact = oracle.loss_fwd(inp["H"], inp["W"], inp["U"], inp["G"], tok)
+    rounded = oracle.loss_fwd(inp["H"], inp["W"], inp["U"], inp["G"], tok, round_y=True)
+    print(f"  |logq + loss|: max {gap.max():.2e}, rms {np.sqrt((gap ** 2).mean()):.2e}; "
+          f"oracle, rounded against exact y: max {np.abs(rounded - exact).max():.2e}", flush=True)
+    assert gap.max() <= 1e-2
+    assert np.abs(loss.cpu().numpy() - exact).max() <= LOSS_ATOL
+    assert np.abs(-logq.cpu().numpy() - rounded).max() <= 1e-3
+    assert np.sqrt((gap ** 2).mean()) <= 2 * np.sqrt(((rounded - exact) ** 2).mean()) + 5e-4
 
 
 def random_draft_shapes(count=12, seed=20241018):

@@ -98,7 +98,7 @@ def test_loss_and_gradients_random_shapes(gpu, oracle, cfg, flags):
 KEEP_LOGITS = 4      # CP_HEAD_KEEP_LOGITS: the backward pass reads the forward pass's logits instead of recomputing them
 
 
-@pytest.mark.parametrize("cfg,flags", [(c, f | KEEP_LOGITS) for c, f in CASES + random_shapes()],
+@pytest.mark.parametrize("cfg,flags", [(c, f | KEEP_LOGITS) for c, f in CASES + random_shapes()[:3]],
                          ids=lambda c: c.name if hasattr(c, "name") else str(c))
 def test_loss_and_gradients_with_kept_logits(gpu, oracle, cfg, flags):
     """On the plain path (fp32 storage, or flag 1) the flag is ignored; on the matrix-core path it swaps the

@@ -3,11 +3,18 @@ default workspace, no materialised logits, dloss = NULL with scale = 1/T); the h
 runs with the logits kept in HBM for the backward pass, the variant bench.py reports beside it.
 
 The fp64 oracle cannot run a full configuration, so:
-* per-position outputs (loss, rows of dH) are compared on a seeded subset S of positions;
-* weight gradients are compared on a second GPU call with exactly the positions of S (T = |S|),
-  whose sums the oracle can form, and the full-T weight gradients are tied to that by
-  self-consistency on the GPU: the gradient of the full batch equals the sum of the gradients of
-  its two halves, and the zero-sum invariants of the softmax and gate gradients hold.
+* per-position outputs (loss, rows of dH) are compared on a subset S of positions: the first and the
+  last position, the positions on both sides of the first and of the last boundary between the
+  backward pass's chunks of head rows (for either chunk size the library may pick), and seeded random
+  ones;
+* weight gradients: the full-size backward launch (every tile, every chunk, the real contraction
+  lengths of the dW and dU products) is run with an upstream gradient that is non-zero on S only, so
+  its dW, dU and dG are exactly the sums over S, which the oracle forms directly; in the same call
+  the rows of dH outside S must be exactly zero;
+* a second GPU call with exactly the positions of S (T = |S|) is compared with the same sums, and the
+  gradient of the full batch with dloss = NULL is tied in by self-consistency on the GPU: it equals
+  the sum of the gradients of its two halves, and the zero-sum invariants of the softmax and gate
+  gradients hold.
 """
 import numpy as np
 import pytest
@@ -18,6 +25,19 @@ from tests.helpers import GRAD_REL_FRO, LOSS_ATOL, rel_fro
 pytestmark = pytest.mark.gpu
 
 SUBSET = 8
+
+
+def sampled_positions(cfg):
+    """SUBSET positions: first, last, both sides of the first and last multiple of the backward chunk (32768 or
+    65536 head rows, whichever the library uses at this vocabulary; a position may straddle it), random fill."""
+    nr = cfg.n * cfg.r
+    rows = 65536 if cfg.V <= 32768 else 32768
+    M = cfg.T * nr
+    first, last = rows // nr, ((M - 1) // rows) * rows // nr
+    fixed = [0, cfg.T - 1, first - 1, first, last - 1, last]
+    fixed = sorted({p for p in fixed if 0 <= p < cfg.T})
+    extra = [int(p) for p in synth.position_subset(cfg.T, SUBSET) if int(p) not in fixed]
+    return np.array(sorted(fixed + extra[:max(0, SUBSET - len(fixed))]), dtype=np.int64)
 
 
 class FullRun:
@@ -39,7 +59,7 @@ class FullRun:
         self.loss = self.head.loss_fwd(self.H, self.X)
         self.grads = self.head.loss_bwd(self.H, self.X, None, scale=self.scale)
         torch.cuda.synchronize()
-        self.sel = synth.position_subset(cfg.T, SUBSET)
+        self.sel = sampled_positions(cfg)
 
     def run_rows(self, lo, hi):
         H, X = self.H[lo:hi].contiguous(), self.X[lo:hi].contiguous()
@@ -91,14 +111,31 @@ def test_gradients_on_sampled_positions(oracle, run):
     if ("bwd", name) not in _ORACLE:
         _ORACLE[("bwd", name)] = oracle.loss_bwd(inp["H"][sel], inp["W"], inp["U"], inp["G"], inp["X"][sel], dloss)
     ref = _ORACLE[("bwd", name)]
+    import torch
+    from paper_2410_17765_amd import head
+    sel_dev = run.torch.from_numpy(sel).cuda()
     # rows of dH are per-position: compare the full run's rows directly
-    got_dH = run.grads["dH"][run.torch.from_numpy(sel).cuda()].cpu().numpy()
+    got_dH = run.grads["dH"][sel_dev].cpu().numpy()
     e = rel_fro(got_dH, ref["dH"])
     print(f"  dH rows rel fro {e:.3e}", flush=True)
     assert e <= GRAD_REL_FRO
-    # weight gradients: a GPU call on exactly these positions
-    import torch
-    from paper_2410_17765_amd import head
+    # weight gradients from the full-size launch: upstream gradient on S only (the forward pass's ctx is still the
+    # full batch's), so dW, dU, dG are the sums over S
+    dl = torch.zeros(cfg.T, dtype=torch.float32, device="cuda")
+    dl[sel_dev] = run.scale
+    g = run.head.loss_bwd(run.H, run.X, dl, scale=1.0)
+    torch.cuda.synchronize()
+    for k in ("dW", "dU", "dG"):
+        e = rel_fro(g[k].cpu().numpy(), ref[k])
+        print(f"  full-size launch, upstream gradient on S only: {k} rel fro {e:.3e}", flush=True)
+        assert e <= GRAD_REL_FRO, k
+    e = rel_fro(g["dH"][sel_dev].cpu().numpy(), ref["dH"])
+    assert e <= GRAD_REL_FRO
+    others = torch.ones(cfg.T, dtype=torch.bool, device="cuda")
+    others[sel_dev] = False
+    assert float(g["dH"][others].abs().max()) == 0.0, "positions with zero upstream gradient"
+    del g, dl, others
+    # and a GPU call on exactly these positions
     Hs = head.to_device(inp["H"][sel], cfg.dtype)
     Xs = torch.from_numpy(inp["X"][sel]).cuda()
     run.head.loss_fwd(Hs, Xs)

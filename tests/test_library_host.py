@@ -230,3 +230,24 @@ def test_bench_defaults_and_roofline_constants():
         sys.argv = argv
     assert args.gpus == 1 and args.steps >= 10 and args.warmup >= 3 and args.workload == "head_7b"
     assert bench.PEAK_BF16_TFLOPS == 2500.0                      # dense bf16 matrix peak of the MI355X
+
+
+def test_fine_tuning_loss_applies_the_plain_paths_limit_by_its_own_path_choice(lib):
+    """Ranks other than 1, 2, 4, 8 send the fine-tuning loss to the plain path even at shapes where the training
+    loss runs on the matrix cores, so a hidden size beyond the plain path's limit must be refused up front
+    (size queries and calls alike), not after some kernels have been enqueued."""
+    wide = binding.make_desc(64, 16384, 1000, 2, 3, binding.BF16)
+    assert binding.cp_head_workspace_bytes(wide, binding.OP_LOSS_FWD) > 0          # training loss: matrix cores
+    for query in (lambda: binding.cp_head_distill_ctx_bytes(wide),
+                  lambda: binding.cp_head_workspace_bytes(wide, binding.OP_DISTILL_FWD),
+                  lambda: binding.cp_head_workspace_bytes(wide, binding.OP_DISTILL_BWD)):
+        with pytest.raises(binding.CpHeadError) as err:
+            query()
+        assert err.value.code == -2
+    fine = binding.make_desc(64, 16384, 1000, 2, 4, binding.BF16)                  # rank 4: matrix cores
+    assert binding.cp_head_distill_ctx_bytes(fine) > 0
+    assert binding.cp_head_workspace_bytes(fine, binding.OP_DISTILL_BWD) > 0
+    # the calls themselves refuse before looking at any pointer that would be dereferenced
+    rc = lib.cp_head_distill_loss_fwd(ctypes.byref(wide), 256, 256, 256, 256, 256, 256, 0.5, 1.0, 256, 256, 256,
+                                      1 << 40, None)
+    assert rc == -2
