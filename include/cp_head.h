@@ -74,7 +74,9 @@ enum {
     CP_HEAD_ERR_INVALID_ARG = -1,     /* null pointer, bad dimension, misaligned buffer */
     CP_HEAD_ERR_UNSUPPORTED = -2,     /* shape or dtype outside the stated limits */
     CP_HEAD_ERR_WORKSPACE = -3,       /* workspace_bytes smaller than the query reports */
-    CP_HEAD_ERR_LAUNCH = -4           /* a kernel launch failed (hipGetLastError) */
+    CP_HEAD_ERR_LAUNCH = -4,          /* a kernel launch failed (hipGetLastError) */
+    CP_HEAD_ERR_STATIC_SCRATCH = -5   /* cp_head_draft_sample_static: the shape needs more scratch than
+                                         CP_HEAD_STATIC_SCRATCH_BYTES */
 };
 
 enum {
@@ -172,6 +174,26 @@ int cp_head_draft_sample(const cp_head_desc *desc,
                          const float *uniforms,
                          int32_t *alpha, int32_t *tokens, float *logq,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same draft step for callers that cannot hand over or allocate a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  The scratch memory the kernels need
+ * lives in a static device array inside the library, CP_HEAD_STATIC_SCRATCH_BYTES per GPU, held until
+ * the process ends; the call allocates nothing (no device, host or library allocation; leave the
+ * timing hook below switched off, which creates events).  Arguments and results are those of
+ * cp_head_draft_sample, bit for bit.  A shape whose cp_head_workspace_bytes(desc, CP_HEAD_OP_DRAFT)
+ * exceeds CP_HEAD_STATIC_SCRATCH_BYTES is refused with CP_HEAD_ERR_STATIC_SCRATCH and nothing is
+ * enqueued (48 MiB holds B = 64 rows at d = 4096, V = 128256, n = 4, r = 8).  The first call on a
+ * device looks up that device's copy of the array (make it outside any graph capture); all calls on
+ * one GPU share the array, so calls that overlap on one GPU (different streams or threads) race:
+ * serialise them.  Nothing in the array has to start at zero and nothing is kept between calls.
+ */
+#define CP_HEAD_STATIC_SCRATCH_BYTES ((size_t)48 << 20)
+int cp_head_draft_sample_static(const cp_head_desc *desc,
+                                const void *H, const void *W, const void *U, const void *G,
+                                const float *uniforms,
+                                int32_t *alpha, int32_t *tokens, float *logq,
+                                void *stream);
 
 /*
  * First-token marginal (eq. 11), in log space, for each of the B = desc->T rows of H:

@@ -26,7 +26,7 @@ LIB_PATH = os.path.join(_PKG, "libcphead.so")
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("cp_head_strerror", "cp_head_ctx_bytes", "cp_head_workspace_bytes",
-           "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample",
+           "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample", "cp_head_draft_sample_static",
            "cp_head_first_token_logprob", "cp_head_draft_sample_sequential", "cp_head_aux_balance",
            "cp_head_full_ctx_bytes", "cp_head_full_loss_fwd", "cp_head_full_loss_bwd",
            "cp_head_distill_ctx_bytes", "cp_head_distill_loss_fwd", "cp_head_distill_loss_bwd",
@@ -66,6 +66,7 @@ def lib() -> ctypes.CDLL:
         L.cp_head_loss_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, ctypes.c_float, vp,
                                        vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_draft_sample.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_draft_sample_static.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.cp_head_first_token_logprob.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_draft_sample_sequential.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_aux_balance.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, sz, vp]
@@ -153,6 +154,18 @@ def cp_head_draft_sample(desc: Desc, H, W, U, G, uniforms, alpha, tokens, logq, 
                                     _stream(stream))
     if rc != 0:
         raise CpHeadError(rc, "cp_head_draft_sample")
+
+
+STATIC_SCRATCH_BYTES = 48 << 20
+ERR_STATIC_SCRATCH = -5
+
+
+def cp_head_draft_sample_static(desc: Desc, H, W, U, G, uniforms, alpha, tokens, logq, stream=None) -> None:
+    """The draft step on the library's own static scratch array: no workspace argument, no allocation."""
+    rc = lib().cp_head_draft_sample_static(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(uniforms),
+                                           _ptr(alpha), _ptr(tokens), _ptr(logq), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_draft_sample_static")
 
 
 def cp_head_first_token_logprob(desc: Desc, H, W, U, G, logp, workspace, stream=None) -> None:

@@ -93,6 +93,34 @@ size_t workspace_need(const cp_head_desc &ds, int op)
 }
 
 
+// ---------------------------------------------------------------- scratch for callers that cannot allocate
+// One array per GPU (every device that loads the code object holds its own copy at its own address), used by
+// cp_head_draft_sample_static in place of a caller's workspace.  In host code the array's name is only a handle for
+// the symbol lookup: the device address is resolved once per device, with that device current, and kept; kernels
+// and every other use take that pointer.
+constexpr size_t kStaticScratchBytes = CP_HEAD_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[CP_HEAD_STATIC_SCRATCH_BYTES];
+namespace {
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int static_scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CP_HEAD_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CP_HEAD_ERR_LAUNCH;
+        if (reinterpret_cast<uintptr_t>(ptr) & 255u) return CP_HEAD_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CP_HEAD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -105,6 +133,7 @@ const char *cp_head_strerror(int code)
     case CP_HEAD_ERR_UNSUPPORTED: return "unsupported shape or storage type";
     case CP_HEAD_ERR_WORKSPACE: return "workspace too small";
     case CP_HEAD_ERR_LAUNCH: return "kernel launch failed";
+    case CP_HEAD_ERR_STATIC_SCRATCH: return "shape needs more scratch than the library's static buffer holds";
     default: return "unknown error code";
     }
 }
@@ -218,6 +247,25 @@ int cp_head_draft_sample(const cp_head_desc *desc, const void *H, const void *W,
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (fast) return fast_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, workspace_bytes, st);
     return generic_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, st);
+}
+
+int cp_head_draft_sample_static(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                                const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !uniforms || !alpha || !tokens)) return CP_HEAD_ERR_INVALID_ARG;
+    const bool fast = use_fast_path(*desc);
+    const size_t need = fast ? fast_workspace_bytes(*desc, CP_HEAD_OP_DRAFT)
+                             : generic_workspace_bytes(*desc, CP_HEAD_OP_DRAFT);
+    if (need > kStaticScratchBytes) return CP_HEAD_ERR_STATIC_SCRATCH;
+    void *ws = nullptr;
+    rc = static_scratch_of_current_device(&ws);
+    if (rc != CP_HEAD_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (fast) return fast_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, ws, kStaticScratchBytes, st);
+    return generic_draft(*desc, H, W, U, G, uniforms, alpha, tokens, logq, ws, st);
 }
 
 int cp_head_first_token_logprob(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
