@@ -83,7 +83,8 @@ enum {
     CP_HEAD_OP_LOSS_FWD = 0, CP_HEAD_OP_LOSS_BWD = 1, CP_HEAD_OP_DRAFT = 2,
     CP_HEAD_OP_FIRST_TOKEN = 3, CP_HEAD_OP_DRAFT_SEQUENTIAL = 4, CP_HEAD_OP_AUX_BALANCE = 5,
     CP_HEAD_OP_FULL_LOSS_FWD = 6, CP_HEAD_OP_FULL_LOSS_BWD = 7,
-    CP_HEAD_OP_DISTILL_FWD = 8, CP_HEAD_OP_DISTILL_BWD = 9
+    CP_HEAD_OP_DISTILL_FWD = 8, CP_HEAD_OP_DISTILL_BWD = 9,
+    CP_HEAD_OP_LOSS_FWD_BWD = 10
 };
 
 typedef struct cp_head_desc {
@@ -152,6 +153,28 @@ int cp_head_loss_bwd(const cp_head_desc *desc,
                      const void *ctx,
                      float *dH, float *dW, float *dU, float *dG,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Training loss and its gradients in one call (section "Training procedure", eq. 9 and its derivative), for
+ * training loops in which the loss is the last node of the graph, so that the upstream gradient is known
+ * before the forward pass: dloss[T] / scale as in cp_head_loss_bwd.  loss[T] and the gradients are exactly
+ * what cp_head_loss_fwd followed by cp_head_loss_bwd return (same kernels, same arithmetic); no ctx is needed,
+ * the workspace is sized by cp_head_workspace_bytes with CP_HEAD_OP_LOSS_FWD_BWD.
+ * What the single call buys on the matrix-core path: forward and backward are interleaved per chunk of
+ * positions, and the logits of a chunk are kept as 16-bit floats from the product that forms their statistics to
+ * the pass that turns them into gradients a few launches later.  U y is therefore multiplied once per step
+ * instead of twice, as with CP_HEAD_KEEP_LOGITS, but the kept logits are those of one chunk only: at most 4 GiB
+ * (8 GiB for vocabularies whose 32768 rows need more), however many positions the batch has.  The logits do
+ * reach HBM in this call, one bounded chunk at a time; the pair of calls above with flags = 0 never stores one.
+ * dU, dW, dG may be NULL as in cp_head_loss_bwd; loss and dH are required.  CP_HEAD_KEEP_LOGITS is ignored.
+ */
+int cp_head_loss_fwd_bwd(const cp_head_desc *desc,
+                         const void *H, const void *W, const void *U, const void *G,
+                         const int32_t *X,
+                         const float *dloss, float scale,
+                         float *loss,
+                         float *dH, float *dW, float *dU, float *dG,
+                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Draft step for self-speculative decoding (section "Sampling method"): for

@@ -20,13 +20,15 @@ OP_LOSS_FWD, OP_LOSS_BWD, OP_DRAFT = 0, 1, 2
 OP_FIRST_TOKEN, OP_DRAFT_SEQUENTIAL, OP_AUX_BALANCE = 3, 4, 5
 OP_FULL_LOSS_FWD, OP_FULL_LOSS_BWD = 6, 7
 OP_DISTILL_FWD, OP_DISTILL_BWD = 8, 9
+OP_LOSS_FWD_BWD = 10
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcphead.so")
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("cp_head_strerror", "cp_head_ctx_bytes", "cp_head_workspace_bytes",
-           "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_draft_sample", "cp_head_draft_sample_static",
+           "cp_head_loss_fwd", "cp_head_loss_bwd", "cp_head_loss_fwd_bwd", "cp_head_draft_sample",
+           "cp_head_draft_sample_static",
            "cp_head_first_token_logprob", "cp_head_draft_sample_sequential", "cp_head_aux_balance",
            "cp_head_full_ctx_bytes", "cp_head_full_loss_fwd", "cp_head_full_loss_bwd",
            "cp_head_distill_ctx_bytes", "cp_head_distill_loss_fwd", "cp_head_distill_loss_bwd",
@@ -65,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.cp_head_loss_fwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_loss_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, ctypes.c_float, vp,
                                        vp, vp, vp, vp, vp, sz, vp]
+        L.cp_head_loss_fwd_bwd.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, ctypes.c_float, vp,
+                                           vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_draft_sample.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_head_draft_sample_static.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.cp_head_first_token_logprob.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, sz, vp]
@@ -146,6 +150,14 @@ def cp_head_loss_bwd(desc: Desc, H, W, U, G, X, dloss, scale: float, ctx, dH, dW
                                 _ptr(workspace), _nbytes(workspace), _stream(stream))
     if rc != 0:
         raise CpHeadError(rc, "cp_head_loss_bwd")
+
+
+def cp_head_loss_fwd_bwd(desc: Desc, H, W, U, G, X, dloss, scale, loss, dH, dW, dU, dG, workspace, stream=None) -> None:
+    rc = lib().cp_head_loss_fwd_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(U), _ptr(G), _ptr(X), _ptr(dloss),
+                                    float(scale), _ptr(loss), _ptr(dH), _ptr(dW), _ptr(dU), _ptr(dG),
+                                    _ptr(workspace), _nbytes(workspace), _stream(stream))
+    if rc != 0:
+        raise CpHeadError(rc, "cp_head_loss_fwd_bwd")
 
 
 def cp_head_draft_sample(desc: Desc, H, W, U, G, uniforms, alpha, tokens, logq, workspace, stream=None) -> None:

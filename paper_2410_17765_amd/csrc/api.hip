@@ -79,8 +79,18 @@ bool distill_shape_supported(const cp_head_desc &ds)
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) != 0; }
 
+// The single-call training step on the plain path is the forward call followed by the backward call, with the
+// saved-for-backward buffer carved out of the workspace.
+size_t plain_step_ctx_bytes(const cp_head_desc &ds) { return (ctx_layout(ds, false).total + 255) / 256 * 256; }
+size_t plain_step_workspace_bytes(const cp_head_desc &ds)
+{
+    const size_t f = generic_workspace_bytes(ds, CP_HEAD_OP_LOSS_FWD), b = generic_workspace_bytes(ds, CP_HEAD_OP_LOSS_BWD);
+    return plain_step_ctx_bytes(ds) + (f > b ? f : b);
+}
+
 size_t workspace_need(const cp_head_desc &ds, int op)
 {
+    if (op == CP_HEAD_OP_LOSS_FWD_BWD) return use_fast_path(ds) ? fast_step_workspace_bytes(ds) : plain_step_workspace_bytes(ds);
     if (op == CP_HEAD_OP_AUX_BALANCE) return 256;   // none needed; a token size keeps the calling pattern uniform
     if (op == CP_HEAD_OP_FULL_LOSS_FWD || op == CP_HEAD_OP_FULL_LOSS_BWD)
         return use_fast_path(ds) ? fast_workspace_bytes(ds, op) : generic_full_workspace_bytes(ds);
@@ -188,7 +198,7 @@ int cp_head_workspace_bytes(const cp_head_desc *desc, int op, size_t *bytes)
     if (!bytes) return CP_HEAD_ERR_INVALID_ARG;
     const int rc = check_desc(desc);
     if (rc != CP_HEAD_OK) return rc;
-    if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_DISTILL_BWD) return CP_HEAD_ERR_INVALID_ARG;
+    if (op < CP_HEAD_OP_LOSS_FWD || op > CP_HEAD_OP_LOSS_FWD_BWD) return CP_HEAD_ERR_INVALID_ARG;
     if ((op == CP_HEAD_OP_DISTILL_FWD || op == CP_HEAD_OP_DISTILL_BWD) && !distill_shape_supported(*desc))
         return CP_HEAD_ERR_UNSUPPORTED;
     *bytes = workspace_need(*desc, op);
@@ -229,6 +239,25 @@ int cp_head_loss_bwd(const cp_head_desc *desc, const void *H, const void *W, con
     if (fast)
         return fast_loss_bwd(*desc, H, W, U, G, X, dloss, scale, ctx, dH, dW, dU, dG, workspace, workspace_bytes, st);
     return generic_loss_bwd(*desc, H, W, U, G, X, dloss, scale, ctx, dH, dW, dU, dG, workspace, st);
+}
+
+int cp_head_loss_fwd_bwd(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,
+                         const int32_t *X, const float *dloss, float scale, float *loss, float *dH, float *dW, float *dU,
+                         float *dG, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != CP_HEAD_OK) return rc;
+    if (!W || !U || !G) return CP_HEAD_ERR_INVALID_ARG;
+    if (desc->T > 0 && (!H || !X || !loss || !dH)) return CP_HEAD_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace)) return CP_HEAD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_need(*desc, CP_HEAD_OP_LOSS_FWD_BWD)) return CP_HEAD_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (use_fast_path(*desc)) return fast_loss_step(*desc, H, W, U, G, X, dloss, scale, loss, dH, dW, dU, dG, workspace, st);
+    void *ctx = workspace;
+    void *ws = static_cast<char *>(workspace) + plain_step_ctx_bytes(*desc);
+    rc = generic_loss_fwd(*desc, H, W, U, G, X, loss, ctx, ws, st);
+    if (rc != CP_HEAD_OK) return rc;
+    return generic_loss_bwd(*desc, H, W, U, G, X, dloss, scale, ctx, dH, dW, dU, dG, ws, st);
 }
 
 int cp_head_draft_sample(const cp_head_desc *desc, const void *H, const void *W, const void *U, const void *G,

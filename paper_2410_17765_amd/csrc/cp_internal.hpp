@@ -166,6 +166,10 @@ int fast_loss_fwd(const cp_head_desc &ds, const void *H, const void *W, const vo
 int fast_loss_bwd(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                   const int32_t *X, const float *dloss, float scale, const void *ctx,
                   float *dH, float *dW, float *dU, float *dG, void *ws, size_t ws_bytes, hipStream_t st);
+size_t fast_step_workspace_bytes(const cp_head_desc &ds);
+int fast_loss_step(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
+                   const int32_t *X, const float *dloss, float scale, float *loss, float *dH, float *dW, float *dU,
+                   float *dG, void *ws, hipStream_t st);
 int fast_draft(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, size_t ws_bytes,
                hipStream_t st);

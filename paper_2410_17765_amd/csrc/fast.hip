@@ -18,6 +18,9 @@ namespace cph {
 namespace {
 
 typedef TileCfg<256, 256, 2, 2> Cfg;
+// the same tile with the second, or both, operands K-major (the contraction index is their slow one)
+typedef TileCfg<256, 256, 2, 2, false, true> CfgNN;
+typedef TileCfg<256, 256, 2, 2, true, true> CfgTN;
 constexpr int kBlock = 256;
 
 
@@ -424,17 +427,16 @@ __device__ __forceinline__ float wave_dot_bf16(const bf16_t *__restrict__ a, con
 }
 
 // gate (eq. 7) and the expert draw: log w = log_softmax(G h); a* = first a whose running sum of w
-// (fp64) exceeds u, clamped to r-1.  One block per row of the batch, one wavefront per expert.
+// (fp64) exceeds u, clamped to r-1.  One block per row of the batch, a wavefront per expert at a time.
+// g_s: at least r floats of LDS.  uniforms = null: log w only.
 constexpr int kWideBlock = 1024;
-__global__ void __launch_bounds__(kWideBlock) k_draft_gate_pick(int d, int n, int r, const bf16_t *__restrict__ H,
-                                                                const bf16_t *__restrict__ G,
-                                                                const float *__restrict__ uniforms,
-                                                                float *__restrict__ logw, int32_t *__restrict__ alpha)
+__device__ __forceinline__ void draft_gate_pick_row(size_t b, int nwaves, float *g_s, int d, int n, int r,
+                                                    const bf16_t *__restrict__ H, const bf16_t *__restrict__ G,
+                                                    const float *__restrict__ uniforms, float *__restrict__ logw,
+                                                    int32_t *__restrict__ alpha)
 {
-    __shared__ float g_s[kWave];
-    const size_t b = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int a = wave; a < r; a += kWideBlock / kWave) {
+    for (int a = wave; a < r; a += nwaves) {
         const float p = wave_dot_bf16(G + (size_t)a * d, H + b * d, d, lane);
         if (lane == 0) g_s[a] = p;
     }
@@ -453,6 +455,23 @@ __global__ void __launch_bounds__(kWideBlock) k_draft_gate_pick(int d, int n, in
     const unsigned long long crossed = __ballot(lane < r && incl > u);
     if (lane == 0) alpha[b] = crossed ? __ffsll((long long)crossed) - 1 : r - 1;
 }
+// It runs as a side job of the y product's launch (the two are independent: both read only H and weights), which
+// saves the draft-type calls a launch: workgroup `job` of the first `blocks` (B rounded up to 8) takes row `job`.
+struct GatePickSide {
+    static constexpr bool kActive = true;
+    int blocks;
+    int B, d, n, r;
+    const bf16_t *H, *G;
+    const float *uniforms;
+    float *logw;
+    int32_t *alpha;
+    __device__ void run(int job, char *smem) const
+    {
+        if (job >= B) return;
+        draft_gate_pick_row((size_t)job, (int)(blockDim.x / kWave), reinterpret_cast<float *>(smem), d, n, r, H, G,
+                            uniforms, logw, alpha);
+    }
+};
 
 // Per (b, s): the log-normalisers of its r head rows from the per-segment statistics (eq. 5), then for
 // the drawn expert's row the segment of the vocabulary in which the running sum of probabilities
@@ -1041,19 +1060,18 @@ inline size_t bwd_chunk_rows(const cp_head_desc &ds)
 }
 
 struct BwdWs {
-    size_t coef, dg, dGpart, Ut, Wt, Ht, dY, dYt, dZ, dZt, Yt, total;
-    size_t Vp, Tp, chunk, chunk_p;
-    size_t ldV, ldT, ldM, ldN;   // leading dimensions of the transposed operands (K padded to 64, plus 64)
+    size_t coef, dg, dGpart, Ut, Wt, dY, dZ, dZt, Yt, total;
+    size_t Vp, chunk, chunk_p;
+    size_t ldV, ldM, ldN;   // leading dimensions of the transposed operands (K padded to 64, plus 64)
 };
 inline BwdWs bwd_ws(const cp_head_desc &ds)
 {
     BwdWs b;
     const size_t T = (size_t)ds.T, nrd = (size_t)ds.n * ds.r * ds.d, M = T * ds.n * ds.r;
     b.Vp = round_up((size_t)ds.V, 64);
-    b.Tp = round_up(T, 64);
     b.chunk = bwd_chunk_rows(ds);
     b.chunk_p = round_up(b.chunk, 64);
-    b.ldV = b.Vp + 64; b.ldT = b.Tp + 64; b.ldM = b.chunk_p + 64; b.ldN = nrd + 64;
+    b.ldV = b.Vp + 64; b.ldM = b.chunk_p + 64; b.ldN = nrd + 64;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     b.coef = take(M * 16);
@@ -1061,9 +1079,7 @@ inline BwdWs bwd_ws(const cp_head_desc &ds)
     b.dGpart = take(((T + kGateChunk - 1) / kGateChunk) * ds.r * ds.d * 4);
     b.Ut = take((size_t)ds.d * b.ldV * 2);
     b.Wt = take((size_t)ds.d * b.ldN * 2);
-    b.Ht = take((size_t)ds.d * b.ldT * 2);
     b.dY = take(M * ds.d * 2);
-    b.dYt = take(nrd * b.ldT * 2);
     b.dZ = take(b.chunk * b.Vp * 2);
     b.dZt = take((size_t)ds.V * b.ldM * 2);
     b.Yt = take((size_t)ds.d * b.ldM * 2);
@@ -1129,9 +1145,9 @@ inline size_t full_chunk_rows(const cp_head_desc &ds)
 }
 
 struct FullBwdWs {
-    size_t coef, dg, dGpart, Ft, Ht, dZ, dZt, total;
+    size_t coef, dg, dGpart, Ht, dZ, dZt, total;
     size_t Vp, Tp, chunk, chunk_p;
-    size_t ldV, ldT, ldM;
+    size_t ldT, ldM;
 };
 inline FullBwdWs full_bwd_ws(const cp_head_desc &ds)
 {
@@ -1141,13 +1157,12 @@ inline FullBwdWs full_bwd_ws(const cp_head_desc &ds)
     b.Tp = round_up(T, 64);
     b.chunk = full_chunk_rows(ds);
     b.chunk_p = round_up(b.chunk, 64);
-    b.ldV = b.Vp + 64; b.ldT = b.Tp + 64; b.ldM = b.chunk_p + 64;
+    b.ldT = b.Tp + 64; b.ldM = b.chunk_p + 64;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     b.coef = take(M * 16);
     b.dg = take(T * ds.r * 4);
     b.dGpart = take(((T + kGateChunk - 1) / kGateChunk) * ds.r * ds.d * 4);
-    b.Ft = take((size_t)ds.d * b.ldV * 2);
     b.Ht = take((size_t)ds.d * b.ldT * 2);
     b.dZ = take(b.chunk * b.Vp * 2);
     b.dZt = take((size_t)ds.V * b.ldM * 2);
@@ -1169,6 +1184,42 @@ inline bool dims_fit(const cp_head_desc &ds)
 // rows of a 64-row tile: the draft GEMMs with at most this many rows stream their big operand with
 // two 80 KB workgroups per compute unit instead of one 128 KB workgroup
 typedef TileCfg<64, 256, 1, 4> CfgSkinny;
+// rows up to which the z product of a draft-type call uses the 64-row tile (several tile rows then share the
+// slices of U through L2: their workgroups are neighbours in the tile walk)
+#ifndef CPH_SKINNY_ROWS
+#define CPH_SKINNY_ROWS 64
+#endif
+constexpr int kSkinnyRows = CPH_SKINNY_ROWS;
+// z = U y for the few rows of a draft-type call: picks the tile by the number of rows
+template <class Epi>
+inline void launch_z_streamed(const char *name, const bf16_t *Y, int d, int rows, const bf16_t *U, int V, const Epi &epi,
+                              hipStream_t st)
+{
+    if (rows <= kSkinnyRows) launch_gemm_nt<CfgSkinny>(name, Y, d, rows, U, d, V, d, epi, st, kSkinnyRows / CfgSkinny::BM);
+    else launch_gemm_nt<Cfg>(name, Y, d, rows, U, d, V, d, epi, st);
+}
+// y = W_sa h for the first `heads` of the n r head matrices (bf16, rounded: part of the draft distribution's
+// definition), with the gate (and the expert draw, if uniforms is given) as the launch's side job
+inline void launch_y_with_gate(const char *name, const cp_head_desc &ds, const bf16_t *H, const bf16_t *W, const bf16_t *G,
+                               const float *uniforms, bf16_t *Y, float *logw, int32_t *alpha, int heads, hipStream_t st)
+{
+    const int B = (int)ds.T, d = ds.d, cols = heads * d;
+    const GatePickSide side{(B + 7) / 8 * 8, B, d, ds.n, ds.r, H, G, uniforms, logw, alpha};
+    const EpiStoreBf16 epi{Y, nullptr, (long)cols, B, cols};
+    if (B <= CfgSkinny::BM) launch_gemm_nt<CfgSkinny>(name, H, d, B, W, d, cols, d, epi, st, kGroupRowsWide, side);
+    else launch_gemm_nt<Cfg>(name, H, d, B, W, d, cols, d, epi, st, kGroupRowsWide, side);
+}
+// statistics segments (pairs per row, columns per segment) of that choice
+inline void z_segments(int rows, int V, int &parts, int &seg_cols)
+{
+    if (rows <= kSkinnyRows) {
+        parts = ((V + CfgSkinny::BN - 1) / CfgSkinny::BN) * CfgSkinny::WN;
+        seg_cols = CfgSkinny::WTN;
+    } else {
+        parts = ((V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+        seg_cols = Cfg::WTN;
+    }
+}
 
 struct DraftWs {
     size_t logw, Y, part, lse, seg, base, total;
@@ -1265,26 +1316,76 @@ int fast_loss_fwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
 }
 
+// Which operand layout each product of the backward pass uses.  The main loop reads a K-major operand (the
+// contraction index is its slow one) with gfx950's transposing LDS read, which needs no transposed copy of anything
+// but costs the loop 4-5 % per K-major operand (two 64-bit reads per fragment instead of one 128-bit read: twice the
+// LDS instructions and LDS busy time for the same bytes; measured at the headline size: dY 97.3 -> 101.2 ms per step
+// with U K-major, dU 99.6 -> 109.9 with dz and Y K-major, dH 12.5 -> 13.0, dW 12.7 -> 13.7).  A transposed copy is
+// an HBM-bound pass that costs less than that wherever the product is vocabulary-sized (dz^T from the dz epilogue 5.3
+// ms per step, Y^T 2.7, U^T 0.1, W^T 0.5), so those products keep the K-contiguous form; dW = dY^T H is the one
+// whose transposed copies (4.3 GB of dY: 1.8 ms) cost more than its K-major loop (1.0 ms), and they were 4.3 GB of
+// workspace.
+
+// The backward pass below dY: dH = dY W + G^T dg, dW = dY^T H, dG = dg^T H.  Wt: scratch for W^T [d, n r d + 64];
+// dGpart: the partial sums of the two-stage gate gradient.
+static int bwd_below_dy(const cp_head_desc &ds, const bf16_t *H, const bf16_t *W, const bf16_t *G, const bf16_t *dY,
+                        const float *dg, float *dH, float *dW, float *dG, bf16_t *Wt, float *dGpart, hipStream_t st)
+{
+    const int d = ds.d, r = ds.r;
+    const size_t T = (size_t)ds.T, nrd = (size_t)ds.n * r * d;
+    const long ldN = (long)nrd + 64;
+    // dH = dY W + G^T dg   (contraction over (s, a, k))
+    transpose_bf16(W, d, (int)nrd, d, Wt, ldN, (int)nrd, st);         // Wt[d, nrd]
+    launch_gemm_nt<Cfg>("gemm_dh", dY, (long)nrd, (int)T, Wt, ldN, d, (int)nrd, EpiStoreF32{dH, (long)d, (int)T, d, 0}, st,
+                        kGroupRowsNarrow);
+    k_add_gate_to_dh<<<blocks_for(T * d, kBlock), kBlock, 0, st>>>(T, d, r, G, dg, dH);
+    if (dW)
+        // dW_sa = dY_sa^T H   (contraction over positions: both operands K-major, any number of positions)
+        launch_gemm_nt<CfgTN>("gemm_dw", dY, (long)nrd, (int)nrd, H, d, d, (int)T, EpiStoreF32{dW, (long)d, (int)nrd, d, 0}, st,
+                              kGroupRowsNarrow);
+    if (dG) {
+        const unsigned chunks = (unsigned)((T + kGateChunk - 1) / kGateChunk);
+        k_dgate_partial<<<dim3(blocks_for((size_t)d, kBlock), chunks), kBlock, 0, st>>>(T, d, r, H, dg, dGpart);
+        k_dgate_reduce<<<blocks_for((size_t)r * d, kBlock), kBlock, 0, st>>>((int)chunks, d, r, dGpart, dG);
+    }
+    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+}
+
+// dY = dz U and dU (+)= dz^T Y for one chunk of head rows whose dz (and, if dU is wanted, dz^T) is in place.
+// Ut: U^T [d, Vp + 64]; Yt: scratch for the chunk's Y^T [d, Mcp + 64].
+static void bwd_chunk_products(const cp_head_desc &ds, const bf16_t *dZ, const bf16_t *dZt, long ldM, const bf16_t *Yc,
+                               int Mc, const bf16_t *Ut, bf16_t *Yt, bf16_t *dYc, float *dU, bool accumulate, hipStream_t st)
+{
+    const int d = ds.d, V = ds.V;
+    const int Vp = (int)round_up((size_t)V, 64), Mcp = (int)round_up((size_t)Mc, 64);
+    const long ldV = (long)Vp + 64;
+    // dY = dz U   (contraction over the vocabulary)
+    launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dYc, nullptr, (long)d, Mc, d}, st, kGroupRowsNarrow);
+    if (dU) {
+        // dU += dz^T Y   (contraction over the rows of the chunk)
+        transpose_bf16(Yc, d, Mc, d, Yt, ldM, Mcp, st);               // Yt[d, Mcp]
+        launch_gemm_nt<Cfg>("gemm_du", dZt, ldM, V, Yt, ldM, d, Mcp, EpiStoreF32{dU, (long)d, V, d, accumulate ? 1 : 0}, st,
+                            kGroupRowsNarrow);
+    }
+}
+
 // The backward pass below the logit gradients: per bounded chunk of head rows `dz_launch` writes dz
-// (bf16, row-major and, if asked, transposed), then dY = dz U and dU += dz^T Y; afterwards
+// (bf16, row-major and, if dU is wanted, transposed), then dY = dz U and dU += dz^T Y; afterwards
 // dW = dY^T H, dH = dY W + G^T dg and dG = dg^T H.  dg[T,r] must already hold the gate gradients.
 int fast_bwd_from_dz(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
                      const void *Yv, const float *dg, float *dH, float *dW, float *dU, float *dG, void *ws,
                      FastDzLaunch dz_launch, void *user, hipStream_t st)
 {
     const int d = ds.d, V = ds.V, r = ds.r, n = ds.n;
-    const size_t nrd = (size_t)n * r * d;
     const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
     const bf16_t *Y = (const bf16_t *)Yv;
     const BwdWs b = bwd_ws(ds);
     const size_t T = (size_t)ds.T, M = T * n * r;
-    bf16_t *Ut = at<bf16_t>(ws, b.Ut), *Wt = at<bf16_t>(ws, b.Wt), *Ht = at<bf16_t>(ws, b.Ht);
-    bf16_t *dY = at<bf16_t>(ws, b.dY), *dYt = at<bf16_t>(ws, b.dYt);
+    bf16_t *Ut = at<bf16_t>(ws, b.Ut), *Wt = at<bf16_t>(ws, b.Wt), *dY = at<bf16_t>(ws, b.dY);
     bf16_t *dZ = at<bf16_t>(ws, b.dZ), *dZt = at<bf16_t>(ws, b.dZt), *Yt = at<bf16_t>(ws, b.Yt);
-    const int Vp = (int)b.Vp, Tp = (int)b.Tp;
-    const long ldV = (long)b.ldV, ldT = (long)b.ldT, ldM = (long)b.ldM, ldN = (long)b.ldN;
+    const int Vp = (int)b.Vp;
 
-    transpose_bf16(U, d, V, d, Ut, ldV, Vp, st);                      // Ut[d, Vp]
+    transpose_bf16(U, d, V, d, Ut, (long)b.ldV, Vp, st);              // Ut[d, Vp]
     int first = 1;
     for (size_t m0 = 0; m0 < M; m0 += b.chunk) {
         const int Mc = (int)((M - m0 < b.chunk) ? M - m0 : b.chunk);
@@ -1292,35 +1393,11 @@ int fast_bwd_from_dz(const cp_head_desc &ds, const void *Hv, const void *Wv, con
         const bf16_t *Yc = Y + m0 * d;
         // recompute z for the chunk; the epilogue turns it into dz (bf16); the tiles over V also
         // cover the padding columns V..Vp-1, which the epilogue zero-fills
-        dz_launch(user, Yc, Mc, Mcp, m0, dZ, (long)Vp, dU ? dZt : nullptr, ldM, st);
-        // dY = dz U   (contraction over the vocabulary)
-        launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dY + m0 * d, nullptr, (long)d, Mc, d}, st,
-                            kGroupRowsNarrow);
-        if (dU) {
-            // dU += dz^T Y   (contraction over the rows of the chunk)
-            transpose_bf16(Yc, d, Mc, d, Yt, ldM, Mcp, st);           // Yt[d, Mcp]
-            launch_gemm_nt<Cfg>("gemm_du", dZt, ldM, V, Yt, ldM, d, Mcp, EpiStoreF32{dU, (long)d, V, d, first ? 0 : 1}, st,
-                                kGroupRowsNarrow);
-        }
+        dz_launch(user, Yc, Mc, Mcp, m0, dZ, (long)Vp, dU ? dZt : nullptr, (long)b.ldM, st);
+        bwd_chunk_products(ds, dZ, dZt, (long)b.ldM, Yc, Mc, Ut, Yt, dY + m0 * d, dU, !first, st);
         first = 0;
     }
-    // dH = dY W + G^T dg   (contraction over (s, a, k))
-    transpose_bf16(W, d, (int)nrd, d, Wt, ldN, (int)nrd, st);         // Wt[d, nrd]
-    launch_gemm_nt<Cfg>("gemm_dh", dY, (long)nrd, (int)T, Wt, ldN, d, (int)nrd, EpiStoreF32{dH, (long)d, (int)T, d, 0}, st, kGroupRowsNarrow);
-    k_add_gate_to_dh<<<blocks_for(T * d, kBlock), kBlock, 0, st>>>(T, d, r, G, dg, dH);
-    if (dW) {
-        // dW_sa = dY_sa^T H   (contraction over positions)
-        transpose_bf16(dY, (long)nrd, (int)T, (int)nrd, dYt, ldT, Tp, st);  // dYt[nrd, Tp]
-        transpose_bf16(H, d, (int)T, d, Ht, ldT, Tp, st);                   // Ht[d, Tp]
-        launch_gemm_nt<Cfg>("gemm_dw", dYt, ldT, (int)nrd, Ht, ldT, d, Tp, EpiStoreF32{dW, (long)d, (int)nrd, d, 0}, st, kGroupRowsNarrow);
-    }
-    if (dG) {
-        float *part = at<float>(ws, b.dGpart);
-        const unsigned chunks = (unsigned)((T + kGateChunk - 1) / kGateChunk);
-        k_dgate_partial<<<dim3(blocks_for((size_t)d, kBlock), chunks), kBlock, 0, st>>>(T, d, r, H, dg, part);
-        k_dgate_reduce<<<blocks_for((size_t)r * d, kBlock), kBlock, 0, st>>>((int)chunks, d, r, part, dG);
-    }
-    return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    return bwd_below_dy(ds, H, W, G, dY, dg, dH, dW, dG, Wt, at<float>(ws, b.dGpart), st);
 }
 
 bool fast_dims_fit(const cp_head_desc &ds) { return dims_fit(ds); }
@@ -1382,6 +1459,107 @@ int fast_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Wv, const 
     return fast_bwd_from_dz(ds, Hv, Wv, Uv, Gv, at<bf16_t>(ctx, cl.Y), dg, dH, dW, dU, dG, ws, loss_dz_launch, &args, st);
 }
 
+// ------------------------------------------------------------------------------------------
+// training step in one call: loss and gradients, one chunk of positions at a time
+// ------------------------------------------------------------------------------------------
+
+// Positions per chunk: whole positions whose head rows fit the backward pass's bound on logit-sized buffers.
+struct StepWs {
+    size_t logw, w, gamma, dg, dGpart, Ut, Wt, dY, C, lse, coef, Yc, Ylo, part, zs, dZ, dZt, Yt, total;
+    size_t Vp, pos, rows, ldM;
+    int parts;
+};
+inline StepWs step_ws(const cp_head_desc &ds)
+{
+    StepWs f;
+    const size_t T = (size_t)ds.T, nr = (size_t)ds.n * ds.r, M = T * nr, nrd = nr * ds.d;
+    f.Vp = round_up((size_t)ds.V, 64);
+    f.parts = ((ds.V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
+    f.pos = bwd_chunk_rows(ds) / nr;
+    if (f.pos < 1) f.pos = 1;
+    if (f.pos > T) f.pos = T ? T : 1;
+    f.rows = f.pos * nr;
+    f.ldM = round_up(f.rows, 64) + 64;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    f.logw = take(T * ds.r * 4);
+    f.w = take(T * ds.r * 4);
+    f.gamma = take(T * ds.r * 4);
+    f.dg = take(T * ds.r * 4);
+    f.dGpart = take(((T + kGateChunk - 1) / kGateChunk) * ds.r * ds.d * 4);
+    f.Ut = take((size_t)ds.d * (f.Vp + 64) * 2);
+    f.Wt = take((size_t)ds.d * (nrd + 64) * 2);
+    f.dY = take(M * ds.d * 2);
+    f.C = take(f.rows * 4);
+    f.lse = take(f.rows * 4);
+    f.coef = take(f.rows * 16);
+    f.Yc = take(f.rows * ds.d * 2);
+    f.Ylo = take(f.rows * ds.d * 2);
+    f.part = take(f.rows * f.parts * sizeof(float2));
+    f.zs = take(f.rows * f.Vp * 2);
+    f.dZ = take(f.rows * f.Vp * 2);
+    f.dZt = take((size_t)ds.V * f.ldM * 2);
+    f.Yt = take((size_t)ds.d * f.ldM * 2);
+    f.total = off;
+    return f;
+}
+size_t fast_step_workspace_bytes(const cp_head_desc &ds) { return step_ws(ds).total; }
+
+// Forward and backward interleaved per chunk of positions.  The logits of a chunk are kept as 16-bit floats (as
+// with CP_HEAD_KEEP_LOGITS, but for one chunk: the buffer does not grow with T) from the product that forms their
+// statistics to the pass that turns them into gradients a few launches later, so U y is multiplied once per step.
+int fast_loss_step(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
+                   const int32_t *X, const float *dloss, float scale, float *loss, float *dH, float *dW, float *dU,
+                   float *dG, void *ws, hipStream_t st)
+{
+    const int d = ds.d, V = ds.V, r = ds.r, n = ds.n;
+    const size_t nr = (size_t)n * r, nrd = nr * d, T = (size_t)ds.T;
+    if (T == 0) {
+        launch_fill_zero(dW, nrd * d, st);
+        launch_fill_zero(dU, (size_t)V * d, st);
+        launch_fill_zero(dG, (size_t)r * d, st);
+        return hipGetLastError() == hipSuccess ? CP_HEAD_OK : CP_HEAD_ERR_LAUNCH;
+    }
+    if (!dims_fit(ds) || kKeptTile != Cfg::WTN) return CP_HEAD_ERR_UNSUPPORTED;
+    const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
+    const StepWs f = step_ws(ds);
+    float *logw = at<float>(ws, f.logw), *w = at<float>(ws, f.w), *gamma = at<float>(ws, f.gamma), *dg = at<float>(ws, f.dg);
+    float *C = at<float>(ws, f.C), *lse = at<float>(ws, f.lse);
+    float4 *rowinfo = at<float4>(ws, f.coef);
+    bf16_t *dY = at<bf16_t>(ws, f.dY), *Yc = at<bf16_t>(ws, f.Yc), *Ylo = at<bf16_t>(ws, f.Ylo), *dZ = at<bf16_t>(ws, f.dZ);
+    float2 *part = at<float2>(ws, f.part);
+    uint16_t *zs = at<uint16_t>(ws, f.zs);
+    const int Vp = (int)f.Vp;
+
+    bf16_t *Ut = at<bf16_t>(ws, f.Ut), *dZt = at<bf16_t>(ws, f.dZt), *Yt = at<bf16_t>(ws, f.Yt);
+    launch_gate(ds, Hv, Gv, logw, w, st);                                                             // eq. 7, all positions
+    transpose_bf16(U, d, V, d, Ut, (long)f.Vp + 64, Vp, st);                                          // Ut[d, Vp]
+    int first = 1;
+    for (size_t t0 = 0; t0 < T; t0 += f.pos) {
+        const size_t P = (T - t0 < f.pos) ? T - t0 : f.pos;
+        const size_t m0 = t0 * nr;
+        const int Mc = (int)(P * nr), Mcp = (int)round_up((size_t)Mc, 64);
+        cp_head_desc sub = ds;
+        sub.T = (int64_t)P;
+        const int32_t *Xc = X + t0 * n;
+        // forward of the chunk: y, statistics of z with the logits kept, log-normalisers and C (eq. 5, 8), mixture (eq. 9)
+        launch_gemm_nt<Cfg>("gemm_y", H + t0 * d, d, (int)P, W, d, (int)nrd, d, EpiStoreBf16{Yc, Ylo, (long)nrd, (int)P, (int)nrd}, st,
+                            kGroupRowsNarrow);
+        launch_gemm_nt<Cfg>("gemm_z_stats_keep", Yc, d, Mc, U, d, V, d, EpiRowStatsKeep{part, f.parts, Mc, V, zs, (long)Vp, Vp}, st);
+        k_row_finish<<<blocks_for((size_t)Mc, kBlock / kWave), kBlock, 0, st>>>((size_t)Mc, d, r, f.parts, part, Yc, Ylo, U, Xc, lse, C);
+        launch_mixture(sub, logw + t0 * r, C, loss + t0, gamma + t0 * r, -1.f, st);
+        // backward of the chunk down to dY and dU
+        k_bwd_coefficients<<<blocks_for((size_t)Mc, kBlock), kBlock, 0, st>>>((size_t)Mc, n, r, w + t0 * r, gamma + t0 * r, lse,
+                                                                            dloss ? dloss + t0 : nullptr, scale, Xc, rowinfo,
+                                                                            dg + t0 * r);
+        launch_dz_from_kept(KeptLogits{zs, part, (long)Vp, f.parts}, 0, rowinfo, LossDzRule{}, Mc, Mcp, V, dZ, (long)Vp,
+                            dU ? dZt : nullptr, (long)f.ldM, st);
+        bwd_chunk_products(ds, dZ, dZt, (long)f.ldM, Yc, Mc, Ut, Yt, dY + m0 * d, dU, !first, st);
+        first = 0;
+    }
+    return bwd_below_dy(ds, H, W, G, dY, dg, dH, dW, dG, at<bf16_t>(ws, f.Wt), at<float>(ws, f.dGpart), st);
+}
+
 int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const void *Uv, const void *Gv,
                const float *uniforms, int32_t *alpha, int32_t *tokens, float *logq, void *ws, size_t,
                hipStream_t st)
@@ -1392,7 +1570,6 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
     const DraftWs f = draft_ws(ds);
     const int B = (int)ds.T, d = ds.d, V = ds.V, n = ds.n, r = ds.r;
     const size_t M = (size_t)B * n * r;
-    const int nrd = n * r * d;
     float *logw = at<float>(ws, f.logw), *lse = at<float>(ws, f.lse);
     bf16_t *Y = at<bf16_t>(ws, f.Y);
     float2 *part = at<float2>(ws, f.part);
@@ -1400,26 +1577,13 @@ int fast_draft(const cp_head_desc &ds, const void *Hv, const void *Wv, const voi
     double *base = at<double>(ws, f.base);
     const unsigned rows = (unsigned)(B * n);
 
-    {
-        ProfileScope prof("draft_gate_pick", (double)B * r * d * 2, st);
-        k_draft_gate_pick<<<(unsigned)B, kWideBlock, 0, st>>>(d, n, r, H, G, uniforms, logw, alpha);   // eq. 7, a* ~ w
-    }
-    // y = W_sa h, rounded to bf16 (part of the draft distribution's definition); streams W once
-    if (B <= CfgSkinny::BM)
-        launch_gemm_nt<CfgSkinny>("draft_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
-    else
-        launch_gemm_nt<Cfg>("draft_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
+    // y = W_sa h, rounded to bf16 (part of the draft distribution's definition); streams W once.  The gate and the
+    // expert draw (eq. 7, a* ~ w) ride along as the launch's first workgroups.
+    launch_y_with_gate("draft_gemm_y", ds, H, W, G, uniforms, Y, logw, alpha, n * r, st);
     // z = U y for all B*n*r rows with running statistics; streams U once, logits are not stored
     int parts, seg_cols;
-    if (M <= (size_t)CfgSkinny::BM) {
-        parts = ((V + CfgSkinny::BN - 1) / CfgSkinny::BN) * CfgSkinny::WN;
-        seg_cols = CfgSkinny::WTN;
-        launch_gemm_nt<CfgSkinny>("draft_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
-    } else {
-        parts = ((V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
-        seg_cols = Cfg::WTN;
-        launch_gemm_nt<Cfg>("draft_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
-    }
+    z_segments((int)M, V, parts, seg_cols);
+    launch_z_streamed("draft_gemm_z", Y, d, (int)M, U, V, EpiRowStats{part, parts, (int)M, V}, st);
     {
         ProfileScope prof("draft_lse_segment", (double)M * parts * 8, st);
         k_draft_lse_segment<<<rows, kWideBlock, 0, st>>>(n, r, parts, part, alpha, uniforms, lse, seg, base);
@@ -1444,21 +1608,14 @@ int fast_first_token(const cp_head_desc &ds, const void *Hv, const void *Wv, con
     const bf16_t *H = (const bf16_t *)Hv, *W = (const bf16_t *)Wv, *U = (const bf16_t *)Uv, *G = (const bf16_t *)Gv;
     const FirstTokenWs f = first_token_ws(ds);
     const int B = (int)ds.T, d = ds.d, V = ds.V, r = ds.r;
-    const int rows = B * r, rd = r * d, V4 = (int)f.V4;
+    const int rows = B * r, V4 = (int)f.V4;
     float *logw = at<float>(ws, f.logw), *z = at<float>(ws, f.z), *lse = at<float>(ws, f.lse);
     bf16_t *Y = at<bf16_t>(ws, f.Y);
-    k_draft_gate_pick<<<(unsigned)B, kWideBlock, 0, st>>>(d, ds.n, r, H, G, nullptr, logw, nullptr);      // eq. 7
-    // first head only: its matrices are the first r blocks of W, so y has rows (b, a)
-    if (B <= CfgSkinny::BM)
-        launch_gemm_nt<CfgSkinny>("first_gemm_y", H, d, B, W, d, rd, d, EpiStoreBf16{Y, nullptr, (long)rd, B, rd}, st);
-    else
-        launch_gemm_nt<Cfg>("first_gemm_y", H, d, B, W, d, rd, d, EpiStoreBf16{Y, nullptr, (long)rd, B, rd}, st);
+    // first head only: its matrices are the first r blocks of W, so y has rows (b, a); the gate (eq. 7) rides along
+    launch_y_with_gate("first_gemm_y", ds, H, W, G, nullptr, Y, logw, nullptr, r, st);
     // the r rows of logits per b are the output's own size: they are stored once (fp32), read once for
     // their log-normalisers and once for the mixture
-    if (rows <= CfgSkinny::BM)
-        launch_gemm_nt<CfgSkinny>("first_gemm_z", Y, d, rows, U, d, V, d, EpiStoreF32{z, (long)V4, rows, V4, 0}, st);
-    else
-        launch_gemm_nt<Cfg>("first_gemm_z", Y, d, rows, U, d, V, d, EpiStoreF32{z, (long)V4, rows, V4, 0}, st);
+    launch_z_streamed("first_gemm_z", Y, d, rows, U, V, EpiStoreF32{z, (long)V4, rows, V4, 0}, st);
     ProfileScope prof("first_mix", (double)rows * V * 8 + (double)B * V * 4, st);
     float2 *part = at<float2>(ws, f.part);
     k_row_stats_f32<<<dim3((unsigned)rows, (unsigned)f.parts), kBlock, 0, st>>>(V, (size_t)V4, f.parts, z, part);
@@ -1476,25 +1633,13 @@ int fast_draft_sequential(const cp_head_desc &ds, const void *Hv, const void *Wv
     const DraftWs f = draft_ws(ds);
     const int B = (int)ds.T, d = ds.d, V = ds.V, n = ds.n, r = ds.r;
     const size_t M = (size_t)B * n * r;
-    const int nrd = n * r * d;
     float *logw = at<float>(ws, f.logw);
     bf16_t *Y = at<bf16_t>(ws, f.Y);
     float2 *part = at<float2>(ws, f.part);
-    k_draft_gate_pick<<<(unsigned)B, kWideBlock, 0, st>>>(d, n, r, H, G, nullptr, logw, nullptr);          // eq. 7
-    if (B <= CfgSkinny::BM)
-        launch_gemm_nt<CfgSkinny>("seq_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
-    else
-        launch_gemm_nt<Cfg>("seq_gemm_y", H, d, B, W, d, nrd, d, EpiStoreBf16{Y, nullptr, (long)nrd, B, nrd}, st);
+    launch_y_with_gate("seq_gemm_y", ds, H, W, G, nullptr, Y, logw, nullptr, n * r, st);          // y and the gate (eq. 7)
     int parts, seg_cols;
-    if (M <= (size_t)CfgSkinny::BM) {
-        parts = ((V + CfgSkinny::BN - 1) / CfgSkinny::BN) * CfgSkinny::WN;
-        seg_cols = CfgSkinny::WTN;
-        launch_gemm_nt<CfgSkinny>("seq_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
-    } else {
-        parts = ((V + Cfg::BN - 1) / Cfg::BN) * Cfg::WN;
-        seg_cols = Cfg::WTN;
-        launch_gemm_nt<Cfg>("seq_gemm_z", Y, d, (int)M, U, d, V, d, EpiRowStats{part, parts, (int)M, V}, st);
-    }
+    z_segments((int)M, V, parts, seg_cols);
+    launch_z_streamed("seq_gemm_z", Y, d, (int)M, U, V, EpiRowStats{part, parts, (int)M, V}, st);
     ProfileScope prof("seq_draw", (double)B * n * r * seg_cols * d * 2, st);
     k_draft_sequential<<<(unsigned)B, kSeqBlock, 0, st>>>(d, V, n, r, parts, seg_cols, part, Y, U, logw, uniforms, tokens,
                                                           logq);                                             // eq. 11-13
@@ -1555,10 +1700,10 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Fv, c
     const float *lse = at<float>(ctx, cl.lse), *w = at<float>(ctx, cl.w), *gamma = at<float>(ctx, cl.gamma);
     float4 *rowinfo = at<float4>(ws, b.coef);
     float *dg = at<float>(ws, b.dg);
-    bf16_t *Ft = at<bf16_t>(ws, b.Ft), *Ht = at<bf16_t>(ws, b.Ht);
+    bf16_t *Ht = at<bf16_t>(ws, b.Ht);
     bf16_t *dZ = at<bf16_t>(ws, b.dZ), *dZt = at<bf16_t>(ws, b.dZt);
     const int Vp = (int)b.Vp, Tp = (int)b.Tp;
-    const long ldV = (long)b.ldV, ldT = (long)b.ldT, ldM = (long)b.ldM;
+    const long ldT = (long)b.ldT, ldM = (long)b.ldM;
 
     k_full_bwd_coefficients<<<blocks_for(M, kBlock), kBlock, 0, st>>>(T, n, r, w, gamma, lse, dloss, scale, X, rowinfo, dg);
     if (dF) transpose_bf16(H, d, (int)T, d, Ht, ldT, Tp, st);         // Ht[d, Tp]
@@ -1577,10 +1722,10 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Fv, c
                 launch_gemm_nt<Cfg>("full_gemm_z_dz", Hc, d, Tc, Fsa, d, V, d,
                                     EpiDz{dZ, (long)Vp, dF ? dZt : nullptr, ldM, rowinfo + (size_t)sa * T + t0, Tc, Tcp, V, Vp}, st);
             }
-            // dH += dz F_sa   (contraction over the vocabulary)
-            transpose_bf16(Fsa, d, V, d, Ft, ldV, Vp, st);            // Ft[d, Vp]
-            launch_gemm_nt<Cfg>("full_gemm_dh", dZ, Vp, Tc, Ft, ldV, d, Vp,
-                                EpiStoreF32{dH + t0 * d, (long)d, Tc, d, sa ? 1 : 0}, st, kGroupRowsNarrow);
+            // dH += dz F_sa   (contraction over the vocabulary; F_sa as it is stored is K-major for this product, and
+            // a transposed copy of every head matrix per chunk would cost more than the K-major loop does)
+            launch_gemm_nt<CfgNN>("full_gemm_dh", dZ, Vp, Tc, Fsa, d, d, Vp,
+                                  EpiStoreF32{dH + t0 * d, (long)d, Tc, d, sa ? 1 : 0}, st, kGroupRowsNarrow, NoSideJob{0}, -1, V);
             // dF_sa += dz^T H   (contraction over the positions of the chunk)
             if (dF)
                 launch_gemm_nt<Cfg>("full_gemm_df", dZt, ldM, V, Ht + t0, ldT, d, Tcp,

@@ -15,6 +15,14 @@
 // layout so that the 16-byte fragment reads of a wavefront are free of bank conflicts.
 //
 // K must be a multiple of 64; M and N are arbitrary.
+//
+// Either operand may instead be "K-major" (the contraction index is the slow one: A[K, lda] with the M output rows
+// along its columns, likewise B[K, ldb]): the products of the backward pass that contract over rows (dU = dz^T Y,
+// dW = dY^T H) or against a weight matrix stored the other way round (dY = dz U, dH = dY W) then need no
+// transposed copy of anything.  A K-major tile is 64 k-rows of 256 columns; it is laid out in LDS so that gfx950's
+// transposing LDS read (ds_read_b64_tr_b16: inside 16 lanes, 4 k-rows x 16 columns in, 4 k-values of one column
+// per lane out) delivers MFMA operand fragments directly.  With both operands K-major K is arbitrary (rows past
+// its end read as zero); otherwise K must still be a multiple of 64.
 #pragma once
 
 #include "cp_internal.hpp"
@@ -24,25 +32,42 @@ namespace cph {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
 struct GemmOperands {
     const bf16_t *A;   // [M, lda]
     const bf16_t *B;   // [N, ldb]
     long lda, ldb;     // elements
-    int M, N, K;       // K % 64 == 0
+    int M, N, K;       // K % 64 == 0 unless both operands are K-major
+    int ka_rows, kb_rows;   // K-major operands: rows that exist (<= K; the rest of K reads as zero)
     int tiles_m, tiles_n;
     int gm;            // tile rows per group of the workgroup -> tile walk
 };
 
-template <int BM_, int BN_, int WM_, int WN_>
+// LDS layout of a K-major tile (64 k-rows x 256 columns).  Four consecutive k-rows (a quad) are interleaved in
+// units of 32 bytes: the 16 columns [16 p, 16 p + 16) of the quad's rows t = 0..3 sit at p * 128 + t * 32, so the
+// 4 x 32 bytes that 16 lanes hand to one transposing read are one 128-byte span; quads are 2 KB apart and every
+// pair of quads is followed by 128 bytes of padding, which puts the quads of k-groups g and g + 1 (8 k-rows = two
+// quads apart) into the two halves of the 256-byte bank cycle: a wavefront's read is free of bank conflicts.
+// A direct global->LDS load instruction (64 lanes x 16 bytes = 1 KB, consecutive in LDS) fills half a quad: lane i
+// fetches 8 columns [16 (8 e + i / 8) + 8 (i % 2), +8) of k-row (i % 8) / 2, i.e. 256 contiguous bytes of each of
+// four rows; the four wavefronts of a pass fill two quads, and a pass advances by 4224 bytes.
+constexpr int kKmPassBytes = 2 * 2048 + 128;
+constexpr int kKmTileBytes = 8 * kKmPassBytes;
+
+template <int BM_, int BN_, int WM_, int WN_, bool AKM_ = false, bool BKM_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = 64;
+    static constexpr bool AKM = AKM_, BKM = BKM_;     // operand is K-major
     static constexpr int THREADS = WM * WN * kWave;
     static constexpr int WTM = BM / WM, WTN = BN / WN;       // wavefront sub-tile
     static constexpr int TM16 = WTM / 16, TN16 = WTN / 16;   // 16x16 MFMA blocks per wavefront
     static constexpr int ROWS_PER_PASS = THREADS / 8;        // a pass moves one 16-byte chunk per thread
     static constexpr int A_PASSES = BM / ROWS_PER_PASS, B_PASSES = BN / ROWS_PER_PASS;
-    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    static constexpr int A_BYTES = AKM_ ? kKmTileBytes : BM * BK * 2, B_BYTES = BKM_ ? kKmTileBytes : BN * BK * 2;
+    static_assert(!(AKM_ || BKM_) || WM_ * WN_ == 4, "K-major operands: four wavefronts");
+    static_assert((!AKM_ || BM_ == 256) && (!BKM_ || BN_ == 256), "a K-major tile has 256 columns");
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
     static_assert(BM % (WM * 64) == 0 && BN % (WN * 32) == 0, "wave tile must be a multiple of 64 rows x 32 columns");
@@ -53,6 +78,33 @@ struct TileCfg {
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+// The same descriptor as four scalar words, and a direct global->LDS load of 16 bytes per lane spelled out, for the
+// kernels with K-major operands.  Their fragments come from gfx950's transposing LDS read, and before every such
+// read the compiler waits for all outstanding loads once it knows that loads into LDS are in flight (it cannot tell
+// that they go to the other stage), which serialises the whole pipeline (measured: 3-5 times slower).  Loads
+// issued this way are invisible to that bookkeeping; the main loop's own explicit waits (before the barrier that
+// publishes a stage) are what orders them, exactly as for the other kernels.
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4_t make_rsrc_words(const void *base, unsigned bytes)
+{
+    const unsigned long long p = reinterpret_cast<unsigned long long>(base);
+    i32x4_t r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(p & 0xFFFFFFFFull));
+    r[1] = __builtin_amdgcn_readfirstlane((int)((p >> 32) & 0xFFFFull));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+// lds_addr: LDS byte address of the wavefront's 1 KB destination (uniform); voff: per-lane byte offset (range-checked
+// against the descriptor); soff: uniform byte offset (not range-checked)
+__device__ __forceinline__ void load_lds_16_spelled_out(i32x4_t rsrc, unsigned lds_addr, unsigned voff, int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
 }
 
 // Workgroup id -> output tile.  Consecutive workgroup ids go round-robin over the 8 XCDs, so the
@@ -118,48 +170,140 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
 
     const int m0 = tm * BM, n0 = tn * BN;
     const int rows_a = min(BM, g.M - m0), rows_b = min(BN, g.N - n0);
+    // K-contiguous operand: one descriptor over the tile's rows, the K-step is a scalar byte offset.
+    // K-major operand: a descriptor per K-step over its 64 k-rows from the tile's first column on (the whole
+    // operand may exceed the 4 GiB a descriptor can address); k-rows past the operand's end are out of range and
+    // read as zero, columns past M or N read whatever follows in the row and only reach accumulators that are
+    // never stored.
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A + (size_t)m0 * g.lda, (unsigned)((size_t)rows_a * g.lda * 2));
     const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.B + (size_t)n0 * g.ldb, (unsigned)((size_t)rows_b * g.ldb * 2));
+    // A K-major operand's descriptor is kept for the K-tile whose loads are being issued and moved on by one tile
+    // (64 k-rows) at a time: a 64-bit add on the base and a choice among three sizes (a full tile, the operand's
+    // last, partial one, nothing past its end).  Rebuilding it from the tile index cost a dozen scalar instructions
+    // in one place, four times per K-step, which held the matrix instructions up by several percent.
+    struct KmWalk {
+        i32x4_t d;          // descriptor of tile `tile`
+        int tile;
+        unsigned step;      // bytes from one K-tile to the next
+        int full_tiles;     // tiles with all 64 rows
+        unsigned full, tail;
+    };
+    auto km_start = [&](const bf16_t *base, long ld, int col0, int krows) {
+        KmWalk w;
+        w.tile = 0;
+        w.step = (unsigned)(BK * ld * 2);
+        w.full_tiles = krows / BK;
+        w.full = (unsigned)(((long)BK * ld - col0) * 2);
+        const int rest = krows % BK;
+        w.tail = rest > 0 ? (unsigned)(((long)rest * ld - col0) * 2) : 0u;
+        w.d = make_rsrc_words(base + col0, w.full_tiles > 0 ? w.full : w.tail);
+        return w;
+    };
+    auto km_advance = [&](KmWalk &w) {
+        const unsigned long long at = (((unsigned long long)(unsigned)w.d[1] << 32) | (unsigned)w.d[0]) + w.step;
+        ++w.tile;
+        w.d[0] = (int)(unsigned)at;
+        w.d[1] = (int)(unsigned)(at >> 32);
+        w.d[2] = (int)(w.tile < w.full_tiles ? w.full : (w.tile == w.full_tiles ? w.tail : 0u));
+    };
+    KmWalk walk_a = km_start(g.A, g.lda, m0, g.ka_rows), walk_b = km_start(g.B, g.ldb, n0, g.kb_rows);
+    constexpr bool kSpelledOut = Cfg::AKM || Cfg::BKM;
+    const i32x4_t wa = make_rsrc_words(g.A + (size_t)m0 * g.lda, (unsigned)((size_t)rows_a * g.lda * 2));
+    const i32x4_t wb = make_rsrc_words(g.B + (size_t)n0 * g.ldb, (unsigned)((size_t)rows_b * g.ldb * 2));
+    const unsigned lds_smem = __builtin_amdgcn_readfirstlane((unsigned)reinterpret_cast<unsigned long long>((lds_void *)smem));
 
     const int lrow = tid >> 3, pchunk = tid & 7;
     const int gchunk = pchunk ^ ((lrow >> 1) & 7);
-    const unsigned voff_a = (unsigned)lrow * (unsigned)g.lda * 2u + gchunk * 16u;
-    const unsigned voff_b = (unsigned)lrow * (unsigned)g.ldb * 2u + gchunk * 16u;
-    const unsigned pass_a = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.lda * 2u;
-    const unsigned pass_b = (unsigned)Cfg::ROWS_PER_PASS * (unsigned)g.ldb * 2u;
+    // K-major: k-row of the pass and first column that this thread fetches (see the layout above)
+    const int km_row = (wave >> 1) * 4 + ((lane & 7) >> 1);
+    const int km_col = ((wave & 1) * 8 + (lane >> 3)) * 16 + (lane & 1) * 8;
+    const unsigned voff_a = Cfg::AKM ? (unsigned)km_row * (unsigned)g.lda * 2u + km_col * 2u
+                                     : (unsigned)lrow * (unsigned)g.lda * 2u + gchunk * 16u;
+    const unsigned voff_b = Cfg::BKM ? (unsigned)km_row * (unsigned)g.ldb * 2u + km_col * 2u
+                                     : (unsigned)lrow * (unsigned)g.ldb * 2u + gchunk * 16u;
+    const unsigned pass_a = (unsigned)(Cfg::AKM ? 8 : Cfg::ROWS_PER_PASS) * (unsigned)g.lda * 2u;
+    const unsigned pass_b = (unsigned)(Cfg::BKM ? 8 : Cfg::ROWS_PER_PASS) * (unsigned)g.ldb * 2u;
+    constexpr int lds_pass_a = Cfg::AKM ? kKmPassBytes : Cfg::ROWS_PER_PASS * 128;
+    constexpr int lds_pass_b = Cfg::BKM ? kKmPassBytes : Cfg::ROWS_PER_PASS * 128;
     const int lds_wave = wave * 8 * 128;
 
     // fragment reads: lane l reads row l%16 of a 16-row block, 16-byte k-chunk 4*kb + l/16 of its 128-byte row
     const int frag_row = lane & 15, frag_q = lane >> 4, frag_sw = (lane >> 1) & 7;
-    const int lds_ra = (wm0 + frag_row) * 128;
-    const int lds_rb = Cfg::A_BYTES + (wn0 + frag_row) * 128;
+    // K-major fragments: lane (g, s) = (lane / 16, lane % 16) of a transposing read addresses 8 bytes of k-row
+    // s / 4 of a quad; k-group g is two quads (and one padding) further on; the 16-column block is a constant
+    const int km_lane = frag_q * (2 * 2048 + 128) + frag_row * 8;
+    const int lds_ra = Cfg::AKM ? km_lane + (wm0 / 16) * 128 : (wm0 + frag_row) * 128;
+    const int lds_rb = Cfg::A_BYTES + (Cfg::BKM ? km_lane + (wn0 / 16) * 128 : (wn0 + frag_row) * 128);
     int coff[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) coff[kb] = ((kb * 4 + frag_q) ^ frag_sw) << 4;
 
     bf16x8_t fa[2][HA], fb[2][TN];
 
+    // Everything that the descriptor's range check must see is in the vector offset (the scalar offset is added to
+    // the address but not checked): the pass for both layouts.  The K-step is the scalar offset of a K-contiguous
+    // operand and part of the descriptor's base for a K-major one.  Kernels with a K-major operand issue all their
+    // loads spelled out (see load_lds_16_spelled_out).
     auto load_one = [&](int kt, int stage, int q) {
         const int soff = kt * BK * 2;
         char *base = smem + stage * Cfg::STAGE_BYTES + lds_wave;
-        if (q < Cfg::A_PASSES)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void *)(base + q * Cfg::ROWS_PER_PASS * 128), 16,
-                                                     (int)(voff_a + q * pass_a), soff, 0, 0);
-        else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rb, (lds_void *)(base + Cfg::A_BYTES + (q - Cfg::A_PASSES) * Cfg::ROWS_PER_PASS * 128), 16,
-                (int)(voff_b + (q - Cfg::A_PASSES) * pass_b), soff, 0, 0);
+        const unsigned lbase = lds_smem + stage * Cfg::STAGE_BYTES + lds_wave;
+        if (q < Cfg::A_PASSES) {
+            if (Cfg::AKM)
+                load_lds_16_spelled_out(walk_a.d, lbase + q * lds_pass_a, voff_a + q * pass_a, 0);       // tile kt == walk_a.tile
+            else if (kSpelledOut)
+                load_lds_16_spelled_out(wa, lbase + q * lds_pass_a, voff_a + q * pass_a, soff);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void *)(base + q * lds_pass_a), 16,
+                                                         (int)(voff_a + q * pass_a), soff, 0, 0);
+        } else {
+            const int qb = q - Cfg::A_PASSES;
+            if (Cfg::BKM)
+                load_lds_16_spelled_out(walk_b.d, lbase + Cfg::A_BYTES + qb * lds_pass_b, voff_b + qb * pass_b, 0);
+            else if (kSpelledOut)
+                load_lds_16_spelled_out(wb, lbase + Cfg::A_BYTES + qb * lds_pass_b, voff_b + qb * pass_b, soff);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void *)(base + Cfg::A_BYTES + qb * lds_pass_b), 16,
+                                                         (int)(voff_b + qb * pass_b), soff, 0, 0);
+        }
+    };
+    // a fragment of a K-major tile: 16-column block `blk` of the wavefront, k-block kb: two transposing reads
+    // (k-rows 0..3 and 4..7 of the lane's group of 8)
+    auto read_km = [&](const char *st, int lane_base, int kb, int blk) {
+        const char *p = st + lane_base + kb * (4 * kKmPassBytes) + blk * 128;
+#if defined(__HIP_DEVICE_COMPILE__)
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p));
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 2048));
+#else   // the host pass only parses this function
+        const s16x4_t lo = *reinterpret_cast<const s16x4_t *>(p), hi = lo;
+#endif
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
     auto read_a = [&](const char *st, int kb, int buf, int half, int q) {
-        fa[buf][q] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + (half * HA + q) * 16 * 128 + coff[kb]);
+        if (Cfg::AKM) fa[buf][q] = read_km(st, lds_ra, kb, half * HA + q);
+        else fa[buf][q] = *reinterpret_cast<const bf16x8_t *>(st + lds_ra + (half * HA + q) * 16 * 128 + coff[kb]);
     };
     auto read_b = [&](const char *st, int kb, int buf, int q) {
-        fb[buf][q] = *reinterpret_cast<const bf16x8_t *>(st + lds_rb + q * 16 * 128 + coff[kb]);
+        if (Cfg::BKM) fb[buf][q] = read_km(st, lds_rb, kb, q);
+        else fb[buf][q] = *reinterpret_cast<const bf16x8_t *>(st + lds_rb + q * 16 * 128 + coff[kb]);
     };
     auto mfma_one = [&](int abuf, int bbuf, int half, int idx) {
         const int i = idx / TN, j = idx % TN;
-        acc[half * HA + i][j] =
-            __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[abuf][i], fb[bbuf][j], acc[half * HA + i][j], 0, 0, 0);
+        // With K-major operands (fragments assembled from two 64-bit reads) the register allocator no longer keeps
+        // the accumulators in place: it rotates them through copies between the two register files, several hundred
+        // per K-step.  Spelling the instruction out with the accumulator tied to itself in the accumulation
+        // registers and the fragments in vector registers gives the allocation the other kernels get by themselves.
+        // The compiler still inserts the waits for the fragments' LDS reads (it sees the operands); what it cannot see
+        // is that the instruction is a matrix instruction: uses of one accumulator are 64 instructions apart here, and
+        // the wait states before the accumulators are read back are added after the loop (without them the epilogue
+        // read accumulators that lacked the last K-block's contribution).
+        if (Cfg::AKM || Cfg::BKM)
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                         : "+a"(acc[half * HA + i][j])
+                         : "v"(fa[abuf][i]), "v"(fb[bbuf][j]));
+        else
+            acc[half * HA + i][j] =
+                __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[abuf][i], fb[bbuf][j], acc[half * HA + i][j], 0, 0, 0);
     };
     // the reads of the four phases, in the order the MFMAs that follow need them
     auto reads0 = [&](const char *st, const char *, int q) {       // A half 1 of k-block 0, then B first half of k-block 1
@@ -196,10 +340,12 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
 
     // No load is ever issued for a tile past the end of K: a late arrival would land in LDS while the
     // epilogue is using it.  The last two K-steps are therefore peeled off with their loads removed.
-    const int KT = g.K / BK;
+    const int KT = (g.K + BK - 1) / BK;
 #pragma unroll
     for (int q = 0; q < NLOAD; ++q) load_one(0, 0, q);
     if (KT > 1) {
+        if (Cfg::AKM) km_advance(walk_a);
+        if (Cfg::BKM) km_advance(walk_b);
 #pragma unroll
         for (int q = 0; q < NEARLY; ++q) load_one(1, 1, q);
         __builtin_amdgcn_s_waitcnt(0x0F70 | (NEARLY & 15) | ((NEARLY >> 4) << 14));   // vmcnt(NEARLY): tile 0 has landed
@@ -224,6 +370,10 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
         CPH_PHASE16(0, 1, 0, reads2, HA, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3 + L0 + L1, L2)          \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): tile kt+1 is complete in the other stage */ \
         __syncthreads();                                                                           \
+        if (LOAD_AFTER) { /* the loads from here on are tile kt+2's */                             \
+            if (Cfg::AKM) km_advance(walk_a);                                                      \
+            if (Cfg::BKM) km_advance(walk_b);                                                      \
+        }                                                                                          \
         CPH_PHASE16(1, 1, 1, reads3, TN + HA, LOAD_AFTER, (KT_) + 2, cur, 0, NEARLY)               \
     }
     int kt = 0;
@@ -233,6 +383,17 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
         ++kt;
     }
     CPH_K_STEP_DIRECT16(kt, false, false)
+    // The last matrix instructions above must have written their accumulators before anything reads them, and the
+    // compiler does not know that they are matrix instructions: wait out their latency here, and pass every
+    // accumulator through an (empty) volatile statement, which the compiler keeps behind that wait and ahead of
+    // every later use of the accumulator.
+    if (Cfg::AKM || Cfg::BKM) {
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
+    }
 #undef CPH_K_STEP_DIRECT16
 #undef CPH_PHASE16
 #undef CPH_PIN
@@ -247,12 +408,29 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
 // at its start and parks them in LDS.  (Loaded where they are used they are a chain of exposed cache misses per
 // tile while the matrix cores idle; requested before the main loop they cost the main loop 9 %: the registers
 // they occupy across it change its schedule.)
-template <class Cfg, class Epi>
-__global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi epi)
+// A side job rides along in the same launch: its `blocks` workgroups (a multiple of 8, so that the tile walk's
+// view of the XCDs stays aligned) come first in the grid, run `run(job, smem)` and leave; small work that the
+// launch does not depend on saves a launch of its own that way.
+struct NoSideJob {
+    static constexpr bool kActive = false;
+    int blocks;
+    __device__ void run(int, char *) const {}
+};
+template <class Cfg, class Epi, class Side>
+__global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi epi, Side side)
 {
     __shared__ __attribute__((aligned(16))) char smem[Cfg::LDS_BYTES];
+    int bid = blockIdx.x, nblocks = gridDim.x;
+    if (Side::kActive) {
+        if (bid < side.blocks) {
+            side.run(bid, smem);
+            return;
+        }
+        bid -= side.blocks;
+        nblocks -= side.blocks;
+    }
     int tm, tn;
-    if (!tile_of_block(blockIdx.x, gridDim.x, g.tiles_m, g.tiles_n, g.gm, tm, tn)) return;
+    if (!tile_of_block(bid, nblocks, g.tiles_m, g.tiles_n, g.gm, tm, tn)) return;
     f32x4_t acc[Cfg::TM16][Cfg::TN16];
     gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -261,17 +439,20 @@ __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi ep
     epi.template run<Cfg>(acc, row0, col0, lane, wave, tn, smem);
 }
 
-template <class Cfg, class Epi>
+template <class Cfg, class Epi, class Side = NoSideJob>
 inline void launch_gemm_nt(const char *name, const bf16_t *A, long lda, int M, const bf16_t *B, long ldb, int N, int K,
-                           const Epi &epi, hipStream_t st, int gm = kGroupRowsWide)
+                           const Epi &epi, hipStream_t st, int gm = kGroupRowsWide, const Side &side = Side{0},
+                           int ka_rows = -1, int kb_rows = -1)
 {
     ProfileScope prof(name, 2.0 * (double)M * (double)N * (double)K, st);
     GemmOperands g;
     g.A = A; g.B = B; g.lda = lda; g.ldb = ldb; g.M = M; g.N = N; g.K = K;
+    g.ka_rows = ka_rows < 0 ? K : ka_rows; g.kb_rows = kb_rows < 0 ? K : kb_rows;
     g.tiles_m = (M + Cfg::BM - 1) / Cfg::BM;
     g.tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
     g.gm = gm;
-    k_gemm_nt<Cfg, Epi><<<gemm_grid(g.tiles_m, g.tiles_n), Cfg::THREADS, 0, st>>>(g, epi);
+    const int extra = Side::kActive ? side.blocks : 0;
+    k_gemm_nt<Cfg, Epi, Side><<<gemm_grid(g.tiles_m, g.tiles_n) + extra, Cfg::THREADS, 0, st>>>(g, epi, side);
 }
 
 // Cross-lane steps of the row statistics, as data-parallel-primitive moves (no LDS traffic):

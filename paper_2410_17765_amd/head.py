@@ -94,6 +94,24 @@ class CpHead:
                                  out["dH"], out["dW"], out["dU"], out["dG"], ws)
         return {k: v for k, v in out.items() if v is not None}
 
+    def loss_fwd_bwd(self, H: torch.Tensor, X: torch.Tensor, dloss: Optional[torch.Tensor] = None, scale: float = 1.0,
+                     want_dU: bool = True):
+        """Loss and gradients in one call (the upstream gradient is an input): (loss[T], {dH, dW, dU, dG})."""
+        T = H.shape[0]
+        ds = self.desc(T)
+        ws = _scratch(binding.cp_head_workspace_bytes(ds, binding.OP_LOSS_FWD_BWD), self.device)
+        f32 = dict(dtype=torch.float32, device=self.device)
+        loss = torch.empty(T, **f32)
+        out = {
+            "dH": torch.empty((T, self.d), **f32),
+            "dW": torch.empty((self.n, self.r, self.d, self.d), **f32),
+            "dU": torch.empty((self.V, self.d), **f32) if want_dU else None,
+            "dG": torch.empty((self.r, self.d), **f32),
+        }
+        binding.cp_head_loss_fwd_bwd(ds, H, self.W, self.U, self.G, X, dloss, scale, loss,
+                                     out["dH"], out["dW"], out["dU"], out["dG"], ws)
+        return loss, {k: v for k, v in out.items() if v is not None}
+
     # ------------------------------------------------------------------ fine-tuning (distillation) loss
     def distill_loss_fwd(self, H: torch.Tensor, X: torch.Tensor, TZ: torch.Tensor, beta: float = 0.9,
                          discount: float = 1.0) -> torch.Tensor:

@@ -18,14 +18,19 @@ def gpu():
     return head
 
 
-def run_loss(head, cfg, inp, dloss=None, flags=0, want_dU=True):
+def run_loss(head, cfg, inp, dloss=None, flags=0, want_dU=True, single_call=False):
+    """Loss and gradients through cp_head_loss_fwd + cp_head_loss_bwd, or through cp_head_loss_fwd_bwd."""
     import torch
     h = head.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype, flags=flags)
     H = head.to_device(inp["H"], cfg.dtype)
     X = torch.from_numpy(inp["X"]).cuda()
-    loss = h.loss_fwd(H, X)
     dl = None if dloss is None else torch.from_numpy(dloss).cuda()
-    grads = {k: v.cpu().numpy() for k, v in h.loss_bwd(H, X, dl, want_dU=want_dU).items()}
+    if single_call:
+        loss, g = h.loss_fwd_bwd(H, X, dl, want_dU=want_dU)
+    else:
+        loss = h.loss_fwd(H, X)
+        g = h.loss_bwd(H, X, dl, want_dU=want_dU)
+    grads = {k: v.cpu().numpy() for k, v in g.items()}
     torch.cuda.synchronize()
     return loss.cpu().numpy(), grads
 
@@ -107,6 +112,56 @@ KEEP_LOGITS = 4      # CP_HEAD_KEEP_LOGITS: the backward pass reads the forward 
                          ids=lambda c: c.name if hasattr(c, "name") else str(c))
 def test_loss_and_gradients_with_kept_logits(gpu, oracle, cfg, flags):
     test_loss_and_gradients(gpu, oracle, cfg, flags)
+
+
+STEP_CASES = CASES + random_shapes()[:4] + [
+    (synth.HeadConfig("step_plain_fp32", T=70, d=50, V=333, n=3, r=4, dtype="fp32", targets="uniform"), 0),
+    (synth.HeadConfig("step_three_chunks", T=600, d=128, V=700, n=2, r=4), 2),
+]
+
+
+@pytest.mark.parametrize("cfg,flags", STEP_CASES, ids=lambda c: c.name if hasattr(c, "name") else str(c))
+def test_single_call_training_step(gpu, oracle, cfg, flags):
+    """cp_head_loss_fwd_bwd (forward and backward interleaved per chunk of positions, the chunk's logits kept as 16-bit
+    floats in between) against the oracle, to the bars of the two-call path, and against the two calls themselves."""
+    print(f"case {cfg} flags={flags}", flush=True)
+    inp = synth.make_inputs(cfg)
+    inp["X"][::7, 0] = -1
+    dloss = synth.upstream_grad(cfg.T)
+    loss, grads = run_loss(gpu, cfg, inp, dloss, flags=flags, single_call=True)
+    if cfg.name in _ORACLE_RESULTS or cfg.T * cfg.n * cfg.r * cfg.d * cfg.V < 3e9:
+        ref, gref = oracle_results(oracle, cfg, inp, dloss)
+        err = np.abs(loss - ref).max()
+        print(f"  loss max abs err {err:.3e}", flush=True)
+        assert err <= loss_atol_bf16(cfg)
+        for k, v in gref.items():
+            if k == "dG" and cfg.r == 1:
+                continue
+            e = rel_fro(grads[k], v)
+            print(f"  {k} rel fro {e:.3e}", flush=True)
+            assert e <= GRAD_REL_FRO, (k, e)
+    # the pair of calls with kept logits does the same arithmetic (other chunk boundaries: fp32 sums in another order)
+    loss2, grads2 = run_loss(gpu, cfg, inp, dloss, flags=flags | KEEP_LOGITS)
+    assert (loss.view(np.int32) == loss2.view(np.int32)).all()
+    for k in grads2:
+        assert rel_fro(grads[k], grads2[k]) <= 2e-5, k
+    # frozen unembedding
+    _, g3 = run_loss(gpu, cfg, inp, dloss, flags=flags, want_dU=False, single_call=True)
+    assert "dU" not in g3
+    for k in g3:
+        assert (g3[k].view(np.int32) == grads[k].view(np.int32)).all(), k
+
+
+def test_single_call_training_step_empty_batch(gpu):
+    import torch
+    cfg = synth.HeadConfig("step_empty", T=0, d=64, V=300, n=2, r=2)
+    inp = synth.make_inputs(cfg.with_(T=4))
+    h = gpu.CpHead(inp["W"], inp["U"], inp["G"], dtype=cfg.dtype)
+    H = gpu.to_device(inp["H"][:0], cfg.dtype)
+    X = torch.zeros((0, cfg.n), dtype=torch.int32, device="cuda")
+    loss, g = h.loss_fwd_bwd(H, X)
+    torch.cuda.synchronize()
+    assert loss.numel() == 0 and all(float(v.abs().max()) == 0.0 for k, v in g.items() if k != "dH")
 
 
 def test_kept_logits_change_nothing_in_the_forward_pass(gpu):
