@@ -27,13 +27,15 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3   # 256 compute units x 128 fp32 FMA lanes x 2 x
 # there report null.
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
-    ("head_7b", "gemm_z_stats_keep"): (212.209 + 32.555) * GIB,
-    ("head_7b", "gemm_z_stats"): (220.394 + 1.311) * GIB,
-    ("head_7b", "gemm_z_dz"): (25.780 + 7.812) * GIB,
+    # (workload, launch name, launches per step): L2 fills + writes per launch
+    ("head_7b", "gemm_z_stats_keep", 1): (217.249 + 32.527) * GIB,       # loss_head_7b_kept_logits_kernel_stats.md
+    ("head_7b", "gemm_z_stats_keep", 8): (26.574 + 4.065) * GIB,         # loss_head_7b_single_call_kernel_stats.md
+    ("head_7b", "gemm_z_stats", 1): (207.265 + 1.376) * GIB,             # loss_head_7b_kernel_stats.md
+    ("head_7b", "gemm_z_dz", 8): (25.864 + 7.812) * GIB,                 # loss_head_7b_kernel_stats.md
     # draft step: L2 fills of its kernels per step at B = 1, 8, 64 (profiles/draft_b8_kernel_stats.md)
-    ("draft", 1): 1.9856 * GIB,
-    ("draft", 8): (1.0006 + 1.0108 + 0.0020 + 0.0316 + 0.0022) * GIB,
-    ("draft", 64): 5.0565 * GIB,
+    ("draft", 1): 1.985 * GIB,
+    ("draft", 8): (1.0018 + 1.0106 + 0.0020 + 0.0316 + 0.0022) * GIB,
+    ("draft", 64): 5.014 * GIB,
 }
 
 
@@ -47,6 +49,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-positions", type=int, default=0, help="oracle sample size (0 = one position per thread for the loss, per two threads for the full heads)")
     ap.add_argument("--frozen-u", action="store_true", help="skip dU (frozen unembedding)")
+    ap.add_argument("--single-call", action="store_true",
+                    help="loss workloads: time cp_head_loss_fwd_bwd (forward and backward interleaved per chunk of "
+                         "positions, one chunk's logits kept as 16-bit floats in between) as the step; an extra mode "
+                         "of the default run")
     ap.add_argument("--keep-logits", action="store_true",
                     help="loss workloads: time the step with CP_HEAD_KEEP_LOGITS (the forward pass keeps the logits in "
                          "HBM as 16-bit floats, the backward pass reads them instead of multiplying U y again).  The "
@@ -294,7 +300,17 @@ def bench_loss(args):
     scale = 1.0 / cfg.T
     stream = torch.cuda.current_stream().cuda_stream
 
+    single = cfg.dtype == "bf16" and bool(args.single_call)
+    if single:
+        ws_step = binding.cp_head_workspace_bytes(ds_plain, binding.OP_LOSS_FWD_BWD)
+        if ws_step > ws.numel():
+            del ws
+            ws = torch.empty(ws_step, dtype=torch.uint8, device=dev)
+
     def step():
+        if single:
+            binding.cp_head_loss_fwd_bwd(ds_plain, H, h.W, h.U, h.G, X, None, scale, loss, dH, dW, dU, dG, ws, stream)
+            return
         binding.cp_head_loss_fwd(ds, H, h.W, h.U, h.G, X, loss, ctx, ws, stream)
         binding.cp_head_loss_bwd(ds, H, h.W, h.U, h.G, X, None, scale, ctx, dH, dW, dU, dG, ws, stream)
 
@@ -326,7 +342,8 @@ def bench_loss(args):
         dom = max(gemms, key=lambda k: k[2])
         achieved = dom[3] / (dom[2] * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": dom[0], "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get((cfg.name, dom[0])),
+                "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": TRAFFIC_BYTES.get((cfg.name, dom[0], dom[1] // max(args.steps, 1))),
                 "traffic_unit": "bytes per launch", "launches": dom[1], "avg_ms": dom[2] / dom[1]}
     else:
         # the plain fp32 path (fp32 storage or shapes off the matrix-core path: the small parity workloads): plain
@@ -342,7 +359,10 @@ def bench_loss(args):
         "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "V": cfg.V, "n": cfg.n, "r": cfg.r,
                    "frozen_u": bool(args.frozen_u), "token": "one position (n future tokens each)",
-                   "logits": "kept in HBM between forward and backward" if keep else "never stored (recomputed in the backward pass)",
+                   "logits": ("one chunk of positions at a time kept in HBM between its forward and backward halves" if single
+                              else "kept in HBM between forward and backward" if keep
+                              else "never stored (recomputed in the backward pass)"),
+                   "call": "cp_head_loss_fwd_bwd" if single else "cp_head_loss_fwd + cp_head_loss_bwd",
                    "ctx_gib": ctx_bytes / GIB},
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "predicted_tokens_per_s": value * cfg.n,      # every position predicts n tokens

@@ -251,3 +251,54 @@ def test_fine_tuning_loss_applies_the_plain_paths_limit_by_its_own_path_choice(l
     rc = lib.cp_head_distill_loss_fwd(ctypes.byref(wide), 256, 256, 256, 256, 256, 256, 0.5, 1.0, 256, 256, 256,
                                       1 << 40, None)
     assert rc == -2
+
+
+def _profile_rows(name):
+    """Rows of the markdown tables of one rocprofv3 summary under profiles/: {first cell: [other cells as float or str]}."""
+    rows = {}
+    for line in open(os.path.join(ROOT, "profiles", name)):
+        if not line.startswith("|") or line.startswith("|---"):
+            continue
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        vals = []
+        for c in cells[1:]:
+            try:
+                vals.append(float(c))
+            except ValueError:
+                vals.append(c)
+        rows.setdefault(cells[0], []).append(vals)
+    return rows
+
+
+def test_bench_traffic_constants_match_the_profile_summaries():
+    """bench.py reports `roofline.traffic` from constants copied out of the counter runs summarised under profiles/:
+    every constant must be what the table it names says (fetch + write GiB per dispatch)."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    gib = float(1 << 30)
+
+    def fetch_write(table, kernel, dispatches):
+        hit = [v for v in table[kernel] if len(v) == 3 and v[0] == dispatches]
+        assert len(hit) == 1, (kernel, dispatches, table.get(kernel))
+        return (hit[0][1] + hit[0][2]) * gib
+
+    head = _profile_rows("loss_head_7b_kernel_stats.md")
+    kept = _profile_rows("loss_head_7b_kept_logits_kernel_stats.md")
+    single = _profile_rows("loss_head_7b_single_call_kernel_stats.md")
+    want = {
+        ("head_7b", "gemm_z_stats", 1): fetch_write(head, "k_gemm_nt<256x256x64,EpiRowStats>", 1),
+        ("head_7b", "gemm_z_dz", 8): fetch_write(head, "k_gemm_nt<256x256x64,EpiDz>", 8),
+        ("head_7b", "gemm_z_stats_keep", 1): fetch_write(kept, "k_gemm_nt<256x256x64,EpiRowStatsKeep>", 1),
+        ("head_7b", "gemm_z_stats_keep", 8): fetch_write(single, "k_gemm_nt<256x256x64,EpiRowStatsKeep>", 8),
+    }
+    draft = _profile_rows("draft_b8_kernel_stats.md")
+    per_dispatch = [row[1] for k, v in draft.items() if k.startswith("k_")
+                    for row in v if len(row) == 2 and isinstance(row[1], float)
+                    and row[0] >= 1 and row[0] == int(row[0])]           # the table of fills at B = 8: dispatches, GiB
+    want[("draft", 8)] = sum(per_dispatch) * gib
+    step = [v for v in draft["step"] if len(v) == 2][0]
+    want[("draft", 1)], want[("draft", 64)] = step[0] * gib, step[1] * gib
+    assert set(want) == set(bench.TRAFFIC_BYTES), set(want) ^ set(bench.TRAFFIC_BYTES)
+    for key, value in want.items():
+        assert abs(bench.TRAFFIC_BYTES[key] - value) <= 2e-3 * value, (key, bench.TRAFFIC_BYTES[key] / gib, value / gib)
