@@ -186,8 +186,9 @@ struct FastFwdBuffers {
 };
 int fast_fwd_rows(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                   const int32_t *X, void *ctx, void *ws, FastFwdBuffers *out, hipStream_t st);
-// writes dz for rows m0 .. m0+Mc-1 of the chunk whose y is Yc: dZ[Mc, ldz] and, unless null, dZt[V, ldzt]
-typedef void (*FastDzLaunch)(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz,
+// writes dz for rows m0 .. m0+Mc-1 of the chunk whose y is Yc: dZ[Mc, ldz] (dz_blocked: stored in blocks of 256 rows x
+// 64 columns instead of row-major) and, unless null, dZt[V, ldzt]
+typedef void (*FastDzLaunch)(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bool dz_blocked,
                              bf16_t *dZt, long ldzt, hipStream_t st);
 int fast_bwd_from_dz(const cp_head_desc &ds, const void *H, const void *W, const void *U, const void *G,
                      const void *Y, const float *dg, float *dH, float *dW, float *dU, float *dG, void *ws,

@@ -291,6 +291,7 @@ struct EpiDzDistill {
     const float4 *grp;       // chunk-relative [Mc / R] {tlse, c3, target as int bits, -}
     const bf16_t *TZ;        // chunk-relative [Mc / R, V]; Mc / R * V < 2^31
     int Mc, Mcp, V, Vp;
+    int blocked;             // dZ is stored block by block (blocked64_index)
     template <class C>
     __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
@@ -319,11 +320,11 @@ struct EpiDzDistill {
         // 64 rows at a time: turn their logits into gradients and write them out at once, so that the
         // finished values do not stay in registers
         convert<C, RG, NG, 0>(acc, row0, col0, lane, winfo, wgrp);
-        store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+        store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz, blocked != 0);
         if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         if (C::WTM > 64) {
             convert<C, RG, NG, 1>(acc, row0, col0, lane, winfo, wgrp);
-            store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+            store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz, blocked != 0);
             if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         }
     }
@@ -600,13 +601,13 @@ struct DistillDzArgs {
     int d, V, r;
 };
 template <int R>
-void distill_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt,
-                       long ldzt, hipStream_t st)
+void distill_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bool dz_blocked,
+                       bf16_t *dZt, long ldzt, hipStream_t st)
 {
     const DistillDzArgs *a = static_cast<const DistillDzArgs *>(user);
     launch_gemm_nt<Cfg>("distill_gemm_z_dz", Yc, a->d, Mc, a->U, a->d, a->V, a->d,
                         EpiDzDistill<R>{dZ, ldz, dZt, ldzt, a->rowinfo + m0, a->grp + m0 / R, a->TZ + (m0 / R) * a->V, Mc, Mcp,
-                                        a->V, (int)ldz},
+                                        a->V, (int)ldz, dz_blocked ? 1 : 0},
                         st);
 }
 
@@ -627,12 +628,12 @@ struct DistillKeptArgs {
     int V;
 };
 template <int R>
-void distill_kept_dz_launch(void *user, const bf16_t *, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt,
-                            long ldzt, hipStream_t st)
+void distill_kept_dz_launch(void *user, const bf16_t *, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bool dz_blocked,
+                            bf16_t *dZt, long ldzt, hipStream_t st)
 {
     const DistillKeptArgs *a = static_cast<const DistillKeptArgs *>(user);
     launch_dz_from_kept(a->kept, m0, a->rowinfo + m0, DistillDzRule<R>{a->grp + m0 / R, a->TZ + (m0 / R) * a->V}, Mc, Mcp,
-                        a->V, dZ, ldz, dZt, ldzt, st);
+                        a->V, dZ, ldz, dz_blocked, dZt, ldzt, st);
 }
 
 int mfma_distill_fwd(const cp_head_desc &ds, const void *H, const void *W, const void *Uv, const void *G,

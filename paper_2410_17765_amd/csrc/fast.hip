@@ -21,6 +21,8 @@ typedef TileCfg<256, 256, 2, 2> Cfg;
 // the same tile with the second, or both, operands K-major (the contraction index is their slow one)
 typedef TileCfg<256, 256, 2, 2, false, true> CfgNN;
 typedef TileCfg<256, 256, 2, 2, true, true> CfgTN;
+// A stored in blocks of 256 rows x 64 columns (the chunk's logit gradients as the dY product reads them)
+typedef TileCfg<256, 256, 2, 2, false, false, true, false> CfgBlockedA;
 constexpr int kBlock = 256;
 
 
@@ -167,6 +169,7 @@ struct EpiDz {
     long ldzt;
     const float4 *rowinfo;   // chunk-relative: {lse, coef (zero for dropped factors), target as int bits, -}
     int Mc, Mcp, V, Vp;
+    int blocked;             // dZ is stored block by block (blocked64_index)
     template <class C>
     __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int, char *smem) const
     {
@@ -191,11 +194,11 @@ struct EpiDz {
         // 64 rows at a time: turn their logits into gradients in place and write them out at once, so that
         // the finished values do not stay in registers
         convert<C, 0>(acc, row0, col0, lane, winfo);
-        store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+        store_tile_bf16<C, decltype(dz), 0, 2>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz, blocked != 0);
         if (dZt) store_tile_bf16_transposed<C, decltype(dz), 0, 1>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         if (C::WTM > 64) {
             convert<C, 1>(acc, row0, col0, lane, winfo);
-            store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz);
+            store_tile_bf16<C, decltype(dz), 2, 4>(smem, wave, lane, row0, col0, Mc, Vp, dZ, ldz, dz, blocked != 0);
             if (dZt) store_tile_bf16_transposed<C, decltype(dz), 1, 2>(smem, wave, lane, row0, col0, Mcp, V, dZt, ldzt, dz);
         }
     }
@@ -1080,7 +1083,7 @@ inline BwdWs bwd_ws(const cp_head_desc &ds)
     b.Ut = take((size_t)ds.d * b.ldV * 2);
     b.Wt = take((size_t)ds.d * b.ldN * 2);
     b.dY = take(M * ds.d * 2);
-    b.dZ = take(b.chunk * b.Vp * 2);
+    b.dZ = take(round_up(b.chunk, 256) * b.Vp * 2);   // stored in blocks of 256 rows x 64 columns
     b.dZt = take((size_t)ds.V * b.ldM * 2);
     b.Yt = take((size_t)ds.d * b.ldM * 2);
     b.total = off;
@@ -1352,7 +1355,9 @@ static int bwd_below_dy(const cp_head_desc &ds, const bf16_t *H, const bf16_t *W
 }
 
 // dY = dz U and dU (+)= dz^T Y for one chunk of head rows whose dz (and, if dU is wanted, dz^T) is in place.
-// Ut: U^T [d, Vp + 64]; Yt: scratch for the chunk's Y^T [d, Mcp + 64].
+// dZ is stored block by block (blocked64_index, ld = Vp): its rows are 2 Vp bytes apart otherwise, a tile's K-step
+// touches 256 separate cache lines of it, and the product, which streams the chunk's 4 GiB of it from HBM, runs 4 %
+// slower.  Ut: U^T [d, Vp + 64]; Yt: scratch for the chunk's Y^T [d, Mcp + 64].
 static void bwd_chunk_products(const cp_head_desc &ds, const bf16_t *dZ, const bf16_t *dZt, long ldM, const bf16_t *Yc,
                                int Mc, const bf16_t *Ut, bf16_t *Yt, bf16_t *dYc, float *dU, bool accumulate, hipStream_t st)
 {
@@ -1360,7 +1365,8 @@ static void bwd_chunk_products(const cp_head_desc &ds, const bf16_t *dZ, const b
     const int Vp = (int)round_up((size_t)V, 64), Mcp = (int)round_up((size_t)Mc, 64);
     const long ldV = (long)Vp + 64;
     // dY = dz U   (contraction over the vocabulary)
-    launch_gemm_nt<Cfg>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dYc, nullptr, (long)d, Mc, d}, st, kGroupRowsNarrow);
+    launch_gemm_nt<CfgBlockedA>("gemm_dy", dZ, Vp, Mc, Ut, ldV, d, Vp, EpiStoreBf16{dYc, nullptr, (long)d, Mc, d}, st,
+                                kGroupRowsNarrow);
     if (dU) {
         // dU += dz^T Y   (contraction over the rows of the chunk)
         transpose_bf16(Yc, d, Mc, d, Yt, ldM, Mcp, st);               // Yt[d, Mcp]
@@ -1393,7 +1399,7 @@ int fast_bwd_from_dz(const cp_head_desc &ds, const void *Hv, const void *Wv, con
         const bf16_t *Yc = Y + m0 * d;
         // recompute z for the chunk; the epilogue turns it into dz (bf16); the tiles over V also
         // cover the padding columns V..Vp-1, which the epilogue zero-fills
-        dz_launch(user, Yc, Mc, Mcp, m0, dZ, (long)Vp, dU ? dZt : nullptr, (long)b.ldM, st);
+        dz_launch(user, Yc, Mc, Mcp, m0, dZ, (long)Vp, true, dU ? dZt : nullptr, (long)b.ldM, st);
         bwd_chunk_products(ds, dZ, dZt, (long)b.ldM, Yc, Mc, Ut, Yt, dY + m0 * d, dU, !first, st);
         first = 0;
     }
@@ -1409,12 +1415,12 @@ struct LossDzArgs {
     int d, V;
 };
 // dz of the training loss: dz[m, v] = coef[m] (exp(z - lse[m]) - 1[v = x_m])
-void loss_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt, long ldzt,
-                    hipStream_t st)
+void loss_dz_launch(void *user, const bf16_t *Yc, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bool dz_blocked,
+                    bf16_t *dZt, long ldzt, hipStream_t st)
 {
     const LossDzArgs *a = static_cast<const LossDzArgs *>(user);
     launch_gemm_nt<Cfg>("gemm_z_dz", Yc, a->d, Mc, a->U, a->d, a->V, a->d,
-                        EpiDz{dZ, ldz, dZt, ldzt, a->rowinfo + m0, Mc, Mcp, a->V, (int)ldz}, st);
+                        EpiDz{dZ, ldz, dZt, ldzt, a->rowinfo + m0, Mc, Mcp, a->V, (int)ldz, dz_blocked ? 1 : 0}, st);
 }
 
 struct KeptDzArgs {
@@ -1423,11 +1429,11 @@ struct KeptDzArgs {
     int V;
 };
 // the same dz from the logits kept by the forward pass
-void kept_dz_launch(void *user, const bf16_t *, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bf16_t *dZt, long ldzt,
-                    hipStream_t st)
+void kept_dz_launch(void *user, const bf16_t *, int Mc, int Mcp, size_t m0, bf16_t *dZ, long ldz, bool dz_blocked,
+                    bf16_t *dZt, long ldzt, hipStream_t st)
 {
     const KeptDzArgs *a = static_cast<const KeptDzArgs *>(user);
-    launch_dz_from_kept(a->kept, m0, a->rowinfo + m0, LossDzRule{}, Mc, Mcp, a->V, dZ, ldz, dZt, ldzt, st);
+    launch_dz_from_kept(a->kept, m0, a->rowinfo + m0, LossDzRule{}, Mc, Mcp, a->V, dZ, ldz, dz_blocked, dZt, ldzt, st);
 }
 }  // namespace
 
@@ -1497,7 +1503,7 @@ inline StepWs step_ws(const cp_head_desc &ds)
     f.Ylo = take(f.rows * ds.d * 2);
     f.part = take(f.rows * f.parts * sizeof(float2));
     f.zs = take(f.rows * f.Vp * 2);
-    f.dZ = take(f.rows * f.Vp * 2);
+    f.dZ = take(round_up(f.rows, 256) * f.Vp * 2);   // stored in blocks of 256 rows x 64 columns
     f.dZt = take((size_t)ds.V * f.ldM * 2);
     f.Yt = take((size_t)ds.d * f.ldM * 2);
     f.total = off;
@@ -1552,7 +1558,7 @@ int fast_loss_step(const cp_head_desc &ds, const void *Hv, const void *Wv, const
         k_bwd_coefficients<<<blocks_for((size_t)Mc, kBlock), kBlock, 0, st>>>((size_t)Mc, n, r, w + t0 * r, gamma + t0 * r, lse,
                                                                             dloss ? dloss + t0 : nullptr, scale, Xc, rowinfo,
                                                                             dg + t0 * r);
-        launch_dz_from_kept(KeptLogits{zs, part, (long)Vp, f.parts}, 0, rowinfo, LossDzRule{}, Mc, Mcp, V, dZ, (long)Vp,
+        launch_dz_from_kept(KeptLogits{zs, part, (long)Vp, f.parts}, 0, rowinfo, LossDzRule{}, Mc, Mcp, V, dZ, (long)Vp, true,
                             dU ? dZt : nullptr, (long)f.ldM, st);
         bwd_chunk_products(ds, dZ, dZt, (long)f.ldM, Yc, Mc, Ut, Yt, dY + m0 * d, dU, !first, st);
         first = 0;
@@ -1717,10 +1723,10 @@ int fast_full_loss_bwd(const cp_head_desc &ds, const void *Hv, const void *Fv, c
             // dz (bf16), also transposed, from the kept logits of these positions, or from z_sa recomputed
             if (cl.keep) {
                 KeptDzArgs kept{KeptLogits{at<uint16_t>(ctx, cl.zs), at<float2>(ctx, cl.zpart), (long)cl.Vp, cl.parts}, rowinfo, V};
-                kept_dz_launch(&kept, nullptr, Tc, Tcp, (size_t)sa * T + t0, dZ, (long)Vp, dF ? dZt : nullptr, ldM, st);
+                kept_dz_launch(&kept, nullptr, Tc, Tcp, (size_t)sa * T + t0, dZ, (long)Vp, false, dF ? dZt : nullptr, ldM, st);
             } else {
                 launch_gemm_nt<Cfg>("full_gemm_z_dz", Hc, d, Tc, Fsa, d, V, d,
-                                    EpiDz{dZ, (long)Vp, dF ? dZt : nullptr, ldM, rowinfo + (size_t)sa * T + t0, Tc, Tcp, V, Vp}, st);
+                                    EpiDz{dZ, (long)Vp, dF ? dZt : nullptr, ldM, rowinfo + (size_t)sa * T + t0, Tc, Tcp, V, Vp, 0}, st);
             }
             // dH += dz F_sa   (contraction over the vocabulary; F_sa as it is stored is K-major for this product, and
             // a transposed copy of every head matrix per chunk would cost more than the K-major loop does)

@@ -26,6 +26,7 @@
 #pragma once
 
 #include "cp_internal.hpp"
+#include "tile_walk.hpp"
 
 namespace cph {
 
@@ -56,10 +57,12 @@ struct GemmOperands {
 constexpr int kKmPassBytes = 2 * 2048 + 128;
 constexpr int kKmTileBytes = 8 * kKmPassBytes;
 
-template <int BM_, int BN_, int WM_, int WN_, bool AKM_ = false, bool BKM_ = false>
+template <int BM_, int BN_, int WM_, int WN_, bool AKM_ = false, bool BKM_ = false, bool ABL_ = false, bool BBL_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = 64;
     static constexpr bool AKM = AKM_, BKM = BKM_;     // operand is K-major
+    static constexpr bool ABL = ABL_, BBL = BBL_;     // operand is stored tile by tile: [rows/256][K/64][256][64]
+    static_assert(!(AKM_ && ABL_) && !(BKM_ && BBL_), "an operand is K-major or blocked, not both");
     static constexpr int THREADS = WM * WN * kWave;
     static constexpr int WTM = BM / WM, WTN = BN / WN;       // wavefront sub-tile
     static constexpr int TM16 = WTM / 16, TN16 = WTN / 16;   // 16x16 MFMA blocks per wavefront
@@ -107,29 +110,11 @@ __device__ __forceinline__ void load_lds_16_spelled_out(i32x4_t rsrc, unsigned l
                  : "memory");
 }
 
-// Workgroup id -> output tile.  Consecutive workgroup ids go round-robin over the 8 XCDs, so the
-// id is first unrolled into a per-XCD contiguous range; inside it tiles are walked in groups of GM
-// rows of tiles so that the tiles in flight on one XCD share operand panels in its L2.
-__device__ __forceinline__ bool tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int GM, int &tm, int &tn)
-{
-    const int per_xcd = nblocks >> 3;
-    const int lid = (bid & 7) * per_xcd + (bid >> 3);
-    if (lid >= tiles_m * tiles_n) return false;
-    const int per_group = GM * tiles_n;
-    const int group = lid / per_group;
-    const int first_m = group * GM;
-    const int gsize = min(tiles_m - first_m, GM);
-    const int in = lid - group * per_group;
-    tm = first_m + in % gsize;
-    tn = in / gsize;
-    return true;
-}
 // Tile rows per group of that walk.  8 x 4 tiles in flight per XCD suit the vocabulary-wide products (125 or
 // more tile columns; 16 rows per group cost them 10-25 %); the products with a d-wide output (16 tile columns)
 // and y = W h run 2-5 % faster with 4 x 8, which re-reads their large A operand half as often (1, 2 and 8 rows per
 // group cost dY 1.7-2.4 %, 2 and 8 cost dU 1.2-1.8 %).
 constexpr int kGroupRowsWide = 8, kGroupRowsNarrow = 4;
-inline int gemm_grid(int tiles_m, int tiles_n) { return (tiles_m * tiles_n + 7) / 8 * 8; }
 
 // The main loop, with direct global->LDS loads (no staging registers, no LDS write instructions) and
 // 16x16x32 MFMAs.  Each wavefront load instruction moves 64 x 16 bytes = 8 operand rows of 128 bytes into
@@ -161,6 +146,11 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     // 12/4 loses 3-5 %, 16/0 and any load in phases 1 or 2 (less time to land) lose 10-30 %.
     constexpr int L3 = NLOAD * 5 / 8, L0 = NLOAD - L3, L1 = 0, L2 = 0;
     constexpr int NEARLY = L3;
+    // The fragment reads of phase 2 are the last ones before the barrier, whose fence waits for every LDS read of the
+    // wavefront: spread over the whole phase, the last of them was issued one matrix instruction before that wait and
+    // the matrix pipe could run dry for an LDS latency per K-step.  They go into the first half of the phase (worth
+    // 0.2-0.4 % on the three large shapes).
+    constexpr int P2_SPAN = NM / 2;
     static_assert(BK == 64 && TM % 2 == 0 && TN % 2 == 0 && TN + HA <= NM && L2 >= 0, "schedule slots");
     typedef __attribute__((address_space(3))) void lds_void;
     const int tid = threadIdx.x;
@@ -176,8 +166,13 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     // operand may exceed the 4 GiB a descriptor can address); k-rows past the operand's end are out of range and
     // read as zero, columns past M or N read whatever follows in the row and only reach accumulators that are
     // never stored.
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A + (size_t)m0 * g.lda, (unsigned)((size_t)rows_a * g.lda * 2));
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.B + (size_t)n0 * g.ldb, (unsigned)((size_t)rows_b * g.ldb * 2));
+    // bytes between two rows of the tile: the leading dimension, or 128 for a blocked operand
+    const unsigned rsa = Cfg::ABL ? 128u : (unsigned)g.lda * 2u, rsb = Cfg::BBL ? 128u : (unsigned)g.ldb * 2u;
+    // (a blocked operand's descriptor spans the whole panel of its tile row: all 256 rows of every block exist)
+    const unsigned span_a = Cfg::ABL ? (unsigned)((size_t)BM * g.K * 2) : (unsigned)((size_t)rows_a * g.lda * 2);
+    const unsigned span_b = Cfg::BBL ? (unsigned)((size_t)BN * g.K * 2) : (unsigned)((size_t)rows_b * g.ldb * 2);
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A + (size_t)m0 * g.lda, span_a);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.B + (size_t)n0 * g.ldb, span_b);
     // A K-major operand's descriptor is kept for the K-tile whose loads are being issued and moved on by one tile
     // (64 k-rows) at a time: a 64-bit add on the base and a choice among three sizes (a full tile, the operand's
     // last, partial one, nothing past its end).  Rebuilding it from the tile index cost a dozen scalar instructions
@@ -209,8 +204,8 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     };
     KmWalk walk_a = km_start(g.A, g.lda, m0, g.ka_rows), walk_b = km_start(g.B, g.ldb, n0, g.kb_rows);
     constexpr bool kSpelledOut = Cfg::AKM || Cfg::BKM;
-    const i32x4_t wa = make_rsrc_words(g.A + (size_t)m0 * g.lda, (unsigned)((size_t)rows_a * g.lda * 2));
-    const i32x4_t wb = make_rsrc_words(g.B + (size_t)n0 * g.ldb, (unsigned)((size_t)rows_b * g.ldb * 2));
+    const i32x4_t wa = make_rsrc_words(g.A + (size_t)m0 * g.lda, span_a);
+    const i32x4_t wb = make_rsrc_words(g.B + (size_t)n0 * g.ldb, span_b);
     const unsigned lds_smem = __builtin_amdgcn_readfirstlane((unsigned)reinterpret_cast<unsigned long long>((lds_void *)smem));
 
     const int lrow = tid >> 3, pchunk = tid & 7;
@@ -219,11 +214,11 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     const int km_row = (wave >> 1) * 4 + ((lane & 7) >> 1);
     const int km_col = ((wave & 1) * 8 + (lane >> 3)) * 16 + (lane & 1) * 8;
     const unsigned voff_a = Cfg::AKM ? (unsigned)km_row * (unsigned)g.lda * 2u + km_col * 2u
-                                     : (unsigned)lrow * (unsigned)g.lda * 2u + gchunk * 16u;
+                                     : (unsigned)lrow * rsa + gchunk * 16u;
     const unsigned voff_b = Cfg::BKM ? (unsigned)km_row * (unsigned)g.ldb * 2u + km_col * 2u
-                                     : (unsigned)lrow * (unsigned)g.ldb * 2u + gchunk * 16u;
-    const unsigned pass_a = (unsigned)(Cfg::AKM ? 8 : Cfg::ROWS_PER_PASS) * (unsigned)g.lda * 2u;
-    const unsigned pass_b = (unsigned)(Cfg::BKM ? 8 : Cfg::ROWS_PER_PASS) * (unsigned)g.ldb * 2u;
+                                     : (unsigned)lrow * rsb + gchunk * 16u;
+    const unsigned pass_a = (unsigned)(Cfg::AKM ? 8 : Cfg::ROWS_PER_PASS) * rsa;
+    const unsigned pass_b = (unsigned)(Cfg::BKM ? 8 : Cfg::ROWS_PER_PASS) * rsb;
     constexpr int lds_pass_a = Cfg::AKM ? kKmPassBytes : Cfg::ROWS_PER_PASS * 128;
     constexpr int lds_pass_b = Cfg::BKM ? kKmPassBytes : Cfg::ROWS_PER_PASS * 128;
     const int lds_wave = wave * 8 * 128;
@@ -246,7 +241,8 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
     // operand and part of the descriptor's base for a K-major one.  Kernels with a K-major operand issue all their
     // loads spelled out (see load_lds_16_spelled_out).
     auto load_one = [&](int kt, int stage, int q) {
-        const int soff = kt * BK * 2;
+        // the K-step: 128 bytes along the row, or one block of BM (BN) rows x 128 bytes of a blocked operand
+        const int soff = q < Cfg::A_PASSES ? kt * (Cfg::ABL ? BM * 128 : BK * 2) : kt * (Cfg::BBL ? BN * 128 : BK * 2);
         char *base = smem + stage * Cfg::STAGE_BYTES + lds_wave;
         const unsigned lbase = lds_smem + stage * Cfg::STAGE_BYTES + lds_wave;
         if (q < Cfg::A_PASSES) {
@@ -320,7 +316,7 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
         else read_a(nx, 0, 0, 0, q - TN);
     };
 #define CPH_PIN() __builtin_amdgcn_sched_barrier(0)
-#define CPH_PHASE16(ABUF, BBUF, HALF, READS, NREAD, DO_LOAD, LOAD_KT, LOAD_STAGE, LOAD_Q0, LOAD_CNT) \
+#define CPH_PHASE16(ABUF, BBUF, HALF, READS, NREAD, READ_SPAN, DO_LOAD, LOAD_KT, LOAD_STAGE, LOAD_Q0, LOAD_CNT) \
     _Pragma("unroll") for (int m = 0; m < NM; ++m) {                                               \
         mfma_one(ABUF, BBUF, HALF, m);                                                             \
         CPH_PIN();                                                                                 \
@@ -329,7 +325,7 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
                 if ((q * NM) / ((LOAD_CNT) > 0 ? (LOAD_CNT) : 1) == m) { load_one(LOAD_KT, LOAD_STAGE, (LOAD_Q0) + q); CPH_PIN(); } \
         }                                                                                          \
         _Pragma("unroll") for (int q = 0; q < (NREAD); ++q)                                        \
-            if (((q + 1) * NM) / (NREAD) - 1 == m) { READS(st, nx, q); CPH_PIN(); }                \
+            if (((q + 1) * (READ_SPAN)) / (NREAD) - 1 == m) { READS(st, nx, q); CPH_PIN(); }       \
     }
 
 #pragma unroll
@@ -366,16 +362,16 @@ __device__ __forceinline__ void gemm_nt_mainloop_direct(const GemmOperands &g, i
         const int cur = (KT_) & 1;                                                                 \
         const char *st = smem + cur * Cfg::STAGE_BYTES;                                            \
         const char *nx = smem + (cur ^ 1) * Cfg::STAGE_BYTES;                                      \
-        CPH_PHASE16(0, 0, 0, reads0, HA + HB, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3, L0)               \
-        CPH_PHASE16(1, 0, 1, reads1, HB + HA, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3 + L0, L1)          \
-        CPH_PHASE16(0, 1, 0, reads2, HA, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3 + L0 + L1, L2)          \
+        CPH_PHASE16(0, 0, 0, reads0, HA + HB, NM, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3, L0)           \
+        CPH_PHASE16(1, 0, 1, reads1, HB + HA, NM, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3 + L0, L1)      \
+        CPH_PHASE16(0, 1, 0, reads2, HA, P2_SPAN, LOAD_NEXT, (KT_) + 1, cur ^ 1, L3 + L0 + L1, L2) \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): tile kt+1 is complete in the other stage */ \
         __syncthreads();                                                                           \
         if (LOAD_AFTER) { /* the loads from here on are tile kt+2's */                             \
             if (Cfg::AKM) km_advance(walk_a);                                                      \
             if (Cfg::BKM) km_advance(walk_b);                                                      \
         }                                                                                          \
-        CPH_PHASE16(1, 1, 1, reads3, TN + HA, LOAD_AFTER, (KT_) + 2, cur, 0, NEARLY)               \
+        CPH_PHASE16(1, 1, 1, reads3, TN + HA, NM, LOAD_AFTER, (KT_) + 2, cur, 0, NEARLY)           \
     }
     int kt = 0;
     for (; kt < KT - 2; ++kt) CPH_K_STEP_DIRECT16(kt, true, true)
@@ -421,17 +417,16 @@ template <class Cfg, class Epi, class Side>
 __global__ void __launch_bounds__(Cfg::THREADS) k_gemm_nt(GemmOperands g, Epi epi, Side side)
 {
     __shared__ __attribute__((aligned(16))) char smem[Cfg::LDS_BYTES];
-    int bid = blockIdx.x, nblocks = gridDim.x;
+    int bid = blockIdx.x;
     if (Side::kActive) {
         if (bid < side.blocks) {
             side.run(bid, smem);
             return;
         }
         bid -= side.blocks;
-        nblocks -= side.blocks;
     }
     int tm, tn;
-    if (!tile_of_block(bid, nblocks, g.tiles_m, g.tiles_n, g.gm, tm, tn)) return;
+    if (!tile_of_block(bid, g.tiles_m, g.tiles_n, g.gm, tm, tn)) return;
     f32x4_t acc[Cfg::TM16][Cfg::TN16];
     gemm_nt_mainloop_direct<Cfg>(g, tm, tn, smem, acc);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -453,7 +448,7 @@ inline void launch_gemm_nt(const char *name, const bf16_t *A, long lda, int M, c
     g.tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
     g.gm = gm;
     const int extra = Side::kActive ? side.blocks : 0;
-    k_gemm_nt<Cfg, Epi, Side><<<gemm_grid(g.tiles_m, g.tiles_n) + extra, Cfg::THREADS, 0, st>>>(g, epi, side);
+    k_gemm_nt<Cfg, Epi, Side><<<gemm_grid(g.tiles_m, g.tiles_n, g.gm) + extra, Cfg::THREADS, 0, st>>>(g, epi, side);
 }
 
 // Cross-lane steps of the row statistics, as data-parallel-primitive moves (no LDS traffic):
@@ -495,11 +490,12 @@ __device__ __forceinline__ float row16_sum(float v)
 __device__ __forceinline__ int acc_row(int i, int v, int lane) { return i * 16 + 4 * (lane >> 4) + v; }
 __device__ __forceinline__ int acc_col(int j, int lane) { return j * 16 + (lane & 15); }
 
-// P0, P1 restrict the call to the 32-row passes P0 .. P1-1 (default: all of them).
+// P0, P1 restrict the call to the 32-row passes P0 .. P1-1 (default: all of them).  blocked: dst is stored block by
+// block (blocked64_index) instead of row-major.
 template <class Cfg, class F, int P0 = 0, int P1 = Cfg::WTM / 32>
 __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, int row0, int col0, int row_limit,
                                                 int col_limit /* multiple of 8 */, bf16_t *__restrict__ dst, long ld,
-                                                F value)
+                                                F value, bool blocked = false)
 {
     constexpr int RS = Cfg::WTN * 2 + 16;              // padded row stride in bytes
     constexpr int CPR = Cfg::WTN / 8;                   // 16-byte chunks per row
@@ -508,8 +504,12 @@ __device__ __forceinline__ void store_tile_bf16(char *smem, int wave, int lane, 
     char *stage = smem + wave * (32 * RS);
     // a lane's first output address; every later one is a compile-time multiple of the (uniform) row stride away,
     // which keeps 64-bit multiplies per store out of the vector unit
-    bf16_t *out = dst + (size_t)(row0 + P0 * 32 + lane / CPR) * ld + (col0 + (lane % CPR) * 8);
-    const size_t step = (size_t)RPP * ld;
+    // (blocked: the rows of one call lie in one block of 256 and an 8-column piece in one block of 64 columns)
+    static_assert(Cfg::WTM <= 256 && 256 % Cfg::WTM == 0, "a wavefront's rows stay inside a block of 256");
+    const size_t first_row = (size_t)(row0 + P0 * 32 + lane / CPR);
+    const int first_col = col0 + (lane % CPR) * 8;
+    bf16_t *out = dst + (blocked ? blocked64_index(first_row, first_col, ld) : first_row * ld + first_col);
+    const size_t step = blocked ? (size_t)RPP * 64 : (size_t)RPP * ld;
     __syncthreads();                                    // every wavefront is done reading operand tiles
 #pragma unroll
     for (int p = P0; p < P1; ++p) {

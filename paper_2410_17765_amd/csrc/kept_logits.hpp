@@ -8,7 +8,8 @@
 // better; an overflow to -inf is the exact zero that the exponential of the true value rounds to as well.
 //
 // k_dz_from_kept turns a chunk of kept logits into logit gradients in bf16, row-major and (optionally)
-// transposed, which is what the dY and dU products of the backward pass read.  What the gradient is (training
+// transposed, which is what the dY and dU products of the backward pass read (the row-major copy optionally block by
+// block, the layout the dY product streams best).  What the gradient is (training
 // loss, fine-tuning loss) comes in as a rule.
 #pragma once
 #include "gemm_nt.hpp"
@@ -55,7 +56,7 @@ __device__ __forceinline__ void kept_log_probs(const KeptLogits &k, size_t m, in
 template <class Rule>
 __global__ void __launch_bounds__(kKeptBlock) k_dz_from_kept(KeptLogits kept, const float4 *__restrict__ rowinfo,
                                                              Rule rule, int Mc, int Mcp, int V, int Vp,
-                                                             bf16_t *__restrict__ dZ, long ldz,
+                                                             bf16_t *__restrict__ dZ, long ldz, int dz_blocked,
                                                              bf16_t *__restrict__ dZt, long ldzt, int tiles_c)
 {
     constexpr int RT = Rule::RT;
@@ -91,7 +92,8 @@ __global__ void __launch_bounds__(kKeptBlock) k_dz_from_kept(KeptLogits kept, co
                     u32x4_t out;
 #pragma unroll
                     for (int k = 0; k < 4; ++k) out[k] = f32x2_to_bf16x2(g[h][2 * k], g[h][2 * k + 1]);
-                    *reinterpret_cast<u32x4_t *>(dZ + (size_t)(row + h) * ldz + col) = out;
+                    const size_t at = dz_blocked ? blocked64_index((size_t)(row + h), col, ldz) : (size_t)(row + h) * ldz + col;
+                    *reinterpret_cast<u32x4_t *>(dZ + at) = out;
                 }
         }
         if (dZt) {
@@ -119,9 +121,10 @@ __global__ void __launch_bounds__(kKeptBlock) k_dz_from_kept(KeptLogits kept, co
 }
 
 // kept: all rows (not offset); the chunk is rows m0 .. m0 + Mc - 1; rowinfo chunk-relative.  ldz = Vp.
+// dz_blocked: dZ is written block by block (blocked64_index) instead of row-major.
 template <class Rule>
 inline void launch_dz_from_kept(const KeptLogits &kept, size_t m0, const float4 *rowinfo, const Rule &rule, int Mc, int Mcp,
-                                int V, bf16_t *dZ, long ldz, bf16_t *dZt, long ldzt, hipStream_t st)
+                                int V, bf16_t *dZ, long ldz, bool dz_blocked, bf16_t *dZt, long ldzt, hipStream_t st)
 {
     const int Vp = (int)ldz;
     const int tiles_c = (Vp + kKeptTile - 1) / kKeptTile;
@@ -129,8 +132,8 @@ inline void launch_dz_from_kept(const KeptLogits &kept, size_t m0, const float4 
     // algorithmic traffic: the logits read once, the gradients written once or twice
     ProfileScope scope("dz_from_kept", (double)Mc * Vp * 2.0 * (dZt ? 3.0 : 2.0), st);
     const KeptLogits chunk{kept.zs + m0 * kept.ld, kept.part + m0 * kept.parts, kept.ld, kept.parts};
-    k_dz_from_kept<Rule><<<(unsigned)(tiles_r * tiles_c), kKeptBlock, 0, st>>>(chunk, rowinfo, rule, Mc, Mcp, V, Vp, dZ, ldz, dZt,
-                                                                               ldzt, tiles_c);
+    k_dz_from_kept<Rule><<<(unsigned)(tiles_r * tiles_c), kKeptBlock, 0, st>>>(chunk, rowinfo, rule, Mc, Mcp, V, Vp, dZ, ldz,
+                                                                               dz_blocked ? 1 : 0, dZt, ldzt, tiles_c);
 }
 
 }  // namespace cph
