@@ -28,10 +28,10 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3   # 256 compute units x 128 fp32 FMA lanes x 2 x
 GIB = float(1 << 30)
 TRAFFIC_BYTES = {
     # (workload, launch name, launches per step): L2 fills + writes per launch
-    ("head_7b", "gemm_z_stats_keep", 1): (217.249 + 32.527) * GIB,       # loss_head_7b_kept_logits_kernel_stats.md
-    ("head_7b", "gemm_z_stats_keep", 8): (26.574 + 4.065) * GIB,         # loss_head_7b_single_call_kernel_stats.md
-    ("head_7b", "gemm_z_stats", 1): (207.265 + 1.376) * GIB,             # loss_head_7b_kernel_stats.md
-    ("head_7b", "gemm_z_dz", 8): (25.864 + 7.812) * GIB,                 # loss_head_7b_kernel_stats.md
+    ("head_7b", "gemm_z_stats_keep", 1): (203.536 + 32.510) * GIB,       # loss_head_7b_kept_logits_kernel_stats.md
+    ("head_7b", "gemm_z_stats_keep", 8): (26.849 + 4.066) * GIB,         # loss_head_7b_single_call_kernel_stats.md
+    ("head_7b", "gemm_z_stats", 1): (210.580 + 1.294) * GIB,             # loss_head_7b_kernel_stats.md
+    ("head_7b", "gemm_z_dz", 8): (25.455 + 7.813) * GIB,                 # loss_head_7b_kernel_stats.md
     # draft step: L2 fills of its kernels per step at B = 1, 8, 64 (profiles/draft_b8_kernel_stats.md)
     ("draft", 1): 1.985 * GIB,
     ("draft", 8): (1.0018 + 1.0106 + 0.0020 + 0.0316 + 0.0022) * GIB,
