@@ -42,6 +42,9 @@ CASES = [
     (synth.HeadConfig("mfma_chunked", T=200, d=64, V=515, n=2, r=4), 2),     # one tile of rows per chunk
     (synth.HeadConfig("mfma_one_position", T=1, d=64, V=300, n=1, r=1), 0),
     (synth.HeadConfig("mfma_wide_rank", T=40, d=64, V=260, n=2, r=33), 0),
+    # 68.75 tiles of head rows: whole bands of the workgroup -> tile walk (one of 64 tile rows for the vocabulary-wide
+    # products, two of 32 for the d-wide ones) and a ragged rest after them, in one launch
+    (synth.HeadConfig("mfma_bands_and_rest", T=1100, d=128, V=600, n=4, r=4), 0),
     # the limits of the interface: vocabulary below one tile and not a multiple of 8, maximal rank, maximal n
     (synth.HeadConfig("mfma_tiny_vocab", T=300, d=64, V=5, n=2, r=2, targets="uniform"), 0),
     (synth.HeadConfig("mfma_max_rank", T=9, d=64, V=70, n=1, r=64, targets="uniform"), 0),
