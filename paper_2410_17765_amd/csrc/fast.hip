@@ -66,6 +66,23 @@ struct EpiStoreF32 {
     }
 };
 
+// The logits of the columns past the vocabulary (only the last tile column has any) are set to -inf once, so that
+// the statistics below need no per-element test: -inf never wins a maximum and its exponential is zero (a row with no
+// valid column keeps the maximum -inf and the reference 0, as before).  Uniform for the wavefront.
+template <class C>
+__device__ __forceinline__ void mask_columns_past_vocabulary(f32x4_t (&acc)[C::TM16][C::TN16], int col0, int lane, int V)
+{
+    if (col0 + C::WTN <= V) return;
+#pragma unroll
+    for (int j = 0; j < C::TN16; ++j)
+        if (col0 + acc_col(j, lane) >= V) {
+#pragma unroll
+            for (int i = 0; i < C::TM16; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = -INFINITY;
+        }
+}
+
 // Running statistics of the logits (eq. 5 in log space): for every row of the wavefront's
 // sub-tile the maximum and the sum of exp(z - max) over its columns.  One (max, sum) pair per
 // row and per (tile column, wavefront column) goes to `part`; the logits themselves are dropped.
@@ -79,23 +96,19 @@ struct EpiRowStats {
     __device__ void run(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave, int tn, char *) const
     {
         const int slot = tn * C::WN + (wave % C::WN);
-        bool valid[C::TN16];
-#pragma unroll
-        for (int j = 0; j < C::TN16; ++j) valid[j] = col0 + acc_col(j, lane) < V;
+        mask_columns_past_vocabulary<C>(acc, col0, lane, V);
 #pragma unroll
         for (int i = 0; i < C::TM16; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 float mx = -INFINITY;
 #pragma unroll
-                for (int j = 0; j < C::TN16; ++j)
-                    if (valid[j]) mx = fmaxf(mx, acc[i][j][v]);
+                for (int j = 0; j < C::TN16; ++j) mx = fmaxf(mx, acc[i][j][v]);
                 mx = row16_max(mx);
                 const float ref = (mx == -INFINITY) ? 0.f : mx;
                 float s = 0.f;
 #pragma unroll
-                for (int j = 0; j < C::TN16; ++j)
-                    if (valid[j]) s += __expf(acc[i][j][v] - ref);
+                for (int j = 0; j < C::TN16; ++j) s += __expf(acc[i][j][v] - ref);
                 s = row16_sum(s);
                 const int r = row0 + acc_row(i, v, lane);
                 if ((lane & 15) == 0 && r < M)
@@ -117,7 +130,7 @@ struct EpiRowStatsKeep {
     int Vp;         // columns of zs that are written (V rounded up to 64; those from V on hold junk)
     template <class C, int P>
     __device__ __forceinline__ void pass(f32x4_t (&acc)[C::TM16][C::TN16], int row0, int col0, int lane, int wave,
-                                         int slot, const bool (&valid)[C::TN16], char *smem) const
+                                         int slot, char *smem) const
     {
 #pragma unroll
         for (int i = 2 * P; i < 2 * P + 2; ++i)
@@ -125,15 +138,14 @@ struct EpiRowStatsKeep {
             for (int v = 0; v < 4; ++v) {
                 float mx = -INFINITY;
 #pragma unroll
-                for (int j = 0; j < C::TN16; ++j)
-                    if (valid[j]) mx = fmaxf(mx, acc[i][j][v]);
+                for (int j = 0; j < C::TN16; ++j) mx = fmaxf(mx, acc[i][j][v]);
                 mx = row16_max(mx);
                 const float ref = (mx == -INFINITY) ? 0.f : mx;
                 float s = 0.f;
 #pragma unroll
                 for (int j = 0; j < C::TN16; ++j) {
                     acc[i][j][v] -= ref;
-                    if (valid[j]) s += __expf(acc[i][j][v]);
+                    s += __expf(acc[i][j][v]);
                 }
                 s = row16_sum(s);
                 const int r = row0 + acc_row(i, v, lane);
@@ -148,13 +160,11 @@ struct EpiRowStatsKeep {
     {
         static_assert(C::WTM == 128 && C::WTN == 128, "blocks of 128 columns, four passes of 32 rows");
         const int slot = tn * C::WN + (wave % C::WN);
-        bool valid[C::TN16];
-#pragma unroll
-        for (int j = 0; j < C::TN16; ++j) valid[j] = col0 + acc_col(j, lane) < V;
-        pass<C, 0>(acc, row0, col0, lane, wave, slot, valid, smem);
-        pass<C, 1>(acc, row0, col0, lane, wave, slot, valid, smem);
-        pass<C, 2>(acc, row0, col0, lane, wave, slot, valid, smem);
-        pass<C, 3>(acc, row0, col0, lane, wave, slot, valid, smem);
+        mask_columns_past_vocabulary<C>(acc, col0, lane, V);
+        pass<C, 0>(acc, row0, col0, lane, wave, slot, smem);
+        pass<C, 1>(acc, row0, col0, lane, wave, slot, smem);
+        pass<C, 2>(acc, row0, col0, lane, wave, slot, smem);
+        pass<C, 3>(acc, row0, col0, lane, wave, slot, smem);
     }
 };
 
